@@ -1,0 +1,382 @@
+"""Pins of the CPU oracle against things other than itself: closed forms, library routines,
+exact rational arithmetic, brute force on tiny inputs, invariants (no GPU needed)."""
+import itertools
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import esparse_oracle as orc
+
+RNG = np.random.default_rng(1234)
+
+
+def _f16(a):
+    return np.asarray(a, dtype=np.float64).astype(np.float16)
+
+
+# ---------------------------------------------------------------- entropy (eq. 1)
+def test_entropy_constant_channel_is_zero():
+    Xc = np.full((64, 3), 1.5, dtype=np.float16)
+    assert (orc.channel_entropy(Xc, 100) == 0.0).all()
+
+
+def test_entropy_uniform_over_bins_is_ln_bins():
+    # 10 samples at the centre of each of the 100 bins of [0, 100]
+    centres = np.arange(100) + 0.5
+    x = np.repeat(centres, 10)
+    x = np.concatenate([x, [0.0] * 0])            # min = 0.5, max = 99.5 -> still one per bin
+    RNG.shuffle(x)
+    IR = orc.channel_entropy(x[:, None].astype(np.float16), 100)
+    assert abs(IR[0] - math.log(100.0)) < 1e-12
+
+
+def test_entropy_two_point_is_ln2():
+    x = np.array([-3.0] * 50 + [7.0] * 50)
+    assert abs(orc.channel_entropy(_f16(x)[:, None], 100)[0] - math.log(2.0)) < 1e-15
+
+
+def test_entropy_matches_numpy_histogram_counts():
+    Xc = _f16(RNG.standard_normal((4096, 6)) * np.array([1, 5, 0.1, 30, 2, 1]))
+    counts = orc.channel_histogram(Xc, 100)
+    IR = orc.channel_entropy(Xc, 100)
+    for c in range(Xc.shape[1]):
+        x = Xc[:, c].astype(np.float64)
+        ref, _ = np.histogram(x, bins=100, range=(x.min(), x.max()))
+        assert (ref == counts[c]).all()
+        p = ref[ref > 0] / x.size
+        assert abs(IR[c] + (p * np.log(p)).sum()) < 1e-12
+    assert (IR > 0).all() and (IR <= math.log(100.0)).all()
+
+
+def test_entropy_scale_free_amplitude_scales():
+    Xc = _f16(RNG.standard_normal((512, 5)))
+    a1, a2 = orc.channel_amplitude(Xc), orc.channel_amplitude(_f16(Xc.astype(np.float64) * 2))
+    assert (orc.channel_entropy(Xc) == orc.channel_entropy(_f16(Xc.astype(np.float64) * 2))).all()
+    assert (a2 == 2 * a1).all()
+
+
+# ---------------------------------------------------------------- amplitude (eq. 2)
+def test_amplitude_exact_rational_and_linalg_norm():
+    Xc = _f16(RNG.standard_normal((1000, 4)) * np.array([1e-3, 1, 30, 200]))
+    AM = orc.channel_amplitude(Xc)
+    for c in range(4):
+        ints = [int(v) for v in (Xc[:, c].astype(np.float64) * 2.0 ** 24)]
+        S = sum(i * i for i in ints)                       # exact, in units of 2^-48
+        exact = math.sqrt(S / 2 ** 48)                     # int / int is correctly rounded
+        assert AM[c] == exact
+        assert abs(AM[c] - np.linalg.norm(Xc[:, c].astype(np.float64))) <= 4e-16 * AM[c]
+
+
+# ---------------------------------------------------------------- metric (eq. 3)
+def test_norm_only_alpha1_is_wanda_metric():
+    Xc = _f16(RNG.standard_normal((256, 8)))
+    W = _f16(RNG.standard_normal((5, 8)))
+    s = orc.channel_score(Xc, 1.0, use_entropy=False, use_norm=True)
+    assert (s == orc.channel_amplitude(Xc)).all()
+    wanda = np.abs(W.astype(np.float64)) * np.sqrt((Xc.astype(np.float64) ** 2).sum(axis=0))[None, :]
+    assert np.allclose(orc.metric(W, s), wanda, rtol=1e-14, atol=0)
+
+
+def test_score_combines_entropy_and_norm():
+    Xc = _f16(RNG.standard_normal((256, 8)))
+    s = orc.channel_score(Xc, 0.25)
+    assert (s == orc.channel_entropy(Xc) + 0.25 * orc.channel_amplitude(Xc)).all()
+    assert (orc.channel_score(Xc, 0.25, use_norm=False) == orc.channel_entropy(Xc)).all()
+
+
+# ---------------------------------------------------------------- n:m mask
+def _rank_count_mask(xi, n, m):
+    N, K = xi.shape
+    out = np.zeros((N, K), dtype=np.uint8)
+    for j in range(N):
+        for g in range(K // m):
+            for i in range(m):
+                v = xi[j, g * m + i]
+                ahead = sum(1 for k in range(m)
+                            if xi[j, g * m + k] > v or (xi[j, g * m + k] == v and k < i))
+                out[j, g * m + i] = 1 if ahead < n else 0
+    return out
+
+
+@pytest.mark.parametrize("n,m", [(2, 4), (4, 8)])
+def test_mask_is_brute_force_top_n_with_ties(n, m):
+    W = _f16(RNG.integers(-3, 4, size=(24, 32)) * 0.5)        # many ties and zeros
+    s = RNG.integers(1, 4, size=32).astype(np.float64)
+    theta = RNG.permutation(32)
+    for fn in (orc.nm_mask, orc.nm_mask_vectorised):
+        mk = fn(W, s, theta, n, m)
+        assert (mk.reshape(24, -1, m).sum(axis=2) == n).all()
+        assert (mk == _rank_count_mask(orc.metric(W, s)[:, theta], n, m)).all()
+
+
+def test_4_8_retains_at_least_2_4():
+    W = _f16(RNG.standard_normal((64, 64)))
+    s = np.abs(RNG.standard_normal(64)) + 0.1
+    theta = RNG.permutation(64)
+    assert orc.retained_metric(W, s, theta, 4, 8) >= orc.retained_metric(W, s, theta, 2, 4)
+
+
+def test_retained_metric_equals_masked_sum():
+    W = _f16(RNG.standard_normal((32, 32)))
+    s = np.abs(RNG.standard_normal(32)) + 0.1
+    theta = RNG.permutation(32)
+    mk = orc.nm_mask(W, s, theta, 2, 4)
+    xi = orc.metric(W, s)[:, theta]
+    assert abs(orc.retained_metric(W, s, theta, 2, 4) - (xi * mk).sum()) < 1e-9
+
+
+# ---------------------------------------------------------------- GNS
+def test_gns_bijection_rank_bands_and_exact_ranking():
+    N, K, m = 16, 48, 4
+    W = _f16(RNG.standard_normal((N, K)))
+    s = np.abs(RNG.standard_normal(K)) + 0.5
+    theta0 = orc.global_naive_shuffle(W, s, m)
+    assert sorted(theta0.tolist()) == list(range(K))
+    # exact-rational channel means of xi (mean over rows of |w| * s)
+    g_exact = [Fraction(float(s[c])) * sum(Fraction(float(abs(W[j, c]))) for j in range(N)) / N
+               for c in range(K)]
+    rank = sorted(range(K), key=lambda c: (-g_exact[c], c))
+    G = K // m
+    pos_of = {int(ch): p for p, ch in enumerate(theta0)}
+    for r, ch in enumerate(rank):
+        assert pos_of[ch] == (r % G) * m + r // G
+    # every group holds one channel of each band of G consecutive ranks
+    rank_of = {ch: r for r, ch in enumerate(rank)}
+    for g in range(G):
+        bands = sorted(rank_of[int(ch)] // G for ch in theta0[g * m:(g + 1) * m])
+        assert bands == list(range(m))
+
+
+def test_gns_tie_break_lower_channel_first():
+    W = np.ones((4, 8), dtype=np.float16)
+    s = np.ones(8)
+    theta0 = orc.global_naive_shuffle(W, s, 4)
+    # all means equal: rank = channel index, dealt round-robin into 2 groups
+    assert theta0.tolist() == [0, 2, 4, 6, 1, 3, 5, 7]
+
+
+# ---------------------------------------------------------------- LBS
+def _exact_retained(xi, theta, n, m):
+    x = xi[:, theta]
+    tot = Fraction(0)
+    for j in range(x.shape[0]):
+        for g in range(x.shape[1] // m):
+            vals = sorted((Fraction(float(v)) for v in x[j, g * m:(g + 1) * m]), reverse=True)
+            tot += sum(vals[:n])
+    return tot
+
+
+@pytest.mark.parametrize("n,m,B", [(2, 4, 16), (4, 8, 16)])
+def test_lbs_invariants_on_exact_data(n, m, B):
+    # small-integer data: every float64 sum in the oracle is exact, so the rational check is strict
+    N, K = 12, 32
+    W = _f16(RNG.integers(-8, 9, size=(N, K)))
+    s = RNG.integers(1, 5, size=K).astype(np.float64)
+    theta0 = orc.global_naive_shuffle(W, s, m)
+    theta, swaps = orc.local_block_shuffle(W, s, theta0, n, m, B)
+    assert sorted(theta.tolist()) == list(range(K))
+    xi = orc.metric(W, s)
+    for b in range(K // B):          # channels stay inside their block
+        assert sorted(theta[b * B:(b + 1) * B].tolist()) == sorted(theta0[b * B:(b + 1) * B].tolist())
+    r0, r1 = _exact_retained(xi, theta0, n, m), _exact_retained(xi, theta, n, m)
+    assert r1 >= r0 and (swaps.sum() == 0 or r1 > r0)
+    assert float(r1) == orc.retained_metric(W, s, theta, n, m)
+    # local optimum: no single cross-group exchange inside a block improves
+    for b in range(K // B):
+        for i, j in itertools.combinations(range(b * B, (b + 1) * B), 2):
+            if i // m == j // m:
+                continue
+            t2 = theta.copy()
+            t2[i], t2[j] = t2[j], t2[i]
+            assert _exact_retained(xi, t2, n, m) <= r1
+
+
+def test_lbs_first_step_takes_largest_improvement_and_is_monotone():
+    N, K, n, m, B = 10, 16, 2, 4, 16
+    W = _f16(RNG.integers(-8, 9, size=(N, K)))
+    s = RNG.integers(1, 5, size=K).astype(np.float64)
+    theta0 = np.arange(K)
+    xi = orc.metric(W, s)
+    prev = _exact_retained(xi, theta0, n, m)
+    theta = theta0.copy()
+    for step in range(1, 50):
+        t_next, sw = orc.local_block_shuffle(W, s, theta, n, m, B, max_swaps=1)
+        if sw.sum() == 0:
+            break
+        # the accepted exchange is the best single exchange, smallest (i, j) among equals
+        gains = {}
+        for i, j in itertools.combinations(range(K), 2):
+            if i // m != j // m:
+                t2 = theta.copy()
+                t2[i], t2[j] = t2[j], t2[i]
+                gains[(i, j)] = _exact_retained(xi, t2, n, m) - prev
+        best = max(gains.values())
+        assert best > 0
+        first = min(p for p, gval in gains.items() if gval == best)
+        changed = tuple(np.nonzero(t_next != theta)[0].tolist())
+        assert changed == first
+        cur = _exact_retained(xi, t_next, n, m)
+        assert cur - prev == best
+        prev, theta = cur, t_next
+    else:
+        raise AssertionError("did not terminate")
+
+
+def test_lbs_greedy_not_above_exhaustive_optimum_on_tiny_block():
+    N, K, n, m = 20, 8, 2, 4
+    W = _f16(RNG.integers(-8, 9, size=(N, K)))
+    s = RNG.integers(1, 5, size=K).astype(np.float64)
+    theta, _ = orc.local_block_shuffle(W, s, np.arange(K), n, m, 8)
+    xi = orc.metric(W, s)
+    opt = orc.brute_force_best_partition(xi, n, m)
+    got = orc.retained_metric(W, s, theta, n, m)
+    assert orc.retained_metric(W, s, np.arange(K), n, m) <= got <= opt
+
+
+@pytest.mark.parametrize("n,m", [(2, 4), (4, 8)])
+def test_vectorised_variants_equal_loop_versions(n, m):
+    N, K, B = 40, 32, 16
+    W = _f16(RNG.standard_normal((N, K)) / 6)
+    Xc = _f16(RNG.standard_normal((128, K)) * np.exp(RNG.standard_normal(K)))
+    s = orc.channel_score(Xc, 1 / math.sqrt(128))
+    theta0 = orc.global_naive_shuffle(W, s, m)
+    ta, sa = orc.local_block_shuffle(W, s, theta0, n, m, B)
+    tb, sb = orc.local_block_shuffle_vectorised(W, s, theta0, n, m, B)
+    assert (ta == tb).all() and (sa == sb).all() and sa.sum() > 0
+    mk = orc.nm_mask(W, s, ta, n, m)
+    assert (mk == orc.nm_mask_vectorised(W, s, ta, n, m)).all()
+    va, ma = orc.compress(W, ta, mk, n, m)
+    vb, mb = orc.compress_vectorised(W, ta, mk, n, m)
+    assert (va.view(np.uint16) == vb.view(np.uint16)).all() and (ma == mb).all()
+    xi_blk = orc.metric(W, s)[:, theta0[:B]]
+    assert orc._block_swap_search(xi_blk, n, m) == orc._block_swap_search_vectorised(xi_blk, n, m)
+
+
+# ---------------------------------------------------------------- compression (Section 4, step 1)
+@pytest.mark.parametrize("n,m", [(2, 4), (4, 8)])
+def test_compress_roundtrip_sizes_and_order(n, m):
+    N, K = 8, 64
+    W = _f16(RNG.standard_normal((N, K)))
+    s = np.abs(RNG.standard_normal(K)) + 0.1
+    theta = RNG.permutation(K)
+    mk = orc.nm_mask(W, s, theta, n, m)
+    values, meta = orc.compress(W, theta, mk, n, m)
+    vb, mb = orc.compressed_bytes(N, K, n, m)
+    assert values.nbytes == vb == N * K and meta.nbytes == mb == N * K // 8
+    assert (vb + mb) / (2 * N * K) == 0.5625                       # 56.25 % of dense 16-bit
+    dense_masked = W[:, theta] * mk
+    assert (orc.decompress(values, meta, K, n, m) == dense_masked).all()
+    if m == 4:
+        f = np.array([[(int(meta[j, q // 16]) >> (2 * (q % 16))) & 3 for q in range(K // 2)] for j in range(N)])
+        assert (f[:, 0::2] < f[:, 1::2]).all()                     # ascending inside each group
+
+
+def test_model_level_saving_in_table6_band():
+    path = os.path.join(os.path.dirname(__file__), "golden", "table6_memory.txt")
+    paper = {}
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, dense, sparse, pct = line.split()
+        paper[name] = (float(dense), float(sparse), float(pct))
+        assert abs(100 * (1 - float(sparse) / float(dense)) - float(pct)) < 0.06
+    arch = {"LLaMA-7B": (4096, 11008, 32), "LLaMA-13B": (5120, 13824, 40),
+            "LLaMA-30B": (6656, 17920, 60), "LLaMA-65B": (8192, 22016, 80)}
+    prev = 0.0
+    for name, (h, f, L) in arch.items():
+        lin = L * (4 * h * h + 3 * h * f)
+        rest = 2 * 32000 * h + (2 * L + 1) * h
+        vb, mb = orc.compressed_bytes(1, lin, 2, 4)
+        saving = 100 * (1 - (vb + mb + 2 * rest) / (2 * (lin + rest)))
+        assert abs(saving - paper[name][2]) < 0.7 and saving < 43.75
+        assert saving > prev                                       # larger model, larger saving
+        prev = saving
+
+
+# ---------------------------------------------------------------- native tiling vs the probed SMFMAC lane map
+def _emulated_smfmac_spmm(nv, nm, Xp, N, K):
+    """Y^T tiles computed the way v_smfmac_f32_16x16x64 consumes its operands (lane layout
+    measured on gfx950 with one-hot inputs): A lane l = (row l%16, ga = l//16) holds 8 kept values of
+    channels [16 ga, 16 ga + 16) of the 64-channel step, value e sits at channel
+    16 ga + 4 (e//2) + field e of the lane's 16 index bits."""
+    Np, Kp = -(-N // 16) * 16, -(-K // 256) * 256
+    M = Xp.shape[0]
+    Y = np.zeros((M, Np))
+    vals = nv.reshape(Np // 16, Kp // 64, 64, 8).astype(np.float64)
+    idx = nm.reshape(Np // 16, Kp // 256, 64, 4)
+    Xpad = np.zeros((M, Kp))
+    Xpad[:, :K] = Xp
+    for rt in range(Np // 16):
+        for ks in range(Kp // 64):
+            for lane in range(64):
+                r, ga = lane % 16, lane // 16
+                bits = int(idx[rt, ks // 4, lane, ks % 4])
+                for e in range(8):
+                    k = 64 * ks + 16 * ga + 4 * (e // 2) + ((bits >> (2 * e)) & 3)
+                    Y[:, 16 * rt + r] += vals[rt, ks, lane, e] * Xpad[:, k]
+    return Y[:, :N]
+
+
+def test_native_tiling_is_bijection_and_matches_instruction_layout():
+    N, K, M = 24, 320, 3                      # ragged: N not a multiple of 16, K not of 256
+    W = _f16(RNG.standard_normal((N, K)))
+    s = np.abs(RNG.standard_normal(K)) + 0.1
+    theta = RNG.permutation(K)
+    mk = orc.nm_mask(W, s, theta, 2, 4)
+    values, meta = orc.compress(W, theta, mk, 2, 4)
+    tags = (np.arange(values.size, dtype=np.uint16) + 1).view(np.float16).reshape(values.shape)
+    nv_t, _ = orc.native_tiling(tags, meta, N, K)
+    got = np.sort(nv_t.view(np.uint16)[nv_t.view(np.uint16) != 0])
+    assert (got == np.arange(1, values.size + 1)).all()             # each value exactly once
+    nv, nm = orc.native_tiling(values, meta, N, K)
+    assert nv.nbytes + nm.nbytes == 1.125 * 32 * 512
+    X = _f16(RNG.standard_normal((M, K)))
+    Y = _emulated_smfmac_spmm(nv, nm, X.astype(np.float64)[:, theta], N, K)
+    assert np.allclose(Y, orc.spmm_ref(X, W, theta, mk), rtol=1e-12, atol=1e-12)
+
+
+# ---------------------------------------------------------------- products
+def test_spmm_ref_definition_on_tiny_inputs():
+    N, K, M = 6, 16, 4
+    W = _f16(RNG.integers(-4, 5, size=(N, K)))
+    X = _f16(RNG.integers(-4, 5, size=(M, K)))
+    s = RNG.integers(1, 4, size=K).astype(np.float64)
+    theta = RNG.permutation(K)
+    mk = orc.nm_mask(W, s, theta, 2, 4)
+    Y = orc.spmm_ref(X, W, theta, mk)
+    for t in range(M):
+        for j in range(N):
+            acc = 0
+            for p in range(K):
+                if mk[j, p]:
+                    acc += int(X[t, theta[p]]) * int(W[j, theta[p]])
+            assert Y[t, j] == acc
+    # all-ones X -> row sums of the kept weights
+    ones = np.ones((1, K), dtype=np.float16)
+    kept_sum = (W[:, theta].astype(np.float64) * mk).sum(axis=1)
+    assert (orc.spmm_ref(ones, W, theta, mk)[0] == kept_sum).all()
+    # one-hot X reads back single weights through theta
+    eye = np.eye(K, dtype=np.float16)
+    back = orc.spmm_ref(eye, W, theta, mk)                        # [K, N]: row c = W_masked[:, c]
+    values, meta = orc.compress(W, theta, mk, 2, 4)
+    dec = orc.decompress(values, meta, K, 2, 4)                  # re-ordered order
+    assert (back[theta, :] == dec.T.astype(np.float64)).all()
+    # relabelling channels consistently changes nothing
+    sigma = RNG.permutation(K)
+    inv = np.argsort(sigma)
+    Y2 = orc.spmm_ref(X[:, sigma], W[:, sigma], inv[theta], mk)
+    assert (Y2 == Y).all()
+    assert (orc.dense_ref(X, W) == X.astype(np.float64) @ W.astype(np.float64).T).all()
+
+
+def test_rowwise_error_and_output_error():
+    Yref = np.array([[3.0, 4.0], [1.0, 0.0]])
+    Y = np.array([[3.0, 4.5], [1.0, 0.0]])
+    assert np.allclose(orc.rowwise_rel_error(Y, Yref), [0.1, 0.0])
+    W = _f16(RNG.standard_normal((8, 16)))
+    X = _f16(RNG.standard_normal((5, 16)))
+    full = np.ones((8, 16), dtype=np.uint8)
+    assert orc.output_error(X, W, np.arange(16), full) == 0.0
