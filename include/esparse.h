@@ -1,0 +1,167 @@
+/*
+ * esparse.h - C ABI of the MI355X (gfx950) implementation of the E-Sparse hot path
+ * (E-Sparse: entropy-based N:M sparsity for LLMs, arXiv 2310.15929).
+ *
+ * Three offline / online stages of one linear layer  Y[M,N] = X[M,K] . W[N,K]^T :
+ *   esparse_prune     calibration features + weights -> channel permutation + n:m mask
+ *                     (Section 3.2 eq. 1-3, Section 3.3, Algorithm 1)
+ *   esparse_compress  masked weights -> kept values + 2-bit in-group indices (Section 4, step 1)
+ *   esparse_spmm      activations x compressed weights -> output, on sparse MFMA (Section 4)
+ * plus the dense GEMM of the same shapes (the "Dense GEMM" column of Table 5), the per-shape
+ * choice of the fastest kernel variant (Section 4, step 2) and size queries.
+ *
+ * Conventions
+ *   - Notation: n:m = keep n_keep of every m_group consecutive RE-ORDERED input channels of each
+ *     output row.  theta ("perm") is a gather permutation: re-ordered position p holds original
+ *     channel perm[p]; W' = W[:, perm], X' = X[:, perm].
+ *   - Unless a parameter is marked HOST, every data pointer is a DEVICE pointer owned by the
+ *     caller, row-major, contiguous and 16-byte aligned.  The library never frees or keeps them.
+ *   - All GPU work is enqueued on the context's stream.  esparse_spmm, esparse_dense_gemm,
+ *     esparse_dense_pack and esparse_gather_activations do not synchronise; esparse_prune,
+ *     esparse_compress, esparse_channel_stats and esparse_tune do (they return host results).
+ *   - Every function returns an esparse_status (0 = ok, negative = error) and never throws.
+ *     Arguments are validated before the first GPU call; on an argument error nothing is
+ *     launched and outputs are untouched.  esparse_last_error gives a message.
+ *   - Calibration features and activations must be finite.
+ */
+#ifndef ESPARSE_H
+#define ESPARSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct esparse_ctx esparse_ctx; /* opaque: device, stream, scratch, last error */
+
+typedef enum { ESPARSE_F16 = 0, ESPARSE_BF16 = 1 } esparse_dtype;
+
+typedef enum {
+  ESPARSE_OK = 0,
+  ESPARSE_EINVAL = -1,       /* null pointer, bad size, misaligned pointer                     */
+  ESPARSE_EUNSUPPORTED = -2, /* pattern / dtype / size the library has no kernel for            */
+  ESPARSE_ENOMEM = -3,       /* internal scratch allocation failed                              */
+  ESPARSE_EHIP = -4,         /* a HIP call failed (message has the HIP error string)            */
+  ESPARSE_EBADMASK = -5,     /* a group of the mask does not keep exactly n_keep                */
+  ESPARSE_EBADPERM = -6,     /* perm is not a bijection on [0, K)                               */
+  ESPARSE_EWORKSPACE = -7    /* caller workspace smaller than esparse_spmm_workspace reports    */
+} esparse_status;
+
+/* Switches of esparse_prune_opts.flags: the four rows of the ablation of Table 4. */
+#define ESPARSE_USE_ENTROPY 1u /* IR_c term of eq. 3            */
+#define ESPARSE_USE_NORM 2u    /* alpha * AM_c term of eq. 3    */
+#define ESPARSE_USE_GNS 4u     /* global naive shuffle          */
+#define ESPARSE_USE_LBS 8u     /* local block shuffle           */
+#define ESPARSE_USE_ALL 15u
+
+typedef struct {
+  int n_keep, m_group;  /* 2:4 or 4:8                                                          */
+  int block;            /* local-block-shuffle block size in channels (paper default 256);     */
+                        /* multiple of m_group, divides K, <= 256                              */
+  int bins;             /* histogram bins of eq. 1 (paper: 100); 1..256                        */
+  double alpha;         /* weight of the norm term in eq. 3 (the paper prints no value)        */
+  unsigned flags;       /* ESPARSE_USE_*                                                       */
+  long long max_swaps;  /* cap on exchanges per block; 0 = until none improves (Algorithm 1)   */
+} esparse_prune_opts;
+
+/* ---- context -------------------------------------------------------------------------------
+ * esparse_create binds a context to HIP device `device` and to `hip_stream` (a hipStream_t passed
+ * as void*, NULL = the default stream).  Contexts are not thread-safe; use one per thread. */
+int esparse_create(esparse_ctx** out, int device, void* hip_stream);
+void esparse_destroy(esparse_ctx* ctx);
+int esparse_set_stream(esparse_ctx* ctx, void* hip_stream);
+const char* esparse_last_error(const esparse_ctx* ctx); /* HOST string owned by the context */
+const char* esparse_version(void);
+
+/* ---- Section 3.2, eq. 1-2: per-channel statistics of the calibration features ---------------
+ * calib[T,K] (dtype) -> entropy IR_c over `bins` equal-width bins spanning the channel's own
+ * [min, max] (natural log, top edge closed), amplitude AM_c = ||X_c||_2 (sum of squares exact,
+ * rounded once).  ir_out / am_out: HOST double[K], either may be NULL.  Synchronises. */
+int esparse_channel_stats(esparse_ctx* ctx, const void* calib, long long T, long long K,
+                          esparse_dtype dtype, int bins, double* ir_out, double* am_out);
+
+/* ---- Section 3.2 eq. 3 + Section 3.3 + Algorithm 1: metric, channel shuffle, n:m mask -------
+ * calib[T,K], W[N,K] (dtype) -> perm_out[K] int32 (DEVICE), mask_out[N,K] uint8 (DEVICE, one byte
+ * per weight, 1 = kept, in RE-ORDERED channel order).  Optional HOST outputs (NULL to skip):
+ * score_out double[K] (s_c = IR_c + alpha AM_c), swaps_out int64[K/block] (exchanges made per
+ * block), retained_out double[1] (objective of eq. 5: total metric kept).
+ * Ties: equal metric -> lower position kept; equal channel means -> lower channel first; equal
+ * improvements -> smallest (i, j).  Synchronises and allocates internal scratch. */
+int esparse_prune(esparse_ctx* ctx, const void* calib, long long T, const void* W, long long N,
+                  long long K, esparse_dtype dtype, const esparse_prune_opts* opts,
+                  int32_t* perm_out, uint8_t* mask_out, double* score_out, int64_t* swaps_out,
+                  double* retained_out);
+
+/* Same as esparse_prune from the shuffle on, with the channel scores s_c given (HOST double[K]). */
+int esparse_prune_with_scores(esparse_ctx* ctx, const double* score, const void* W, long long N,
+                              long long K, esparse_dtype dtype, const esparse_prune_opts* opts,
+                              int32_t* perm_out, uint8_t* mask_out, int64_t* swaps_out,
+                              double* retained_out);
+
+/* ---- Section 4, step 1: compressed format ---------------------------------------------------
+ * Sizes (closed form; 2 bits of index per kept value -> 56.25 % of dense 16-bit for n/m = 1/2):
+ *   values_bytes = N*K*n/m * 2,  meta_bytes = N*K/8,
+ *   native_bytes = 1.125 * Np * Kp with Np = N rounded up to 16, Kp = K rounded up to 256
+ *                  (0 for 4:8, which has no SpMM kernel yet).
+ * Any of the three outputs may be NULL. */
+int esparse_compressed_size(long long N, long long K, int n_keep, int m_group, esparse_dtype dtype,
+                            size_t* values_bytes, size_t* meta_bytes, size_t* native_bytes);
+
+/* W[N,K] in ORIGINAL channel order, mask[N,K] uint8 in re-ordered order (NULL = keep the non-zero
+ * weights; a group with fewer than n non-zeros is topped up with its lowest-position zeros),
+ * perm[K] int32 (NULL = identity).  Outputs, each optional (NULL to skip):
+ *   values_out [N, K*n/m] dtype : kept W[j, perm[p]] in ascending p
+ *   meta_out   2:4 -> uint32[N, ceil(K/32)]: field f (f-th kept value of the row) = its position in
+ *              its group of 4, at bit 2*(f mod 16) of word f div 16;
+ *              4:8 -> uint8[N, K/8]: occupancy bitmap of each group of 8
+ *   native_out (2:4 only) the same data in the order the SpMM kernels stream it: unit = (row, 16
+ *              re-ordered channels) = 8 kept values (16 B) + one uint16 of indices; values units
+ *              ordered [row/16][chunk/4][chunk%4][row%16], then at byte offset Np*Kp the uint16
+ *              units ordered [row/16][chunk/16][chunk%4][row%16][(chunk/4)%4]; zero padded.
+ * Errors: EBADMASK (a group keeping != n, or > n non-zeros with mask NULL), EBADPERM.
+ * Synchronises (it reports those two errors). */
+int esparse_compress(esparse_ctx* ctx, const void* W, const uint8_t* mask, const int32_t* perm,
+                     long long N, long long K, esparse_dtype dtype, int n_keep, int m_group,
+                     void* values_out, void* meta_out, void* native_out);
+
+/* ---- Section 4: sparse product ---------------------------------------------------------------
+ * Y[M,N] (dtype) = X[:, perm] . W'_sparse^T with fp32 accumulation; X[M,K] is in ORIGINAL channel
+ * order, the re-ordering of Section 3.3 is applied while X is staged.  native_w from
+ * esparse_compress.  workspace: DEVICE scratch of at least esparse_spmm_workspace bytes,
+ * 256-byte aligned; it is overwritten.  variant: -1 = the one chosen by esparse_tune for this shape
+ * (a built-in rule if never tuned), >= 0 = a specific kernel variant (EINVAL if out of range).
+ * M = 0 is a no-op.  Only n:m = 2:4 (EUNSUPPORTED otherwise).  Does not synchronise. */
+int esparse_spmm_workspace(long long M, long long N, long long K, size_t* bytes);
+int esparse_spmm(esparse_ctx* ctx, const void* X, long long M, const void* native_w,
+                 const int32_t* perm, long long N, long long K, esparse_dtype dtype, int n_keep,
+                 int m_group, void* Y, void* workspace, size_t workspace_bytes, int variant);
+int esparse_spmm_num_variants(void);
+const char* esparse_spmm_variant_name(int variant);
+
+/* ---- Table 5, "Dense GEMM" column: the dense product on the same shapes ----------------------
+ * esparse_dense_pack re-tiles W[N,K] into the order the dense kernel streams (packed_out:
+ * esparse_dense_packed_size bytes = 2 * Np * Kp, rows padded to 16, K to 256, zero filled).
+ * esparse_dense_gemm: Y[M,N] = X . W^T, same workspace query as the sparse product. */
+int esparse_dense_packed_size(long long N, long long K, size_t* bytes);
+int esparse_dense_pack(esparse_ctx* ctx, const void* W, long long N, long long K,
+                       esparse_dtype dtype, void* packed_out);
+int esparse_dense_gemm(esparse_ctx* ctx, const void* X, long long M, const void* packed_w,
+                       long long N, long long K, esparse_dtype dtype, void* Y, void* workspace,
+                       size_t workspace_bytes, int variant);
+
+/* ---- Section 4, step 2: pick and remember the fastest variant for a shape --------------------
+ * Times every applicable variant of esparse_spmm (sparse != 0) or esparse_dense_gemm on
+ * zero-filled scratch operands of shape (M, N, K) and stores the winner in the context; later
+ * calls with variant = -1 use it.  best_variant (HOST, optional) receives its id.  The table can be
+ * saved to / restored from a text file (HOST path).  Synchronises; allocates scratch. */
+int esparse_tune(esparse_ctx* ctx, long long M, long long N, long long K, esparse_dtype dtype,
+                 int sparse, int* best_variant, float* best_ms);
+int esparse_tune_save(const esparse_ctx* ctx, const char* path);
+int esparse_tune_load(esparse_ctx* ctx, const char* path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ESPARSE_H */

@@ -1,0 +1,406 @@
+// C ABI of libesparse: context, argument validation, dispatch.  Every argument check in this
+// file runs before the first HIP call of the entry point, so the error paths need no GPU.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <cmath>
+
+#include "common.h"
+
+int esp_fail(esparse_ctx* ctx, int code, const char* fmt, ...) {
+  if (ctx) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    ctx->err = buf;
+  }
+  return code;
+}
+
+// value = sum_b bins[b] * 2^(unit0 + 16 b), exact, then one round-to-nearest-even to double.
+double esp_exact_bins_to_double(const unsigned long long* bins, int nb, int unit0) {
+  // little-endian limbs of 32 bits, limb i has weight 2^(unit0 + 32 i)
+  const int NL = 2 * 40;
+  unsigned long long limb[NL];
+  for (int i = 0; i < NL; i++) limb[i] = 0;
+  for (int b = 0; b < nb; b++) {
+    unsigned long long v = bins[b];
+    if (!v) continue;
+    int pos = 16 * b;  // bit offset relative to unit0
+    int li = pos / 32, sh = pos % 32;
+    // v << sh spans up to 96 bits: add three 32-bit pieces
+    unsigned long long lo = (v & 0xffffffffull) << sh;  // < 2^64
+    unsigned long long hi = (v >> 32) << sh;            // weight 2^32 more
+    limb[li] += lo & 0xffffffffull;
+    limb[li + 1] += (lo >> 32) + (hi & 0xffffffffull);
+    limb[li + 2] += hi >> 32;
+  }
+  for (int i = 0; i + 1 < NL; i++) {  // carry propagation (each limb holds < 2^40 before this)
+    limb[i + 1] += limb[i] >> 32;
+    limb[i] &= 0xffffffffull;
+  }
+  int top = -1;
+  for (int i = NL - 1; i >= 0 && top < 0; i--)
+    if (limb[i]) {
+      int bit = 31;
+      while (!((limb[i] >> bit) & 1ull)) bit--;
+      top = 32 * i + bit;
+    }
+  if (top < 0) return 0.0;
+  auto bit_at = [&](int p) -> int { return p < 0 ? 0 : (int)((limb[p / 32] >> (p % 32)) & 1ull); };
+  // 53 significant bits: positions top .. top-52
+  unsigned long long mant = 0;
+  for (int p = top; p > top - 53; p--) mant = (mant << 1) | (unsigned long long)bit_at(p);
+  int guard = bit_at(top - 53);
+  int sticky = 0;
+  for (int p = top - 54; p >= 0 && !sticky; p--) sticky |= bit_at(p);
+  if (guard && (sticky || (mant & 1ull))) mant++;  // may become 2^53: ldexp handles it
+  return std::ldexp((double)mant, unit0 + top - 52);
+}
+
+extern "C" {
+
+const char* esparse_version(void) { return "esparse-gfx950 0.1"; }
+
+int esparse_create(esparse_ctx** out, int device, void* hip_stream) {
+  if (!out || device < 0) return ESPARSE_EINVAL;
+  esparse_ctx* c = new (std::nothrow) esparse_ctx();
+  if (!c) return ESPARSE_ENOMEM;
+  c->device = device;
+  c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  *out = c;
+  return ESPARSE_OK;
+}
+
+void esparse_destroy(esparse_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->d_flags) (void)hipFree(ctx->d_flags);
+  delete ctx;
+}
+
+int esparse_set_stream(esparse_ctx* ctx, void* hip_stream) {
+  if (!ctx) return ESPARSE_EINVAL;
+  ctx->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  return ESPARSE_OK;
+}
+
+const char* esparse_last_error(const esparse_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+static int check_dtype(esparse_ctx* ctx, int dtype) {
+  ESP_REQUIRE(ctx, dtype == ESPARSE_F16 || dtype == ESPARSE_BF16, ESPARSE_EUNSUPPORTED,
+              "dtype %d is not f16 / bf16", dtype);
+  return ESPARSE_OK;
+}
+
+static int check_pattern(esparse_ctx* ctx, int n, int m) {
+  ESP_REQUIRE(ctx, (n == 2 && m == 4) || (n == 4 && m == 8), ESPARSE_EUNSUPPORTED,
+              "n:m = %d:%d is not 2:4 or 4:8", n, m);
+  return ESPARSE_OK;
+}
+
+static int bind_device(esparse_ctx* ctx) {
+  ESP_HIP(ctx, hipSetDevice(ctx->device));
+  if (!ctx->d_flags) ESP_HIP(ctx, hipMalloc((void**)&ctx->d_flags, 64 * sizeof(int)));
+  return ESPARSE_OK;
+}
+
+int esparse_channel_stats(esparse_ctx* ctx, const void* calib, long long T, long long K,
+                          esparse_dtype dtype, int bins, double* ir_out, double* am_out) {
+  if (!ctx) return ESPARSE_EINVAL;
+  int rc = check_dtype(ctx, dtype);
+  if (rc) return rc;
+  ESP_REQUIRE(ctx, calib, ESPARSE_EINVAL, "calib is null");
+  ESP_REQUIRE(ctx, T >= 1 && T <= (1ll << 24), ESPARSE_EINVAL, "T = %lld outside [1, 2^24]", T);
+  ESP_REQUIRE(ctx, K >= 2 && K % 2 == 0, ESPARSE_EINVAL, "K = %lld must be even and >= 2", K);
+  ESP_REQUIRE(ctx, bins >= 1 && bins <= 256, ESPARSE_EINVAL, "bins = %d outside [1, 256]", bins);
+  ESP_REQUIRE(ctx, esp_aligned16(calib), ESPARSE_EINVAL, "calib is not 16-byte aligned");
+  if ((rc = bind_device(ctx))) return rc;
+  std::vector<double> ir, am;
+  if ((rc = esp_stats_device(ctx, calib, T, K, dtype, bins, ir_out ? &ir : nullptr, am_out ? &am : nullptr)))
+    return rc;
+  if (ir_out) memcpy(ir_out, ir.data(), sizeof(double) * K);
+  if (am_out) memcpy(am_out, am.data(), sizeof(double) * K);
+  return ESPARSE_OK;
+}
+
+static int check_prune_args(esparse_ctx* ctx, const void* W, long long N, long long K, int dtype,
+                            const esparse_prune_opts* o, const int32_t* perm_out,
+                            const uint8_t* mask_out) {
+  int rc = check_dtype(ctx, dtype);
+  if (rc) return rc;
+  ESP_REQUIRE(ctx, o, ESPARSE_EINVAL, "opts is null");
+  if ((rc = check_pattern(ctx, o->n_keep, o->m_group))) return rc;
+  ESP_REQUIRE(ctx, W && perm_out && mask_out, ESPARSE_EINVAL, "W / perm_out / mask_out is null");
+  ESP_REQUIRE(ctx, N >= 1 && N < (1ll << 31), ESPARSE_EINVAL, "N = %lld out of range", N);
+  ESP_REQUIRE(ctx, K >= o->m_group && K < (1ll << 31), ESPARSE_EINVAL, "K = %lld out of range", K);
+  ESP_REQUIRE(ctx, K % o->m_group == 0, ESPARSE_EINVAL, "K = %lld is not a multiple of m = %d", K,
+              o->m_group);
+  ESP_REQUIRE(ctx, (o->flags & ~ESPARSE_USE_ALL) == 0, ESPARSE_EINVAL, "unknown flag bits 0x%x", o->flags);
+  ESP_REQUIRE(ctx, (o->flags & (ESPARSE_USE_ENTROPY | ESPARSE_USE_NORM)) != 0, ESPARSE_EINVAL,
+              "flags select neither the entropy nor the norm term");
+  if (o->flags & ESPARSE_USE_LBS) {
+    ESP_REQUIRE(ctx, o->block >= 2 * o->m_group && o->block <= 256, ESPARSE_EINVAL,
+                "block = %d outside [2 m, 256]", o->block);
+    ESP_REQUIRE(ctx, o->block % o->m_group == 0, ESPARSE_EINVAL, "block = %d is not a multiple of m = %d",
+                o->block, o->m_group);
+    ESP_REQUIRE(ctx, K % o->block == 0, ESPARSE_EINVAL, "K = %lld is not a multiple of block = %d", K,
+                o->block);
+  }
+  ESP_REQUIRE(ctx, o->max_swaps >= 0, ESPARSE_EINVAL, "max_swaps < 0");
+  ESP_REQUIRE(ctx, esp_aligned16(W) && esp_aligned16(perm_out) && esp_aligned16(mask_out), ESPARSE_EINVAL,
+              "W / perm_out / mask_out is not 16-byte aligned");
+  return ESPARSE_OK;
+}
+
+int esparse_prune_with_scores(esparse_ctx* ctx, const double* score, const void* W, long long N,
+                              long long K, esparse_dtype dtype, const esparse_prune_opts* opts,
+                              int32_t* perm_out, uint8_t* mask_out, int64_t* swaps_out,
+                              double* retained_out) {
+  if (!ctx) return ESPARSE_EINVAL;
+  int rc = check_prune_args(ctx, W, N, K, dtype, opts, perm_out, mask_out);
+  if (rc) return rc;
+  ESP_REQUIRE(ctx, score, ESPARSE_EINVAL, "score is null");
+  if ((rc = bind_device(ctx))) return rc;
+  return esp_prune_device(ctx, score, W, N, K, dtype, opts, perm_out, mask_out, swaps_out, retained_out);
+}
+
+int esparse_prune(esparse_ctx* ctx, const void* calib, long long T, const void* W, long long N,
+                  long long K, esparse_dtype dtype, const esparse_prune_opts* opts,
+                  int32_t* perm_out, uint8_t* mask_out, double* score_out, int64_t* swaps_out,
+                  double* retained_out) {
+  if (!ctx) return ESPARSE_EINVAL;
+  int rc = check_prune_args(ctx, W, N, K, dtype, opts, perm_out, mask_out);
+  if (rc) return rc;
+  ESP_REQUIRE(ctx, calib, ESPARSE_EINVAL, "calib is null");
+  ESP_REQUIRE(ctx, T >= 1 && T <= (1ll << 24), ESPARSE_EINVAL, "T = %lld outside [1, 2^24]", T);
+  ESP_REQUIRE(ctx, opts->bins >= 1 && opts->bins <= 256, ESPARSE_EINVAL, "bins = %d outside [1, 256]",
+              opts->bins);
+  ESP_REQUIRE(ctx, std::isfinite(opts->alpha), ESPARSE_EINVAL, "alpha is not finite");
+  ESP_REQUIRE(ctx, esp_aligned16(calib), ESPARSE_EINVAL, "calib is not 16-byte aligned");
+  if ((rc = bind_device(ctx))) return rc;
+  const bool use_e = opts->flags & ESPARSE_USE_ENTROPY, use_n = opts->flags & ESPARSE_USE_NORM;
+  std::vector<double> ir, am;
+  if ((rc = esp_stats_device(ctx, calib, T, K, dtype, opts->bins, use_e ? &ir : nullptr, use_n ? &am : nullptr)))
+    return rc;
+  // eq. 3: s_c = IR_c + alpha * AM_c, each term behind its switch
+  std::vector<double> s((size_t)K, 0.0);
+  for (long long c = 0; c < K; c++) {
+    double v = 0.0;
+    if (use_e) v = v + ir[c];
+    if (use_n) {
+      double t = opts->alpha * am[c];
+      v = v + t;
+    }
+    s[c] = v;
+  }
+  if (score_out) memcpy(score_out, s.data(), sizeof(double) * K);
+  return esp_prune_device(ctx, s.data(), W, N, K, dtype, opts, perm_out, mask_out, swaps_out, retained_out);
+}
+
+int esparse_compressed_size(long long N, long long K, int n, int m, esparse_dtype dtype,
+                            size_t* values_bytes, size_t* meta_bytes, size_t* native_bytes) {
+  if (!((n == 2 && m == 4) || (n == 4 && m == 8))) return ESPARSE_EUNSUPPORTED;
+  if (dtype != ESPARSE_F16 && dtype != ESPARSE_BF16) return ESPARSE_EUNSUPPORTED;
+  if (N < 0 || K < 0 || K % m != 0) return ESPARSE_EINVAL;
+  if (values_bytes) *values_bytes = (size_t)N * (size_t)(K / m * n) * 2;
+  if (meta_bytes) *meta_bytes = (m == 4) ? (size_t)N * (size_t)((K / 2 + 15) / 16) * 4 : (size_t)N * (size_t)(K / 8);
+  if (native_bytes) {
+    if (m == 4) {
+      size_t Np = (size_t)esp_round_up(N, 16), Kp = (size_t)esp_round_up(K, 256);
+      *native_bytes = Np * Kp + Np * Kp / 8;
+    } else {
+      *native_bytes = 0;
+    }
+  }
+  return ESPARSE_OK;
+}
+
+int esparse_compress(esparse_ctx* ctx, const void* W, const uint8_t* mask, const int32_t* perm,
+                     long long N, long long K, esparse_dtype dtype, int n, int m, void* values_out,
+                     void* meta_out, void* native_out) {
+  if (!ctx) return ESPARSE_EINVAL;
+  int rc = check_dtype(ctx, dtype);
+  if (rc) return rc;
+  if ((rc = check_pattern(ctx, n, m))) return rc;
+  ESP_REQUIRE(ctx, W, ESPARSE_EINVAL, "W is null");
+  ESP_REQUIRE(ctx, N >= 0 && N < (1ll << 31) && K >= 0 && K < (1ll << 31), ESPARSE_EINVAL, "N or K out of range");
+  ESP_REQUIRE(ctx, K % m == 0, ESPARSE_EINVAL, "K = %lld is not a multiple of m = %d", K, m);
+  ESP_REQUIRE(ctx, !(native_out && m != 4), ESPARSE_EUNSUPPORTED, "native tiling exists for 2:4 only");
+  ESP_REQUIRE(ctx, esp_aligned16(W) && esp_aligned16(mask) && esp_aligned16(perm) && esp_aligned16(values_out) &&
+                       esp_aligned16(meta_out) && esp_aligned16(native_out),
+              ESPARSE_EINVAL, "a pointer is not 16-byte aligned");
+  if (N == 0 || K == 0) return ESPARSE_OK;
+  if ((rc = bind_device(ctx))) return rc;
+  return esp_compress_device(ctx, W, mask, perm, N, K, dtype, n, m, values_out, meta_out, native_out);
+}
+
+static int check_matmul(esparse_ctx* ctx, const void* X, long long M, const void* w, long long N,
+                        long long K, int dtype, const void* Y, const void* ws, size_t ws_bytes,
+                        int variant, int sparse) {
+  int rc = check_dtype(ctx, dtype);
+  if (rc) return rc;
+  ESP_REQUIRE(ctx, M >= 0 && M < (1ll << 24), ESPARSE_EINVAL, "M = %lld out of range", M);
+  ESP_REQUIRE(ctx, N >= 1 && N < (1ll << 31) && K >= 4 && K < (1ll << 31), ESPARSE_EINVAL, "N or K out of range");
+  ESP_REQUIRE(ctx, K % 4 == 0, ESPARSE_EINVAL, "K = %lld is not a multiple of 4", K);
+  if (M == 0) return ESPARSE_OK;
+  ESP_REQUIRE(ctx, X && w && Y && ws, ESPARSE_EINVAL, "X / weights / Y / workspace is null");
+  ESP_REQUIRE(ctx, esp_aligned16(X) && esp_aligned16(w) && esp_aligned16(Y), ESPARSE_EINVAL,
+              "X / weights / Y is not 16-byte aligned");
+  ESP_REQUIRE(ctx, (reinterpret_cast<uintptr_t>(ws) & 255u) == 0, ESPARSE_EINVAL, "workspace is not 256-byte aligned");
+  ESP_REQUIRE(ctx, ws_bytes >= esp_workspace_bytes(M, N, K), ESPARSE_EWORKSPACE,
+              "workspace has %zu bytes, %zu needed", ws_bytes, esp_workspace_bytes(M, N, K));
+  ESP_REQUIRE(ctx, variant >= -1 && variant < esp_num_variants(), ESPARSE_EINVAL, "variant %d does not exist", variant);
+  ESP_REQUIRE(ctx, variant < 0 || esp_variant_applicable(variant, M, N, K, sparse), ESPARSE_EUNSUPPORTED,
+              "variant %d (%s) cannot run M=%lld N=%lld K=%lld", variant, esp_variant_name(variant), M, N, K);
+  return ESPARSE_OK;
+}
+
+static int pick_variant(esparse_ctx* ctx, int sparse, int dtype, long long M, long long N, long long K, int variant) {
+  if (variant >= 0) return variant;
+  auto it = ctx->tuned.find(std::make_tuple(sparse, dtype, M, N, K));
+  if (it != ctx->tuned.end() && esp_variant_applicable(it->second, M, N, K, sparse)) return it->second;
+  return esp_default_variant(M, N, K, sparse);
+}
+
+int esparse_spmm_workspace(long long M, long long N, long long K, size_t* bytes) {
+  if (!bytes || M < 0 || N < 1 || K < 4) return ESPARSE_EINVAL;
+  *bytes = esp_workspace_bytes(M, N, K);
+  return ESPARSE_OK;
+}
+
+int esparse_spmm_num_variants(void) { return esp_num_variants(); }
+const char* esparse_spmm_variant_name(int v) { return (v >= 0 && v < esp_num_variants()) ? esp_variant_name(v) : ""; }
+
+int esparse_spmm(esparse_ctx* ctx, const void* X, long long M, const void* native_w, const int32_t* perm,
+                 long long N, long long K, esparse_dtype dtype, int n, int m, void* Y, void* workspace,
+                 size_t workspace_bytes, int variant) {
+  if (!ctx) return ESPARSE_EINVAL;
+  ESP_REQUIRE(ctx, n == 2 && m == 4, ESPARSE_EUNSUPPORTED, "the sparse product exists for 2:4 only (got %d:%d)", n, m);
+  int rc = check_matmul(ctx, X, M, native_w, N, K, dtype, Y, workspace, workspace_bytes, variant, 1);
+  if (rc) return rc;
+  ESP_REQUIRE(ctx, esp_aligned16(perm), ESPARSE_EINVAL, "perm is not 16-byte aligned");
+  if (M == 0) return ESPARSE_OK;
+  ESP_HIP(ctx, hipSetDevice(ctx->device));
+  return esp_matmul_device(ctx, 1, X, M, native_w, perm, N, K, dtype, Y, workspace,
+                           pick_variant(ctx, 1, dtype, M, N, K, variant));
+}
+
+int esparse_dense_packed_size(long long N, long long K, size_t* bytes) {
+  if (!bytes || N < 0 || K < 0) return ESPARSE_EINVAL;
+  *bytes = (size_t)esp_round_up(N, 16) * (size_t)esp_round_up(K, 256) * 2;
+  return ESPARSE_OK;
+}
+
+int esparse_dense_pack(esparse_ctx* ctx, const void* W, long long N, long long K, esparse_dtype dtype,
+                       void* packed_out) {
+  if (!ctx) return ESPARSE_EINVAL;
+  int rc = check_dtype(ctx, dtype);
+  if (rc) return rc;
+  ESP_REQUIRE(ctx, W && packed_out, ESPARSE_EINVAL, "W / packed_out is null");
+  ESP_REQUIRE(ctx, N >= 1 && N < (1ll << 31) && K >= 4 && K < (1ll << 31) && K % 4 == 0, ESPARSE_EINVAL,
+              "N or K out of range (K must be a multiple of 4)");
+  ESP_REQUIRE(ctx, esp_aligned16(W) && esp_aligned16(packed_out), ESPARSE_EINVAL, "a pointer is not 16-byte aligned");
+  ESP_HIP(ctx, hipSetDevice(ctx->device));
+  return esp_dense_pack_device(ctx, W, N, K, dtype, packed_out);
+}
+
+int esparse_dense_gemm(esparse_ctx* ctx, const void* X, long long M, const void* packed_w, long long N,
+                       long long K, esparse_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
+                       int variant) {
+  if (!ctx) return ESPARSE_EINVAL;
+  int rc = check_matmul(ctx, X, M, packed_w, N, K, dtype, Y, workspace, workspace_bytes, variant, 0);
+  if (rc) return rc;
+  if (M == 0) return ESPARSE_OK;
+  ESP_HIP(ctx, hipSetDevice(ctx->device));
+  return esp_matmul_device(ctx, 0, X, M, packed_w, nullptr, N, K, dtype, Y, workspace,
+                           pick_variant(ctx, 0, dtype, M, N, K, variant));
+}
+
+int esparse_tune(esparse_ctx* ctx, long long M, long long N, long long K, esparse_dtype dtype, int sparse,
+                 int* best_variant, float* best_ms) {
+  if (!ctx) return ESPARSE_EINVAL;
+  int rc = check_dtype(ctx, dtype);
+  if (rc) return rc;
+  ESP_REQUIRE(ctx, M >= 1 && M < (1ll << 24) && N >= 1 && N < (1ll << 31) && K >= 4 && K < (1ll << 31) && K % 4 == 0,
+              ESPARSE_EINVAL, "shape out of range");
+  sparse = sparse ? 1 : 0;
+  ESP_HIP(ctx, hipSetDevice(ctx->device));
+  const size_t Np = (size_t)esp_round_up(N, 16), Kp = (size_t)esp_round_up(K, 256);
+  DevBuf w, x, y, ws;
+  const size_t wbytes = sparse ? Np * Kp + Np * Kp / 8 : Np * Kp * 2;
+  if (w.alloc(wbytes) != hipSuccess || x.alloc((size_t)M * K * 2) != hipSuccess ||
+      y.alloc((size_t)M * N * 2) != hipSuccess || ws.alloc(esp_workspace_bytes(M, N, K)) != hipSuccess)
+    return esp_fail(ctx, ESPARSE_ENOMEM, "scratch allocation for tuning failed");
+  ESP_HIP(ctx, hipMemsetAsync(w.p, 0, wbytes, ctx->stream));
+  ESP_HIP(ctx, hipMemsetAsync(x.p, 0, (size_t)M * K * 2, ctx->stream));
+  hipEvent_t e0, e1;
+  ESP_HIP(ctx, hipEventCreate(&e0));
+  ESP_HIP(ctx, hipEventCreate(&e1));
+  int best = -1;
+  float best_t = 0.f;
+  const int reps = 20;
+  for (int v = 0; v < esp_num_variants(); v++) {
+    if (!esp_variant_applicable(v, M, N, K, sparse)) continue;
+    for (int i = 0; i < 3; i++)
+      if ((rc = esp_matmul_device(ctx, sparse, x.p, M, w.p, nullptr, N, K, dtype, y.p, ws.p, v))) break;
+    if (rc) break;
+    (void)hipEventRecord(e0, ctx->stream);
+    for (int i = 0; i < reps; i++)
+      if ((rc = esp_matmul_device(ctx, sparse, x.p, M, w.p, nullptr, N, K, dtype, y.p, ws.p, v))) break;
+    (void)hipEventRecord(e1, ctx->stream);
+    if (rc) break;
+    if (hipEventSynchronize(e1) != hipSuccess) {
+      rc = esp_fail(ctx, ESPARSE_EHIP, "event synchronize failed while tuning");
+      break;
+    }
+    float ms = 0.f;
+    (void)hipEventElapsedTime(&ms, e0, e1);
+    ms /= reps;
+    if (best < 0 || ms < best_t) {
+      best = v;
+      best_t = ms;
+    }
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc) return rc;
+  ESP_REQUIRE(ctx, best >= 0, ESPARSE_EUNSUPPORTED, "no variant can run this shape");
+  ctx->tuned[std::make_tuple(sparse, (int)dtype, M, N, K)] = best;
+  if (best_variant) *best_variant = best;
+  if (best_ms) *best_ms = best_t;
+  return ESPARSE_OK;
+}
+
+int esparse_tune_save(const esparse_ctx* ctx, const char* path) {
+  if (!ctx || !path) return ESPARSE_EINVAL;
+  FILE* f = fopen(path, "w");
+  if (!f) return ESPARSE_EINVAL;
+  fprintf(f, "# sparse dtype M N K variant-name\n");
+  for (const auto& kv : ctx->tuned)
+    fprintf(f, "%d %d %lld %lld %lld %s\n", std::get<0>(kv.first), std::get<1>(kv.first), std::get<2>(kv.first),
+            std::get<3>(kv.first), std::get<4>(kv.first), esp_variant_name(kv.second));
+  fclose(f);
+  return ESPARSE_OK;
+}
+
+int esparse_tune_load(esparse_ctx* ctx, const char* path) {
+  if (!ctx || !path) return ESPARSE_EINVAL;
+  FILE* f = fopen(path, "r");
+  if (!f) return esp_fail(ctx, ESPARSE_EINVAL, "cannot open %s", path);
+  char line[256];
+  while (fgets(line, sizeof line, f)) {
+    if (line[0] == '#') continue;
+    int sp, dt;
+    long long M, N, K;
+    char name[128];
+    if (sscanf(line, "%d %d %lld %lld %lld %127s", &sp, &dt, &M, &N, &K, name) != 6) continue;
+    for (int v = 0; v < esp_num_variants(); v++)
+      if (!strcmp(name, esp_variant_name(v))) ctx->tuned[std::make_tuple(sp, dt, M, N, K)] = v;
+  }
+  fclose(f);
+  return ESPARSE_OK;
+}
+
+}  // extern "C"

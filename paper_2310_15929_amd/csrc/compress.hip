@@ -1,0 +1,239 @@
+// Compression of n:m-pruned weights (Section 4, step 1): kept values + 2 bits of index per kept
+// value, written both in the canonical row-major form and in the order the sparse-MFMA kernels
+// stream (the layout is documented in include/esparse.h).  Pure data movement: HBM-bound.
+#include "common.h"
+
+// flags[0] |= 1 : a group does not keep exactly n ; flags[0] |= 2 : perm is not a bijection
+__global__ void k_perm_count(const int32_t* __restrict__ perm, long long K, int* __restrict__ count, int* __restrict__ flags) {
+  long long p = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (p >= K) return;
+  int c = perm[p];
+  if (c < 0 || c >= K)
+    atomicOr(flags, 2);
+  else if (atomicAdd(&count[c], 1) != 0)
+    atomicOr(flags, 2);
+}
+
+// ---- 2:4 ----------------------------------------------------------------------------------------
+// One thread per unit = (row, 16 re-ordered channels): 4 groups, 8 kept values, 16 index bits.
+// Units beyond N or K (padding of the native tiling) are written as zeros.
+__global__ void __launch_bounds__(256) k_compress_2_4(const uint16_t* __restrict__ W, const uint8_t* __restrict__ mask,
+                                                       const int32_t* __restrict__ perm, long long N, long long K, long long Np,
+                                                       long long Kp, uint16_t* __restrict__ values, uint32_t* __restrict__ meta,
+                                                       uint16_t* __restrict__ nvalues, uint16_t* __restrict__ nmeta,
+                                                       int* __restrict__ flags) {
+  const long long nchunk = Kp / 16;
+  long long u = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (u >= Np * nchunk) return;
+  // native order of the thread index keeps the native stores coalesced:
+  // u = ((rt * (nchunk/4) + ks) * 4 + ga) * 16 + r
+  const int r = (int)(u & 15), ga = (int)((u >> 4) & 3);
+  const long long t = u >> 6;
+  const long long ks = t % (nchunk / 4), rt = t / (nchunk / 4);
+  const long long row = rt * 16 + r, ch = ks * 4 + ga;
+  uint16_t kept[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  uint32_t bits = 0;
+  int nk = 0;  // kept values in this unit (8 unless the unit is cut by K or is padding)
+  const long long p0 = ch * 16;
+  if (row < N && p0 < K) {
+    const int ngroups = (int)((K - p0) >= 16 ? 4 : (K - p0) / 4);
+    for (int g = 0; g < ngroups; g++) {
+      uint16_t w[4];
+      uint8_t mk[4];
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        long long p = p0 + g * 4 + i;
+        long long c = perm ? perm[p] : p;
+        w[i] = W[row * K + c];
+        mk[i] = mask ? mask[row * K + p] : 0;
+      }
+      if (!mask) {
+        // keep the non-zero weights, topped up with the lowest-position zeros
+        int nz = 0;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          mk[i] = (w[i] & 0x7fffu) ? 1 : 0;
+          nz += mk[i];
+        }
+        if (nz > 2) atomicOr(flags, 1);
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+          if (nz < 2 && !mk[i]) {
+            mk[i] = 1;
+            nz++;
+          }
+      }
+      int cnt = 0;
+#pragma unroll
+      for (int i = 0; i < 4; i++)
+        if (mk[i]) {
+          if (cnt < 2) {
+            kept[nk] = w[i];
+            bits |= (uint32_t)i << (2 * nk);
+            nk++;
+          }
+          cnt++;
+        }
+      if (cnt != 2) {
+        atomicOr(flags, 1);
+        while (cnt < 2) {  // keep the layout well-formed; the call reports EBADMASK
+          nk++;
+          cnt++;
+        }
+      }
+    }
+    // canonical: values[row][ch*8 .. ch*8+nk), meta halves
+    if (values) {
+      uint16_t* dst = values + row * (K / 2) + ch * 8;
+      if (nk == 8 && ((K / 2) % 8 == 0)) {
+        uint4 v;
+        v.x = kept[0] | ((uint32_t)kept[1] << 16);
+        v.y = kept[2] | ((uint32_t)kept[3] << 16);
+        v.z = kept[4] | ((uint32_t)kept[5] << 16);
+        v.w = kept[6] | ((uint32_t)kept[7] << 16);
+        *reinterpret_cast<uint4*>(dst) = v;
+      } else {
+        for (int i = 0; i < nk; i++) dst[i] = kept[i];
+      }
+    }
+    if (meta) {
+      // uint32 words per row: ceil(K/32); this unit is half-word (ch & 1) of word ch / 2
+      uint16_t* m16 = reinterpret_cast<uint16_t*>(meta + row * ((K / 2 + 15) / 16));
+      m16[ch] = (uint16_t)bits;
+      if (p0 + 16 >= K && (ch & 1) == 0) m16[ch + 1] = 0;  // unused half of the row's last word
+    }
+  }
+  if (nvalues) {
+    uint4 v;
+    v.x = kept[0] | ((uint32_t)kept[1] << 16);
+    v.y = kept[2] | ((uint32_t)kept[3] << 16);
+    v.z = kept[4] | ((uint32_t)kept[5] << 16);
+    v.w = kept[6] | ((uint32_t)kept[7] << 16);
+    reinterpret_cast<uint4*>(nvalues)[u] = v;
+    // meta unit order [rt][ks/4][ga][r][ks%4]
+    const long long mi = (((rt * (nchunk / 16) + ks / 4) * 4 + ga) * 16 + r) * 4 + (ks % 4);
+    nmeta[mi] = (uint16_t)bits;
+  }
+}
+
+// ---- 4:8 ----------------------------------------------------------------------------------------
+// One thread per (row, group of 8): 4 kept values + one bitmap byte.
+__global__ void __launch_bounds__(256) k_compress_4_8(const uint16_t* __restrict__ W, const uint8_t* __restrict__ mask,
+                                                       const int32_t* __restrict__ perm, long long N, long long K,
+                                                       uint16_t* __restrict__ values, uint8_t* __restrict__ meta,
+                                                       int* __restrict__ flags) {
+  const long long ng = K / 8;
+  long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= N * ng) return;
+  const long long row = e / ng, g = e % ng;
+  uint16_t w[8];
+  uint8_t mk[8];
+  int nz = 0;
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    long long p = g * 8 + i;
+    long long c = perm ? perm[p] : p;
+    w[i] = W[row * K + c];
+    mk[i] = mask ? (mask[row * K + p] ? 1 : 0) : ((w[i] & 0x7fffu) ? 1 : 0);
+    nz += mk[i];
+  }
+  if (!mask) {
+    if (nz > 4) atomicOr(flags, 1);
+#pragma unroll
+    for (int i = 0; i < 8; i++)
+      if (nz < 4 && !mk[i]) {
+        mk[i] = 1;
+        nz++;
+      }
+  }
+  if (nz != 4) atomicOr(flags, 1);
+  uint16_t kept[4] = {0, 0, 0, 0};
+  uint32_t bm = 0;
+  int nk = 0;
+#pragma unroll
+  for (int i = 0; i < 8; i++)
+    if (mk[i] && nk < 4) {
+      kept[nk++] = w[i];
+      bm |= 1u << i;
+    }
+  if (values) {
+    uint2 v;
+    v.x = kept[0] | ((uint32_t)kept[1] << 16);
+    v.y = kept[2] | ((uint32_t)kept[3] << 16);
+    *reinterpret_cast<uint2*>(values + row * (K / 2) + g * 4) = v;
+  }
+  if (meta) meta[row * ng + g] = (uint8_t)bm;
+}
+
+int esp_compress_device(esparse_ctx* ctx, const void* Wv, const uint8_t* mask, const int32_t* perm, long long N,
+                        long long K, int dtype, int n, int m, void* values_out, void* meta_out, void* native_out) {
+  (void)dtype;  // both dtypes are 16-bit patterns here
+  (void)n;
+  hipStream_t st = ctx->stream;
+  int* flags = ctx->d_flags;
+  ESP_HIP(ctx, hipMemsetAsync(flags, 0, sizeof(int), st));
+  DevBuf count;
+  if (perm) {
+    if (count.alloc(K * 4) != hipSuccess) return esp_fail(ctx, ESPARSE_ENOMEM, "scratch allocation failed");
+    ESP_HIP(ctx, hipMemsetAsync(count.p, 0, K * 4, st));
+    hipLaunchKernelGGL(k_perm_count, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, perm, K, count.as<int>(), flags);
+    ESP_HIP(ctx, hipGetLastError());
+    int h = 0;
+    ESP_HIP(ctx, hipMemcpyAsync(&h, flags, sizeof(int), hipMemcpyDeviceToHost, st));
+    ESP_HIP(ctx, hipStreamSynchronize(st));
+    if (h & 2) return esp_fail(ctx, ESPARSE_EBADPERM, "perm is not a bijection on [0, %lld)", K);
+  }
+  const uint16_t* W = reinterpret_cast<const uint16_t*>(Wv);
+  if (m == 4) {
+    const long long Np = esp_round_up(N, 16);
+    const long long Kp = esp_round_up(K, 256);
+    uint16_t* nvalues = reinterpret_cast<uint16_t*>(native_out);
+    uint16_t* nmeta = native_out ? reinterpret_cast<uint16_t*>(reinterpret_cast<unsigned char*>(native_out) + (size_t)Np * Kp) : nullptr;
+    const long long units = Np * (Kp / 16);
+    hipLaunchKernelGGL(k_compress_2_4, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, st, W, mask, perm, N, K, Np, Kp,
+                       reinterpret_cast<uint16_t*>(values_out), reinterpret_cast<uint32_t*>(meta_out), nvalues, nmeta, flags);
+  } else {
+    const long long groups = N * (K / 8);
+    hipLaunchKernelGGL(k_compress_4_8, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, W, mask, perm, N, K,
+                       reinterpret_cast<uint16_t*>(values_out), reinterpret_cast<uint8_t*>(meta_out), flags);
+  }
+  ESP_HIP(ctx, hipGetLastError());
+  int h = 0;
+  ESP_HIP(ctx, hipMemcpyAsync(&h, flags, sizeof(int), hipMemcpyDeviceToHost, st));
+  ESP_HIP(ctx, hipStreamSynchronize(st));
+  if (h & 1) return esp_fail(ctx, ESPARSE_EBADMASK, "a group of %d does not keep exactly %d weights", m, n);
+  return ESPARSE_OK;
+}
+
+// ---- dense re-tiling (the dense GEMM streams W the same way the sparse one streams its values) ----
+// unit = (row, 8 channels) = 16 bytes; order [row/16][chunk/4][chunk%4][row%16]; zero padded.
+__global__ void __launch_bounds__(256) k_dense_pack(const uint16_t* __restrict__ W, long long N, long long K, long long Np,
+                                                     long long Kp, uint4* __restrict__ out) {
+  const long long nchunk = Kp / 8;
+  long long u = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (u >= Np * nchunk) return;
+  const int r = (int)(u & 15), g = (int)((u >> 4) & 3);
+  const long long t = u >> 6;
+  const long long ks = t % (nchunk / 4), rt = t / (nchunk / 4);
+  const long long row = rt * 16 + r, k0 = (ks * 4 + g) * 8;
+  uint16_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (row < N)
+    for (int e = 0; e < 8; e++)
+      if (k0 + e < K) v[e] = W[row * K + k0 + e];
+  uint4 o;
+  o.x = v[0] | ((uint32_t)v[1] << 16);
+  o.y = v[2] | ((uint32_t)v[3] << 16);
+  o.z = v[4] | ((uint32_t)v[5] << 16);
+  o.w = v[6] | ((uint32_t)v[7] << 16);
+  out[u] = o;
+}
+
+int esp_dense_pack_device(esparse_ctx* ctx, const void* W, long long N, long long K, int dtype, void* packed) {
+  (void)dtype;
+  const long long Np = esp_round_up(N, 16), Kp = esp_round_up(K, 256);
+  const long long units = Np * (Kp / 8);
+  hipLaunchKernelGGL(k_dense_pack, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, ctx->stream,
+                     reinterpret_cast<const uint16_t*>(W), N, K, Np, Kp, reinterpret_cast<uint4*>(packed));
+  ESP_HIP(ctx, hipGetLastError());
+  return ESPARSE_OK;
+}

@@ -1,0 +1,360 @@
+// Sparse (2:4, v_smfmac) and dense (v_mfma) products Y[M,N] = X[M,K] . W[N,K]^T on gfx950
+// (Section 4 of the paper: the Sparse-GEMM and its dense baseline, Table 5).
+//
+// Operand layouts of the matrix instructions used here (wave of 64 lanes, lane l, c = l % 16,
+// g = l / 16), measured on the hardware with one-hot operands:
+//   v_mfma_f32_16x16x32_{f16,bf16}    A: row c, k = 8 g + e (e = 0..7)      B: column c, k = 8 g + e
+//   v_smfmac_f32_16x16x64_{f16,bf16}  A: row c, the 8 kept values of channels [16 g, 16 g + 16) in
+//                                        order; value e sits at channel 16 g + 4 (e / 2) + idx_e where
+//                                        idx_e = bits [2e+1 : 2e] of the low (ABID = 0) or high
+//                                        (ABID = 1) half of the index register of the SAME lane
+//                                     B: column c, e < 8 : k = 8 g + e ;  e >= 8 : k = 32 + 8 g + (e - 8)
+//                                        (two B operands of the dense 16x16x32 instruction back to back)
+//   both                              D: column c, rows 4 g + j (j = 0..3)
+// W is the A operand (rows of D = output features), the activations are the B operand (columns of
+// D = tokens), so D is a 16 x 16 tile of Y^T.
+//
+// Memory formats
+//   sparse weights ("native"): see include/esparse.h; the 16-byte unit u = (rt * nks + ks) * 64 + l is
+//     exactly what lane l feeds to the instruction for row tile rt and 64-channel step ks, and the
+//     8-byte index unit (rt * nks/4 + ks/4) * 64 + l holds the lane's index halves of 4 steps.
+//   dense weights (packed): 16-byte unit (rt * ns + s) * 64 + l for 32-channel step s.
+//   activations ("fragment-major" X', built by k_gather_x in the workspace): 16-byte unit
+//     (tt * ns + s) * 64 + l = tokens 16 tt + c, re-ordered channels 32 s + 8 g .. + 7, i.e. the B
+//     operand of the dense instruction for token tile tt and step s; the channel re-ordering theta
+//     of Section 3.3 is applied here (X'[t, p] = X[t, theta[p]]), zero padded in both directions.
+#include <algorithm>
+
+#include "common.h"
+
+#define WS_HEADER_BYTES 65536
+#define MAX_SPLIT 16
+
+// ------------------------------------------------------------------------------------------------
+// instruction wrappers
+// ------------------------------------------------------------------------------------------------
+template <int DT, int ABID>
+__device__ __forceinline__ floatx4_t smfmac16(uint4 a, uint4 b0, uint4 b1, floatx4_t c, int idx) {
+  struct B2 {
+    uint4 lo, hi;
+  } bb = {b0, b1};
+  if (DT == ESPARSE_F16) {
+    return __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half16_t, bb), c, idx, 0, ABID);
+  } else {
+    return __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x16_t, bb), c, idx, 0, ABID);
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ floatx4_t mfma16(uint4 a, uint4 b, floatx4_t c) {
+  if (DT == ESPARSE_F16) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+  } else {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// activation staging: X[M,K] (original channel order) -> fragment-major X' through theta
+// one thread per 16-byte unit
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_gather_x(const uint16_t* __restrict__ X, const int32_t* __restrict__ perm, long long M,
+                                                   long long K, long long Kp, long long units, uint4* __restrict__ Xf) {
+  long long u = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (u >= units) return;
+  const int lane = (int)(u & 63);
+  const long long ns = Kp / 32;
+  const long long s = (u >> 6) % ns, tt = (u >> 6) / ns;
+  const long long t = tt * 16 + (lane & 15);
+  const long long k0 = s * 32 + (lane >> 4) * 8;
+  uint16_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (t < M && k0 < K) {
+    const uint16_t* xr = X + t * K;
+    if (perm) {
+      if (k0 + 8 <= K) {
+        const int4 p0 = *reinterpret_cast<const int4*>(perm + k0);
+        const int4 p1 = *reinterpret_cast<const int4*>(perm + k0 + 4);
+        v[0] = xr[p0.x];
+        v[1] = xr[p0.y];
+        v[2] = xr[p0.z];
+        v[3] = xr[p0.w];
+        v[4] = xr[p1.x];
+        v[5] = xr[p1.y];
+        v[6] = xr[p1.z];
+        v[7] = xr[p1.w];
+      } else {
+        for (int e = 0; e < 8; e++)
+          if (k0 + e < K) v[e] = xr[perm[k0 + e]];
+      }
+    } else {
+      for (int e = 0; e < 8; e++)
+        if (k0 + e < K) v[e] = xr[k0 + e];
+    }
+  }
+  uint4 o;
+  o.x = v[0] | ((uint32_t)v[1] << 16);
+  o.y = v[2] | ((uint32_t)v[3] << 16);
+  o.z = v[4] | ((uint32_t)v[5] << 16);
+  o.w = v[6] | ((uint32_t)v[7] << 16);
+  Xf[u] = o;
+}
+
+// ------------------------------------------------------------------------------------------------
+// epilogue helpers
+// ------------------------------------------------------------------------------------------------
+template <int DT>
+__device__ __forceinline__ void store_y4(uint16_t* __restrict__ Y, long long M, long long N, long long t, long long n,
+                                         floatx4_t acc) {
+  if (t >= M) return;
+  uint16_t h[4];
+#pragma unroll
+  for (int j = 0; j < 4; j++) h[j] = esp_from_float<DT>(acc[j]);
+  uint16_t* dst = Y + t * N + n;
+  if ((N & 3) == 0 && n + 3 < N) {
+    uint2 v;
+    v.x = h[0] | ((uint32_t)h[1] << 16);
+    v.y = h[2] | ((uint32_t)h[3] << 16);
+    *reinterpret_cast<uint2*>(dst) = v;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+      if (n + j < N) dst[j] = h[j];
+  }
+}
+
+// partial[split][t][n] (fp32, padded Mp x Np) -> Y, splits added in ascending order
+template <int DT>
+__global__ void __launch_bounds__(256) k_reduce_splits(const float* __restrict__ partial, int nsplit, long long M, long long N,
+                                                        long long Mp, long long Np, uint16_t* __restrict__ Y) {
+  const long long n4 = Np / 4;
+  long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= M * n4) return;
+  const long long t = e / n4, n = (e % n4) * 4;
+  floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < nsplit; s++) {
+    const floatx4_t v = *reinterpret_cast<const floatx4_t*>(partial + ((long long)s * Mp + t) * Np + n);
+    acc += v;
+  }
+  store_y4<DT>(Y, M, N, t, n, acc);
+}
+
+// ------------------------------------------------------------------------------------------------
+// variant "wave-tile": every wave owns RT row tiles x TT token tiles x one K split and streams
+// both operands straight from global memory (fragment-major, 16 bytes per lane, fully coalesced).
+// No LDS, no barriers.  Items are numbered with the row block fastest.
+// ------------------------------------------------------------------------------------------------
+template <int DT, int SPARSE, int RT, int TT>
+__global__ void __launch_bounds__(256) k_mm_wave_tile(const uint4* __restrict__ A, const uint2* __restrict__ meta,
+                                                       const uint4* __restrict__ Xf, uint16_t* __restrict__ Y,
+                                                       float* __restrict__ partial, long long M, long long N, long long Mp,
+                                                       long long Np, long long Kp, int nsplit, int steps_per_split,
+                                                       long long n_items) {
+  const int lane = threadIdx.x & 63;
+  const long long item = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= n_items) return;
+  const long long nrt = Np / 16, ntt = Mp / 16;
+  const long long nrb = (nrt + RT - 1) / RT, ntb = (ntt + TT - 1) / TT;
+  const long long rb = item % nrb;
+  const long long tb = (item / nrb) % ntb;
+  const int split = (int)(item / (nrb * ntb));
+  const long long nks = Kp / 64;  // 64-channel steps
+  const long long ks0 = (long long)split * steps_per_split;
+  const long long ks1 = (ks0 + steps_per_split < nks) ? ks0 + steps_per_split : nks;
+
+  floatx4_t acc[RT][TT];
+#pragma unroll
+  for (int i = 0; i < RT; i++)
+#pragma unroll
+    for (int j = 0; j < TT; j++) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+  long long rts[RT], tts[TT];
+#pragma unroll
+  for (int i = 0; i < RT; i++) {
+    long long rt = rb * RT + i;
+    rts[i] = rt < nrt ? rt : nrt - 1;  // clamp: duplicate work, discarded in the epilogue
+  }
+#pragma unroll
+  for (int j = 0; j < TT; j++) {
+    long long tt = tb * TT + j;
+    tts[j] = tt < ntt ? tt : ntt - 1;
+  }
+
+  for (long long ks = ks0; ks < ks1; ks += 4) {
+    if (SPARSE) {
+      uint2 md[RT];
+#pragma unroll
+      for (int i = 0; i < RT; i++) md[i] = meta[(rts[i] * (nks / 4) + ks / 4) * 64 + lane];
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        uint4 a[RT], b0[TT], b1[TT];
+#pragma unroll
+        for (int i = 0; i < RT; i++) a[i] = A[(rts[i] * nks + ks + q) * 64 + lane];
+#pragma unroll
+        for (int j = 0; j < TT; j++) {
+          b0[j] = Xf[(tts[j] * (2 * nks) + 2 * (ks + q)) * 64 + lane];
+          b1[j] = Xf[(tts[j] * (2 * nks) + 2 * (ks + q) + 1) * 64 + lane];
+        }
+#pragma unroll
+        for (int i = 0; i < RT; i++) {
+          const int idx = (int)((q < 2) ? md[i].x : md[i].y);
+#pragma unroll
+          for (int j = 0; j < TT; j++) {
+            if (q & 1)
+              acc[i][j] = smfmac16<DT, 1>(a[i], b0[j], b1[j], acc[i][j], idx);
+            else
+              acc[i][j] = smfmac16<DT, 0>(a[i], b0[j], b1[j], acc[i][j], idx);
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < 8; q++) {
+        const long long s = 2 * ks + q;  // 32-channel step
+        uint4 a[RT], b[TT];
+#pragma unroll
+        for (int i = 0; i < RT; i++) a[i] = A[(rts[i] * (2 * nks) + s) * 64 + lane];
+#pragma unroll
+        for (int j = 0; j < TT; j++) b[j] = Xf[(tts[j] * (2 * nks) + s) * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < RT; i++)
+#pragma unroll
+          for (int j = 0; j < TT; j++) acc[i][j] = mfma16<DT>(a[i], b[j], acc[i][j]);
+      }
+    }
+  }
+
+  const int c = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < RT; i++) {
+    const long long rt = rb * RT + i;
+    if (rt >= nrt) continue;
+#pragma unroll
+    for (int j = 0; j < TT; j++) {
+      const long long tt = tb * TT + j;
+      if (tt >= ntt) continue;
+      const long long t = tt * 16 + c, n = rt * 16 + g * 4;
+      if (nsplit == 1)
+        store_y4<DT>(Y, M, N, t, n, acc[i][j]);
+      else
+        *reinterpret_cast<floatx4_t*>(partial + ((long long)split * Mp + t) * Np + n) = acc[i][j];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// variant table and host launcher
+// ------------------------------------------------------------------------------------------------
+struct Variant {
+  const char* name;
+  int rt, tt;      // row tiles / token tiles per wave
+  int split_mode;  // 0 = never split K, 1 = split K to fill the chip (decode sizes)
+};
+static const Variant kVariants[] = {
+    {"wave_r1_t1_splitk", 1, 1, 1},
+    {"wave_r2_t1_splitk", 2, 1, 1},
+    {"wave_r4_t1_splitk", 4, 1, 1},
+    {"wave_r2_t2_splitk", 2, 2, 1},
+    {"wave_r4_t2", 4, 2, 0},
+    {"wave_r4_t4", 4, 4, 0},
+};
+static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+
+int esp_num_variants() { return kNumVariants; }
+const char* esp_variant_name(int v) { return kVariants[v].name; }
+
+bool esp_variant_applicable(int v, long long M, long long N, long long K, int sparse) {
+  (void)N;
+  (void)K;
+  (void)sparse;
+  if (v < 0 || v >= kNumVariants) return false;
+  if (kVariants[v].split_mode == 1 && M > 128) return false;  // partial buffers are sized for decode only
+  return true;
+}
+
+int esp_default_variant(long long M, long long N, long long K, int sparse) {
+  (void)N;
+  (void)K;
+  (void)sparse;
+  if (M <= 16) return 1;
+  if (M <= 128) return 3;
+  return 5;
+}
+
+size_t esp_workspace_bytes(long long M, long long N, long long K) {
+  const size_t Mp = (size_t)esp_round_up(M, 16), Np = (size_t)esp_round_up(N, 16), Kp = (size_t)esp_round_up(K, 256);
+  size_t bytes = WS_HEADER_BYTES + Mp * Kp * 2;
+  bytes = (bytes + 255) / 256 * 256;
+  if (M <= 128) bytes += (size_t)MAX_SPLIT * Mp * Np * 4;
+  return bytes;
+}
+
+template <int DT, int SPARSE>
+static void launch_wave_tile(const Variant& v, dim3 grid, hipStream_t st, const uint4* A, const uint2* meta, const uint4* Xf,
+                             uint16_t* Y, float* partial, long long M, long long N, long long Mp, long long Np, long long Kp,
+                             int nsplit, int sps, long long n_items) {
+#define LAUNCH(R, T)                                                                                                      \
+  hipLaunchKernelGGL((k_mm_wave_tile<DT, SPARSE, R, T>), grid, dim3(256), 0, st, A, meta, Xf, Y, partial, M, N, Mp, Np, Kp, \
+                     nsplit, sps, n_items)
+  if (v.rt == 1 && v.tt == 1) LAUNCH(1, 1);
+  else if (v.rt == 2 && v.tt == 1) LAUNCH(2, 1);
+  else if (v.rt == 4 && v.tt == 1) LAUNCH(4, 1);
+  else if (v.rt == 2 && v.tt == 2) LAUNCH(2, 2);
+  else if (v.rt == 4 && v.tt == 2) LAUNCH(4, 2);
+  else LAUNCH(4, 4);
+#undef LAUNCH
+}
+
+int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, const void* w, const int32_t* perm,
+                      long long N, long long K, int dtype, void* Yv, void* workspace, int variant) {
+  hipStream_t st = ctx->stream;
+  const long long Mp = esp_round_up(M, 16), Np = esp_round_up(N, 16), Kp = esp_round_up(K, 256);
+  unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+  uint4* Xf = reinterpret_cast<uint4*>(ws + WS_HEADER_BYTES);
+  size_t xbytes = ((size_t)Mp * Kp * 2 + 255) / 256 * 256;
+  float* partial = reinterpret_cast<float*>(ws + WS_HEADER_BYTES + xbytes);
+  uint16_t* Y = reinterpret_cast<uint16_t*>(Yv);
+
+  // 1. stage the activations (re-ordered through theta, fragment-major)
+  {
+    const long long units = Mp * Kp / 8;
+    hipLaunchKernelGGL(k_gather_x, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, st, reinterpret_cast<const uint16_t*>(X), perm,
+                       M, K, Kp, units, Xf);
+    ESP_HIP(ctx, hipGetLastError());
+  }
+  // 2. the product
+  const Variant& v = kVariants[variant];
+  const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
+  const long long nrb = (nrt + v.rt - 1) / v.rt, ntb = (ntt + v.tt - 1) / v.tt;
+  int nsplit = 1;
+  if (v.split_mode == 1) {
+    // enough waves for ~8 per CU (256 CUs), splits of at least 4 steps (256 channels)
+    long long want = (256 * 8 + nrb * ntb - 1) / (nrb * ntb);
+    long long maxs = nks / 4;
+    nsplit = (int)std::max<long long>(1, std::min<long long>(std::min<long long>(want, maxs), MAX_SPLIT));
+  }
+  long long sps = (nks + nsplit - 1) / nsplit;
+  sps = (sps + 3) / 4 * 4;
+  nsplit = (int)((nks + sps - 1) / sps);
+  const long long n_items = nrb * ntb * nsplit;
+  dim3 grid((unsigned)((n_items + 3) / 4));
+  const uint4* A = reinterpret_cast<const uint4*>(w);
+  const uint2* meta = sparse ? reinterpret_cast<const uint2*>(reinterpret_cast<const unsigned char*>(w) + (size_t)Np * Kp) : nullptr;
+  if (dtype == ESPARSE_F16) {
+    if (sparse) launch_wave_tile<ESPARSE_F16, 1>(v, grid, st, A, meta, Xf, Y, partial, M, N, Mp, Np, Kp, nsplit, (int)sps, n_items);
+    else launch_wave_tile<ESPARSE_F16, 0>(v, grid, st, A, meta, Xf, Y, partial, M, N, Mp, Np, Kp, nsplit, (int)sps, n_items);
+  } else {
+    if (sparse) launch_wave_tile<ESPARSE_BF16, 1>(v, grid, st, A, meta, Xf, Y, partial, M, N, Mp, Np, Kp, nsplit, (int)sps, n_items);
+    else launch_wave_tile<ESPARSE_BF16, 0>(v, grid, st, A, meta, Xf, Y, partial, M, N, Mp, Np, Kp, nsplit, (int)sps, n_items);
+  }
+  ESP_HIP(ctx, hipGetLastError());
+  // 3. add the K splits in order
+  if (nsplit > 1) {
+    const long long e = M * (Np / 4);
+    if (dtype == ESPARSE_F16)
+      hipLaunchKernelGGL(k_reduce_splits<ESPARSE_F16>, dim3((unsigned)((e + 255) / 256)), dim3(256), 0, st, partial, nsplit, M, N, Mp, Np, Y);
+    else
+      hipLaunchKernelGGL(k_reduce_splits<ESPARSE_BF16>, dim3((unsigned)((e + 255) / 256)), dim3(256), 0, st, partial, nsplit, M, N, Mp, Np, Y);
+    ESP_HIP(ctx, hipGetLastError());
+  }
+  return ESPARSE_OK;
+}

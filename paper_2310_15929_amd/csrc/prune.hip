@@ -1,0 +1,670 @@
+// Offline pruning stage on the GPU: channel statistics (Section 3.2, eq. 1-2), pruning metric
+// (eq. 3), global naive shuffle and local block shuffle (Section 3.3, Algorithm 1), n:m mask.
+//
+// Everything that decides an integer (a bin, a rank, an exchange, a kept position) is computed so
+// that the result does not depend on the order in which threads run:
+//   - histogram counts, minima and maxima are integer / ordered-integer atomics;
+//   - sums of squares and column sums of |w| are accumulated EXACTLY: every term is split by its
+//     binary exponent into one of a few 64-bit integer accumulators (16 exponents per accumulator),
+//     and the host adds the accumulators exactly and rounds once;
+//   - the retained metric of a candidate group is summed over the output rows 0..N-1 by ONE thread,
+//     in that order, in float64 without contraction;
+//   - logs, square roots and the sort of K channel means run on the host (K values each).
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <numeric>
+
+#include "common.h"
+
+// ------------------------------------------------------------------------------------------------
+// exact exponent-binned accumulation
+// ------------------------------------------------------------------------------------------------
+// squares of 16-bit values: exponent in [-266, 255], at most 22 significant bits
+#define SQ_NB 33
+#define SQ_EOFF 272
+#define SQ_SIG 21
+// |w|: exponent in [-133, 127], at most 11 significant bits
+#define AB_NB 17
+#define AB_EOFF 144
+#define AB_SIG 10
+
+__device__ __forceinline__ void exact_bin(double v, int eoff, int sig, int* bin, unsigned long long* q) {
+  // v > 0 finite.  bin = floor((e + eoff) / 16); q = v / 2^(16 bin - eoff - sig), an exact integer.
+  int e = ilogb(v);
+  int b = (e + eoff) >> 4;
+  *bin = b;
+  *q = (unsigned long long)ldexp(v, -(16 * b - eoff - sig));
+}
+
+__device__ __forceinline__ unsigned int ordered_bits(float f) {
+  unsigned int u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+static inline float from_ordered_bits(unsigned int o) {
+  unsigned int u = (o & 0x80000000u) ? (o & 0x7fffffffu) : ~o;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+// ------------------------------------------------------------------------------------------------
+// pass A: per-channel min / max.  grid (ceil(K/512), row chunks), block 256; thread <-> 2 channels
+// ------------------------------------------------------------------------------------------------
+template <int DT>
+__global__ void __launch_bounds__(256) k_minmax(const uint16_t* __restrict__ X, long long T, long long K,
+                                                 long long rows_per_block, unsigned int* __restrict__ omin,
+                                                 unsigned int* __restrict__ omax) {
+  long long c = ((long long)blockIdx.x * 256 + threadIdx.x) * 2;
+  if (c >= K) return;
+  long long r0 = (long long)blockIdx.y * rows_per_block;
+  long long r1 = r0 + rows_per_block < T ? r0 + rows_per_block : T;
+  float lo0 = INFINITY, hi0 = -INFINITY, lo1 = INFINITY, hi1 = -INFINITY;
+  for (long long r = r0; r < r1; r++) {
+    uint32_t two = *reinterpret_cast<const uint32_t*>(X + r * K + c);
+    float a = esp_to_float<DT>((uint16_t)(two & 0xffffu)), b = esp_to_float<DT>((uint16_t)(two >> 16));
+    lo0 = fminf(lo0, a);
+    hi0 = fmaxf(hi0, a);
+    lo1 = fminf(lo1, b);
+    hi1 = fmaxf(hi1, b);
+  }
+  if (r1 > r0) {
+    atomicMin(&omin[c], ordered_bits(lo0));
+    atomicMax(&omax[c], ordered_bits(hi0));
+    atomicMin(&omin[c + 1], ordered_bits(lo1));
+    atomicMax(&omax[c + 1], ordered_bits(hi1));
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// pass B: histogram over [min, max] and exact sum of squares.
+// grid (ceil(K/64), row chunks), block 256 = 8 row lanes x 32 channel pairs
+// ------------------------------------------------------------------------------------------------
+template <int DT>
+__global__ void __launch_bounds__(256) k_hist_sumsq(const uint16_t* __restrict__ X, long long T, long long K,
+                                                     long long rows_per_block, int bins,
+                                                     const float* __restrict__ cmin, const float* __restrict__ cmax,
+                                                     unsigned int* __restrict__ hist /*[K][bins]*/,
+                                                     unsigned long long* __restrict__ sq /*[K][SQ_NB]*/,
+                                                     int want_hist, int want_sq) {
+  extern __shared__ unsigned char smem_raw[];
+  unsigned long long* s_sq = reinterpret_cast<unsigned long long*>(smem_raw);           // [64][SQ_NB]
+  unsigned int* s_hist = reinterpret_cast<unsigned int*>(smem_raw + 64 * SQ_NB * 8);    // [64][bins]
+  const int tid = threadIdx.x;
+  for (int i = tid; i < 64 * SQ_NB; i += 256) s_sq[i] = 0ull;
+  for (int i = tid; i < 64 * bins; i += 256) s_hist[i] = 0u;
+  __syncthreads();
+  const int cp = tid & 31, rl = tid >> 5;
+  const long long c = (long long)blockIdx.x * 64 + cp * 2;
+  if (c < K) {
+    const double lo0 = (double)cmin[c], hi0 = (double)cmax[c];
+    const double lo1 = (double)cmin[c + 1], hi1 = (double)cmax[c + 1];
+    const double w0 = hi0 - lo0, w1 = hi1 - lo1;
+    const double nb = (double)bins;
+    long long r0 = (long long)blockIdx.y * rows_per_block;
+    long long r1 = r0 + rows_per_block < T ? r0 + rows_per_block : T;
+    for (long long r = r0 + rl; r < r1; r += 8) {
+      uint32_t two = *reinterpret_cast<const uint32_t*>(X + r * K + c);
+      double x[2] = {(double)esp_to_float<DT>((uint16_t)(two & 0xffffu)), (double)esp_to_float<DT>((uint16_t)(two >> 16))};
+#pragma unroll
+      for (int h = 0; h < 2; h++) {
+        const int lc = cp * 2 + h;
+        if (want_hist) {
+          const double lo = h ? lo1 : lo0, w = h ? w1 : w0;
+          int b = 0;
+          if (w > 0.0) {
+            double d = (x[h] - lo) * nb / w;
+            b = (int)floor(d);
+            if (b > bins - 1) b = bins - 1;
+          }
+          atomicAdd(&s_hist[lc * bins + b], 1u);
+        }
+        if (want_sq) {
+          double v = x[h] * x[h];
+          if (v > 0.0) {
+            int bi;
+            unsigned long long q;
+            exact_bin(v, SQ_EOFF, SQ_SIG, &bi, &q);
+            atomicAdd(&s_sq[lc * SQ_NB + bi], q);
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();
+  const long long cbase = (long long)blockIdx.x * 64;
+  if (want_hist)
+    for (int i = tid; i < 64 * bins; i += 256) {
+      long long ch = cbase + i / bins;
+      unsigned int v = s_hist[i];
+      if (ch < K && v) atomicAdd(&hist[ch * bins + (i % bins)], v);
+    }
+  if (want_sq)
+    for (int i = tid; i < 64 * SQ_NB; i += 256) {
+      long long ch = cbase + i / SQ_NB;
+      unsigned long long v = s_sq[i];
+      if (ch < K && v) atomicAdd(&sq[ch * SQ_NB + (i % SQ_NB)], v);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// exact column sums of |W|: grid (ceil(K/64), row chunks), block 256 = 8 row lanes x 32 channel pairs
+// ------------------------------------------------------------------------------------------------
+template <int DT>
+__global__ void __launch_bounds__(256) k_abs_colsum(const uint16_t* __restrict__ W, long long N, long long K,
+                                                     long long rows_per_block, unsigned long long* __restrict__ out /*[K][AB_NB]*/) {
+  __shared__ unsigned long long s_acc[64 * AB_NB];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < 64 * AB_NB; i += 256) s_acc[i] = 0ull;
+  __syncthreads();
+  const int cp = tid & 31, rl = tid >> 5;
+  const long long c = (long long)blockIdx.x * 64 + cp * 2;
+  if (c < K) {
+    long long r0 = (long long)blockIdx.y * rows_per_block;
+    long long r1 = r0 + rows_per_block < N ? r0 + rows_per_block : N;
+    for (long long r = r0 + rl; r < r1; r += 8) {
+      uint32_t two = *reinterpret_cast<const uint32_t*>(W + r * K + c);
+      double x[2] = {fabs((double)esp_to_float<DT>((uint16_t)(two & 0xffffu))), fabs((double)esp_to_float<DT>((uint16_t)(two >> 16)))};
+#pragma unroll
+      for (int h = 0; h < 2; h++)
+        if (x[h] > 0.0) {
+          int bi;
+          unsigned long long q;
+          exact_bin(x[h], AB_EOFF, AB_SIG, &bi, &q);
+          atomicAdd(&s_acc[(cp * 2 + h) * AB_NB + bi], q);
+        }
+    }
+  }
+  __syncthreads();
+  const long long cbase = (long long)blockIdx.x * 64;
+  for (int i = tid; i < 64 * AB_NB; i += 256) {
+    long long ch = cbase + i / AB_NB;
+    unsigned long long v = s_acc[i];
+    if (ch < K && v) atomicAdd(&out[ch * AB_NB + (i % AB_NB)], v);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host driver of the statistics
+// ------------------------------------------------------------------------------------------------
+int esp_stats_device(esparse_ctx* ctx, const void* calib, long long T, long long K, int dtype, int bins,
+                     std::vector<double>* ir, std::vector<double>* am) {
+  if (!ir && !am) return ESPARSE_OK;
+  hipStream_t st = ctx->stream;
+  DevBuf dmin, dmax, dhist, dsq;
+  if (dmin.alloc(K * 4) != hipSuccess || dmax.alloc(K * 4) != hipSuccess ||
+      dhist.alloc((size_t)K * bins * 4) != hipSuccess || dsq.alloc((size_t)K * SQ_NB * 8) != hipSuccess)
+    return esp_fail(ctx, ESPARSE_ENOMEM, "scratch allocation for channel statistics failed");
+  ESP_HIP(ctx, hipMemsetAsync(dmin.p, 0xff, K * 4, st));
+  ESP_HIP(ctx, hipMemsetAsync(dmax.p, 0x00, K * 4, st));
+  ESP_HIP(ctx, hipMemsetAsync(dhist.p, 0, (size_t)K * bins * 4, st));
+  ESP_HIP(ctx, hipMemsetAsync(dsq.p, 0, (size_t)K * SQ_NB * 8, st));
+  const uint16_t* X = reinterpret_cast<const uint16_t*>(calib);
+  std::vector<float> hmin((size_t)K), hmax((size_t)K);
+  if (ir) {
+    long long rpb = std::max<long long>(64, (T + 63) / 64);
+    dim3 grid((unsigned)((K + 511) / 512), (unsigned)((T + rpb - 1) / rpb));
+    if (dtype == ESPARSE_F16)
+      hipLaunchKernelGGL(k_minmax<ESPARSE_F16>, grid, dim3(256), 0, st, X, T, K, rpb, dmin.as<unsigned int>(), dmax.as<unsigned int>());
+    else
+      hipLaunchKernelGGL(k_minmax<ESPARSE_BF16>, grid, dim3(256), 0, st, X, T, K, rpb, dmin.as<unsigned int>(), dmax.as<unsigned int>());
+    ESP_HIP(ctx, hipGetLastError());
+    std::vector<unsigned int> omin((size_t)K), omax((size_t)K);
+    ESP_HIP(ctx, hipMemcpyAsync(omin.data(), dmin.p, K * 4, hipMemcpyDeviceToHost, st));
+    ESP_HIP(ctx, hipMemcpyAsync(omax.data(), dmax.p, K * 4, hipMemcpyDeviceToHost, st));
+    ESP_HIP(ctx, hipStreamSynchronize(st));
+    for (long long c = 0; c < K; c++) {
+      hmin[c] = from_ordered_bits(omin[c]);
+      hmax[c] = from_ordered_bits(omax[c]);
+    }
+    // reuse the two buffers for the float bounds
+    ESP_HIP(ctx, hipMemcpyAsync(dmin.p, hmin.data(), K * 4, hipMemcpyHostToDevice, st));
+    ESP_HIP(ctx, hipMemcpyAsync(dmax.p, hmax.data(), K * 4, hipMemcpyHostToDevice, st));
+  }
+  {
+    long long nchunk = std::max<long long>(1, std::min<long long>(T / 256, 2048 / std::max<long long>(1, (K + 63) / 64) + 1));
+    long long rpb = (T + nchunk - 1) / nchunk;
+    rpb = (rpb + 7) / 8 * 8;
+    dim3 grid((unsigned)((K + 63) / 64), (unsigned)((T + rpb - 1) / rpb));
+    size_t smem = (size_t)64 * SQ_NB * 8 + (size_t)64 * bins * 4;
+    if (smem > 48 * 1024) {
+      ESP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist_sumsq<ESPARSE_F16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      ESP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist_sumsq<ESPARSE_BF16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    }
+    if (dtype == ESPARSE_F16)
+      hipLaunchKernelGGL(k_hist_sumsq<ESPARSE_F16>, grid, dim3(256), smem, st, X, T, K, rpb, bins, dmin.as<float>(),
+                         dmax.as<float>(), dhist.as<unsigned int>(), dsq.as<unsigned long long>(), ir ? 1 : 0, am ? 1 : 0);
+    else
+      hipLaunchKernelGGL(k_hist_sumsq<ESPARSE_BF16>, grid, dim3(256), smem, st, X, T, K, rpb, bins, dmin.as<float>(),
+                         dmax.as<float>(), dhist.as<unsigned int>(), dsq.as<unsigned long long>(), ir ? 1 : 0, am ? 1 : 0);
+    ESP_HIP(ctx, hipGetLastError());
+  }
+  std::vector<unsigned int> hist;
+  std::vector<unsigned long long> sq;
+  if (ir) {
+    hist.resize((size_t)K * bins);
+    ESP_HIP(ctx, hipMemcpyAsync(hist.data(), dhist.p, hist.size() * 4, hipMemcpyDeviceToHost, st));
+  }
+  if (am) {
+    sq.resize((size_t)K * SQ_NB);
+    ESP_HIP(ctx, hipMemcpyAsync(sq.data(), dsq.p, sq.size() * 8, hipMemcpyDeviceToHost, st));
+  }
+  ESP_HIP(ctx, hipStreamSynchronize(st));
+  if (ir) {
+    // eq. 1: IR_c = - sum_k p_k ln p_k, ascending k, empty bins skipped
+    ir->assign((size_t)K, 0.0);
+    for (long long c = 0; c < K; c++) {
+      double acc = 0.0;
+      for (int k = 0; k < bins; k++) {
+        unsigned int nk = hist[(size_t)c * bins + k];
+        if (nk) {
+          double p = (double)nk / (double)T;
+          double t = p * std::log(p);
+          acc = acc + t;
+        }
+      }
+      (*ir)[c] = -acc;
+    }
+  }
+  if (am) {
+    // eq. 2: AM_c = sqrt(exact sum of squares rounded once)
+    am->assign((size_t)K, 0.0);
+    for (long long c = 0; c < K; c++)
+      (*am)[c] = std::sqrt(esp_exact_bins_to_double(&sq[(size_t)c * SQ_NB], SQ_NB, -SQ_EOFF - SQ_SIG));
+  }
+  return ESPARSE_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// local block shuffle
+// ------------------------------------------------------------------------------------------------
+// Panel: P[j][p] = |W[j, theta0[p]]| as raw 16-bit magnitudes, p in GNS order (so the B channels of a
+// block are contiguous in every row).
+template <int DT>
+__global__ void __launch_bounds__(256) k_build_panel(const uint16_t* __restrict__ W, const int32_t* __restrict__ theta0,
+                                                      long long N, long long K, uint16_t* __restrict__ P) {
+  long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= N * K) return;
+  long long j = e / K, p = e % K;
+  P[e] = W[j * K + theta0[p]] & 0x7fffu;
+}
+
+template <int NKEEP, int MG>
+__device__ __forceinline__ double top_n_sum(double* v) {
+  // the NKEEP largest of v[0..MG), added largest first
+#pragma unroll
+  for (int a = 0; a < NKEEP; a++) {
+#pragma unroll
+    for (int b = MG - 1; b > a; b--) {
+      // bubble the maximum of v[a..MG) to v[a]
+      double hi = fmax(v[b - 1], v[b]), lo = fmin(v[b - 1], v[b]);
+      v[b - 1] = hi;
+      v[b] = lo;
+    }
+  }
+  double t = v[0];
+#pragma unroll
+  for (int a = 1; a < NKEEP; a++) t = t + v[a];
+  return t;
+}
+
+// V[blk][g][i][x] = retained metric of group g of block blk with its i-th member replaced by panel
+// column x of the block (x == the member itself gives v(g)); rows summed in order by one thread.
+// grid (entries / 256, blocks), block 256.  `groups` = list of 2 group numbers per block to refresh
+// (or NULL = all groups).  Entries whose x sits in group g (other than the member itself) are skipped.
+template <int DT, int NKEEP, int MG>
+__global__ void __launch_bounds__(256) k_lbs_eval(const uint16_t* __restrict__ P, const double* __restrict__ sp /*[K] score in panel order*/,
+                                                   const int* __restrict__ lp /*[nblk][B] position -> panel column*/,
+                                                   const int* __restrict__ groups /*[nblk][2] or null*/,
+                                                   const int* __restrict__ done /*[nblk]*/, long long N, long long K, int B,
+                                                   int rows_chunk, double* __restrict__ V /*[nblk][G][MG][B]*/) {
+  extern __shared__ unsigned char smem_raw[];
+  double* s_xi = reinterpret_cast<double*>(smem_raw);  // [rows_chunk][B]
+  __shared__ int s_lp[256];
+  const int blk = blockIdx.y;
+  if (done[blk]) return;
+  const int G = B / MG;
+  const int tid = threadIdx.x;
+  const int eid = blockIdx.x * 256 + tid;  // entry within this block's refresh list
+  const int per_group = MG * B;
+  const int ngroups = groups ? 2 : G;
+  for (int i = tid; i < B; i += 256) s_lp[i] = lp[blk * B + i];
+  __syncthreads();
+  bool active = eid < ngroups * per_group;
+  int g = 0, i = 0, x = 0;
+  int cols[MG];
+  if (active) {
+    int gsel = eid / per_group;
+    g = groups ? groups[blk * 2 + gsel] : gsel;
+    i = (eid / B) % MG;
+    x = eid % B;
+    if (g < 0) active = false;
+  }
+  if (active) {
+    bool in_group = false;
+#pragma unroll
+    for (int k = 0; k < MG; k++) {
+      int ck = s_lp[g * MG + k];
+      if (ck == x && k != i) in_group = true;
+      cols[k] = (k == i) ? x : ck;
+    }
+    if (in_group) active = false;
+  }
+  const uint16_t* Pb = P + (long long)blk * B;
+  const double* spb = sp + (long long)blk * B;
+  double acc = 0.0;
+  for (long long r0 = 0; r0 < N; r0 += rows_chunk) {
+    const int nr = (int)((N - r0) < rows_chunk ? (N - r0) : rows_chunk);
+    __syncthreads();
+    for (int e = tid; e < nr * B; e += 256) {
+      int rr = e / B, cc = e % B;
+      s_xi[e] = (double)esp_to_float<DT>(Pb[(r0 + rr) * K + cc]) * spb[cc];
+    }
+    __syncthreads();
+    if (active) {
+      for (int rr = 0; rr < nr; rr++) {
+        double v[MG];
+#pragma unroll
+        for (int k = 0; k < MG; k++) v[k] = s_xi[rr * B + cols[k]];
+        acc = acc + top_n_sum<NKEEP, MG>(v);
+      }
+    }
+  }
+  if (active) V[(((long long)blk * G + g) * MG + i) * B + x] = acc;
+}
+
+// One workgroup per block: best exchange (largest delta, ties -> smallest (i, j)), applied if delta > 0.
+template <int MG>
+__global__ void __launch_bounds__(256) k_lbs_select(const double* __restrict__ V, int* __restrict__ lp, int* __restrict__ groups,
+                                                     int* __restrict__ done, long long* __restrict__ swaps, long long max_swaps,
+                                                     int B, int* __restrict__ n_active) {
+  const int blk = blockIdx.x;
+  if (done[blk]) return;
+  const int G = B / MG;
+  const int tid = threadIdx.x;
+  __shared__ int s_lp[256];
+  __shared__ double s_best[256];
+  __shared__ int s_pair[256];
+  for (int i = tid; i < B; i += 256) s_lp[i] = lp[blk * B + i];
+  __syncthreads();
+  const double* Vb = V + (long long)blk * G * MG * B;
+  double best = 0.0;
+  int best_pair = -1;
+  for (int pid = tid; pid < B * B; pid += 256) {  // pid = i * B + j, ascending per thread
+    int i = pid / B, j = pid % B;
+    int a = i / MG, b = j / MG;
+    if (j <= i || a == b) continue;
+    double va2 = Vb[((a * MG) + (i % MG)) * B + s_lp[j]];
+    double vb2 = Vb[((b * MG) + (j % MG)) * B + s_lp[i]];
+    double va = Vb[(a * MG) * B + s_lp[a * MG]];
+    double vb = Vb[(b * MG) * B + s_lp[b * MG]];
+    double delta = (va2 + vb2) - (va + vb);
+    if (delta > 0.0 && (best_pair < 0 || delta > best)) {
+      best = delta;
+      best_pair = pid;
+    }
+  }
+  s_best[tid] = best;
+  s_pair[tid] = best_pair;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s) {
+      double ob = s_best[tid + s];
+      int op = s_pair[tid + s];
+      int mp = s_pair[tid];
+      if (op >= 0 && (mp < 0 || ob > s_best[tid] || (ob == s_best[tid] && op < mp))) {
+        s_best[tid] = ob;
+        s_pair[tid] = op;
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    int pr = s_pair[0];
+    if (pr < 0) {
+      done[blk] = 1;
+      atomicSub(n_active, 1);
+    } else {
+      int i = pr / B, j = pr % B;
+      int ci = s_lp[i], cj = s_lp[j];
+      lp[blk * B + i] = cj;
+      lp[blk * B + j] = ci;
+      groups[blk * 2 + 0] = i / MG;
+      groups[blk * 2 + 1] = j / MG;
+      long long sw = swaps[blk] + 1;
+      swaps[blk] = sw;
+      if (max_swaps > 0 && sw >= max_swaps) {
+        done[blk] = 1;
+        atomicSub(n_active, 1);
+      }
+    }
+  }
+}
+
+__global__ void k_lbs_init(int* lp, int* done, long long* swaps, int nblk, int B) {
+  int t = blockIdx.x * 256 + threadIdx.x;
+  if (t < nblk * B) lp[t] = t % B;
+  if (t < nblk) {
+    done[t] = 0;
+    swaps[t] = 0;
+  }
+}
+
+__global__ void k_lbs_final_theta(const int32_t* theta0, const int* lp, int B, long long K, int32_t* theta) {
+  long long p = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (p >= K) return;
+  long long blk = p / B;
+  theta[p] = theta0[blk * B + lp[p]];
+}
+
+// ------------------------------------------------------------------------------------------------
+// n:m mask on the final order, one thread per (row, group); ties -> lower position kept
+// ------------------------------------------------------------------------------------------------
+template <int DT, int NKEEP, int MG>
+__global__ void __launch_bounds__(256) k_nm_mask(const uint16_t* __restrict__ W, const double* __restrict__ s /*original order*/,
+                                                  const int32_t* __restrict__ theta, long long N, long long K,
+                                                  uint8_t* __restrict__ mask) {
+  const long long ng = K / MG;
+  long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= N * ng) return;
+  long long j = e / ng, g = e % ng;
+  double xi[MG];
+#pragma unroll
+  for (int k = 0; k < MG; k++) {
+    int c = theta[g * MG + k];
+    xi[k] = fabs((double)esp_to_float<DT>(W[j * K + c])) * s[c];
+  }
+  uint8_t out[MG];
+#pragma unroll
+  for (int k = 0; k < MG; k++) {
+    int ahead = 0;
+#pragma unroll
+    for (int q = 0; q < MG; q++) ahead += (xi[q] > xi[k] || (xi[q] == xi[k] && q < k)) ? 1 : 0;
+    out[k] = ahead < NKEEP ? 1 : 0;
+  }
+  uint8_t* dst = mask + j * K + g * MG;
+  if (MG == 4) {
+    *reinterpret_cast<uint32_t*>(dst) = (uint32_t)out[0] | ((uint32_t)out[1] << 8) | ((uint32_t)out[2] << 16) | ((uint32_t)out[3] << 24);
+  } else {
+#pragma unroll
+    for (int k = 0; k < MG; k++) dst[k] = out[k];
+  }
+}
+
+// retained metric of every group under the final order (eq. 5 terms), rows summed in order
+template <int DT, int NKEEP, int MG>
+__global__ void __launch_bounds__(64) k_group_values(const uint16_t* __restrict__ W, const double* __restrict__ s,
+                                                      const int32_t* __restrict__ theta, long long N, long long K,
+                                                      double* __restrict__ out) {
+  long long g = (long long)blockIdx.x * 64 + threadIdx.x;
+  if (g >= K / MG) return;
+  int c[MG];
+  double sc[MG];
+#pragma unroll
+  for (int k = 0; k < MG; k++) {
+    c[k] = theta[g * MG + k];
+    sc[k] = s[c[k]];
+  }
+  double acc = 0.0;
+  for (long long j = 0; j < N; j++) {
+    double v[MG];
+#pragma unroll
+    for (int k = 0; k < MG; k++) v[k] = fabs((double)esp_to_float<DT>(W[j * K + c[k]])) * sc[k];
+    acc = acc + top_n_sum<NKEEP, MG>(v);
+  }
+  out[g] = acc;
+}
+
+// ------------------------------------------------------------------------------------------------
+// host driver: GNS -> LBS -> mask
+// ------------------------------------------------------------------------------------------------
+#define DISPATCH_DT_NM(dtype, n, KERNEL, ...)                                      \
+  do {                                                                             \
+    if ((dtype) == ESPARSE_F16 && (n) == 2) KERNEL(ESPARSE_F16, 2, 4, __VA_ARGS__); \
+    else if ((dtype) == ESPARSE_F16) KERNEL(ESPARSE_F16, 4, 8, __VA_ARGS__);        \
+    else if ((n) == 2) KERNEL(ESPARSE_BF16, 2, 4, __VA_ARGS__);                     \
+    else KERNEL(ESPARSE_BF16, 4, 8, __VA_ARGS__);                                   \
+  } while (0)
+
+int esp_prune_device(esparse_ctx* ctx, const double* score, const void* Wv, long long N, long long K, int dtype,
+                     const esparse_prune_opts* o, int32_t* perm_out, uint8_t* mask_out, int64_t* swaps_out,
+                     double* retained_out) {
+  hipStream_t st = ctx->stream;
+  const uint16_t* W = reinterpret_cast<const uint16_t*>(Wv);
+  const int n = o->n_keep, m = o->m_group;
+  const bool use_gns = o->flags & ESPARSE_USE_GNS, use_lbs = o->flags & ESPARSE_USE_LBS;
+  const int B = o->block;
+  const long long nblk = use_lbs ? K / B : 0;
+  if (swaps_out && !use_lbs && o->block > 0 && K % o->block == 0) memset(swaps_out, 0, sizeof(int64_t) * (K / o->block));
+
+  DevBuf d_s;
+  if (d_s.alloc(K * 8) != hipSuccess) return esp_fail(ctx, ESPARSE_ENOMEM, "scratch allocation failed");
+  ESP_HIP(ctx, hipMemcpyAsync(d_s.p, score, K * 8, hipMemcpyHostToDevice, st));
+
+  // ---- global naive shuffle: g_c = (s_c * sum_j |w_jc|) / N, stable descending sort, round-robin deal
+  std::vector<int32_t> theta0((size_t)K);
+  if (use_gns) {
+    DevBuf d_cs;
+    if (d_cs.alloc((size_t)K * AB_NB * 8) != hipSuccess) return esp_fail(ctx, ESPARSE_ENOMEM, "scratch allocation failed");
+    ESP_HIP(ctx, hipMemsetAsync(d_cs.p, 0, (size_t)K * AB_NB * 8, st));
+    long long nchunk = std::max<long long>(1, std::min<long long>(N / 64, 1024 / std::max<long long>(1, (K + 63) / 64) + 1));
+    long long rpb = ((N + nchunk - 1) / nchunk + 7) / 8 * 8;
+    dim3 grid((unsigned)((K + 63) / 64), (unsigned)((N + rpb - 1) / rpb));
+    if (dtype == ESPARSE_F16)
+      hipLaunchKernelGGL(k_abs_colsum<ESPARSE_F16>, grid, dim3(256), 0, st, W, N, K, rpb, d_cs.as<unsigned long long>());
+    else
+      hipLaunchKernelGGL(k_abs_colsum<ESPARSE_BF16>, grid, dim3(256), 0, st, W, N, K, rpb, d_cs.as<unsigned long long>());
+    ESP_HIP(ctx, hipGetLastError());
+    std::vector<unsigned long long> cs((size_t)K * AB_NB);
+    ESP_HIP(ctx, hipMemcpyAsync(cs.data(), d_cs.p, cs.size() * 8, hipMemcpyDeviceToHost, st));
+    ESP_HIP(ctx, hipStreamSynchronize(st));
+    std::vector<double> g((size_t)K);
+    for (long long c = 0; c < K; c++) {
+      double colsum = esp_exact_bins_to_double(&cs[(size_t)c * AB_NB], AB_NB, -AB_EOFF - AB_SIG);
+      double t = score[c] * colsum;
+      g[c] = t / (double)N;
+    }
+    std::vector<int32_t> order((size_t)K);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return g[a] > g[b]; });
+    const long long G = K / m;
+    for (long long r = 0; r < K; r++) theta0[(size_t)((r % G) * m + r / G)] = order[(size_t)r];
+  } else {
+    std::iota(theta0.begin(), theta0.end(), 0);
+  }
+  DevBuf d_theta0;
+  if (d_theta0.alloc(K * 4) != hipSuccess) return esp_fail(ctx, ESPARSE_ENOMEM, "scratch allocation failed");
+  ESP_HIP(ctx, hipMemcpyAsync(d_theta0.p, theta0.data(), K * 4, hipMemcpyHostToDevice, st));
+
+  // ---- local block shuffle
+  if (use_lbs) {
+    const int G = B / m;
+    DevBuf d_P, d_sp, d_lp, d_groups, d_done, d_swaps, d_V, d_nact;
+    std::vector<double> sp((size_t)K);
+    for (long long p = 0; p < K; p++) sp[p] = score[theta0[p]];
+    if (d_P.alloc((size_t)N * K * 2) != hipSuccess || d_sp.alloc(K * 8) != hipSuccess || d_lp.alloc(K * 4) != hipSuccess ||
+        d_groups.alloc(nblk * 8) != hipSuccess || d_done.alloc(nblk * 4) != hipSuccess || d_swaps.alloc(nblk * 8) != hipSuccess ||
+        d_V.alloc((size_t)nblk * G * m * B * 8) != hipSuccess || d_nact.alloc(4) != hipSuccess)
+      return esp_fail(ctx, ESPARSE_ENOMEM, "scratch allocation for the block shuffle failed");
+    ESP_HIP(ctx, hipMemcpyAsync(d_sp.p, sp.data(), K * 8, hipMemcpyHostToDevice, st));
+    {
+      dim3 grid((unsigned)((N * K + 255) / 256));
+      if (dtype == ESPARSE_F16)
+        hipLaunchKernelGGL(k_build_panel<ESPARSE_F16>, grid, dim3(256), 0, st, W, d_theta0.as<int32_t>(), N, K, d_P.as<uint16_t>());
+      else
+        hipLaunchKernelGGL(k_build_panel<ESPARSE_BF16>, grid, dim3(256), 0, st, W, d_theta0.as<int32_t>(), N, K, d_P.as<uint16_t>());
+      ESP_HIP(ctx, hipGetLastError());
+    }
+    hipLaunchKernelGGL(k_lbs_init, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, d_lp.as<int>(), d_done.as<int>(),
+                       d_swaps.as<long long>(), (int)nblk, B);
+    int nact = (int)nblk;
+    ESP_HIP(ctx, hipMemcpyAsync(d_nact.p, &nact, 4, hipMemcpyHostToDevice, st));
+    const int rows_chunk = std::max(1, 4096 / B);
+    const size_t smem = (size_t)rows_chunk * B * 8;
+    bool first = true;
+    long long iter = 0;
+    while (nact > 0) {
+      const int entries = (first ? G : 2) * m * B;
+      dim3 grid((unsigned)((entries + 255) / 256), (unsigned)nblk);
+      const int* grp = first ? nullptr : d_groups.as<int>();
+#define LAUNCH_EVAL(DT, NK, MGv, ...)                                                                                  \
+  hipLaunchKernelGGL((k_lbs_eval<DT, NK, MGv>), grid, dim3(256), smem, st, d_P.as<uint16_t>(), d_sp.as<double>(), d_lp.as<int>(), \
+                     grp, d_done.as<int>(), N, K, B, rows_chunk, d_V.as<double>())
+      DISPATCH_DT_NM(dtype, n, LAUNCH_EVAL, 0);
+#undef LAUNCH_EVAL
+      ESP_HIP(ctx, hipGetLastError());
+      if (m == 4)
+        hipLaunchKernelGGL(k_lbs_select<4>, dim3((unsigned)nblk), dim3(256), 0, st, d_V.as<double>(), d_lp.as<int>(), d_groups.as<int>(),
+                           d_done.as<int>(), d_swaps.as<long long>(), o->max_swaps, B, d_nact.as<int>());
+      else
+        hipLaunchKernelGGL(k_lbs_select<8>, dim3((unsigned)nblk), dim3(256), 0, st, d_V.as<double>(), d_lp.as<int>(), d_groups.as<int>(),
+                           d_done.as<int>(), d_swaps.as<long long>(), o->max_swaps, B, d_nact.as<int>());
+      ESP_HIP(ctx, hipGetLastError());
+      ESP_HIP(ctx, hipMemcpyAsync(&nact, d_nact.p, 4, hipMemcpyDeviceToHost, st));
+      ESP_HIP(ctx, hipStreamSynchronize(st));
+      first = false;
+      if (++iter > (long long)B * B * 64)
+        return esp_fail(ctx, ESPARSE_EHIP, "block shuffle did not terminate after %lld rounds", iter);
+    }
+    hipLaunchKernelGGL(k_lbs_final_theta, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, st, d_theta0.as<int32_t>(), d_lp.as<int>(), B,
+                       K, perm_out);
+    ESP_HIP(ctx, hipGetLastError());
+    if (swaps_out) {
+      ESP_HIP(ctx, hipMemcpyAsync(swaps_out, d_swaps.p, nblk * 8, hipMemcpyDeviceToHost, st));
+    }
+    ESP_HIP(ctx, hipStreamSynchronize(st));
+  } else {
+    ESP_HIP(ctx, hipMemcpyAsync(perm_out, d_theta0.p, K * 4, hipMemcpyDeviceToDevice, st));
+  }
+
+  // ---- n:m mask under the final order
+  {
+    dim3 grid((unsigned)((N * (K / m) + 255) / 256));
+#define LAUNCH_MASK(DT, NK, MGv, ...) \
+  hipLaunchKernelGGL((k_nm_mask<DT, NK, MGv>), grid, dim3(256), 0, st, W, d_s.as<double>(), perm_out, N, K, mask_out)
+    DISPATCH_DT_NM(dtype, n, LAUNCH_MASK, 0);
+#undef LAUNCH_MASK
+    ESP_HIP(ctx, hipGetLastError());
+  }
+  if (retained_out) {
+    DevBuf d_gv;
+    const long long ng = K / m;
+    if (d_gv.alloc(ng * 8) != hipSuccess) return esp_fail(ctx, ESPARSE_ENOMEM, "scratch allocation failed");
+    dim3 grid((unsigned)((ng + 63) / 64));
+#define LAUNCH_GV(DT, NK, MGv, ...) \
+  hipLaunchKernelGGL((k_group_values<DT, NK, MGv>), grid, dim3(64), 0, st, W, d_s.as<double>(), perm_out, N, K, d_gv.as<double>())
+    DISPATCH_DT_NM(dtype, n, LAUNCH_GV, 0);
+#undef LAUNCH_GV
+    ESP_HIP(ctx, hipGetLastError());
+    std::vector<double> gv((size_t)ng);
+    ESP_HIP(ctx, hipMemcpyAsync(gv.data(), d_gv.p, ng * 8, hipMemcpyDeviceToHost, st));
+    ESP_HIP(ctx, hipStreamSynchronize(st));
+    double tot = 0.0;
+    for (long long g = 0; g < ng; g++) tot = tot + gv[g];
+    *retained_out = tot;
+  }
+  ESP_HIP(ctx, hipStreamSynchronize(st));
+  return ESPARSE_OK;
+}

@@ -1,0 +1,321 @@
+"""GPU parity: every stage of the HIP path against the CPU oracle, through the C ABI.
+
+Bar: permutation, mask, statistics, compressed values and metadata bit-exact; products within a
+normwise relative error per output row of 2e-3 (fp16) / 1e-2 (bf16).
+"""
+import hashlib
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import esparse_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float16: 2e-3, torch.bfloat16: 1e-2}
+
+
+@pytest.fixture(scope="module")
+def esp():
+    import paper_2310_15929_amd as esp
+    esp.load_library()
+    return esp
+
+
+@pytest.fixture(scope="module")
+def ctx(esp):
+    assert torch.cuda.is_available()
+    return esp.Context(0)
+
+
+def _np(t: torch.Tensor) -> np.ndarray:
+    t = t.detach().cpu()
+    if t.dtype == torch.bfloat16:
+        return t.float().numpy()
+    return t.numpy()
+
+
+def _bits(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def _rand(shape, dtype, seed, scale=1.0, col_scale=None):
+    return wl.normal_matrix(shape[0], shape[1], wl.stream_id("test", seed), scale=scale, col_scale=col_scale,
+                            dtype=dtype)
+
+
+def _sha(a):
+    return hashlib.sha256(np.ascontiguousarray(a).tobytes()).hexdigest()
+
+
+# ---------------------------------------------------------------- channel statistics
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("T,K", [(256, 512), (1000, 70), (37, 2)])
+def test_channel_stats_bit_exact(ctx, dtype, T, K):
+    scales = np.exp(np.random.default_rng(T + K).standard_normal(K) * 2.0)
+    Xc = _rand((T, K), dtype, 11, col_scale=scales)
+    if K >= 4:
+        Xc[:, 1] = 0.75          # constant channel
+        Xc[:, 3] = 0.0           # all-zero channel
+    print(f"stats T={T} K={K} {dtype}", flush=True)
+    ir, am = ctx.channel_stats(Xc.cuda(), 100)
+    x = _np(Xc)
+    assert (ir == orc.channel_entropy(x, 100)).all()
+    assert (am == orc.channel_amplitude(x)).all()
+
+
+def test_channel_stats_other_bin_counts(ctx):
+    Xc = _rand((512, 16), torch.float16, 12)
+    for bins in (1, 7, 256):
+        ir, _ = ctx.channel_stats(Xc.cuda(), bins)
+        assert (ir == orc.channel_entropy(_np(Xc), bins)).all()
+
+
+# ---------------------------------------------------------------- prune
+def _prune_case(esp, ctx, N, K, T, B, n, m, dtype, flags, seed, max_swaps=0):
+    scales = wl.channel_scales("lognormal", K, wl.stream_id("ps", seed))
+    W = _rand((N, K), dtype, seed, scale=K ** -0.5)
+    Xc = _rand((T, K), dtype, seed + 1, col_scale=scales)
+    alpha = wl.default_alpha(T)
+    opts = esp.PruneOpts(n_keep=n, m_group=m, block=B, bins=100, alpha=alpha, flags=flags, max_swaps=max_swaps)
+    print(f"prune N={N} K={K} T={T} B={B} {n}:{m} {dtype} flags={flags} max_swaps={max_swaps}", flush=True)
+    res = ctx.prune(Xc.cuda(), W.cuda(), opts, want_retained=True)
+    torch.cuda.synchronize()
+    theta, mask, s, swaps = orc.prune(_np(Xc), _np(W), n, m, B, alpha, 100,
+                                      use_entropy=bool(flags & esp.USE_ENTROPY), use_norm=bool(flags & esp.USE_NORM),
+                                      use_gns=bool(flags & esp.USE_GNS), use_lbs=bool(flags & esp.USE_LBS),
+                                      max_swaps=max_swaps)
+    assert (res.score == s).all(), "scores differ"
+    assert (res.perm.cpu().numpy() == theta).all(), "theta differs"
+    if flags & esp.USE_LBS:
+        assert (res.swaps == swaps).all(), "swap counts differ"
+    assert (res.mask.cpu().numpy() == mask).all(), "mask differs"
+    assert res.retained == orc.retained_metric(_np(W), s, theta, n, m)
+    return res, W, Xc, theta, mask, s
+
+
+@pytest.mark.parametrize("n,m,B", [(2, 4, 32), (2, 4, 64), (4, 8, 32)])
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+def test_prune_bit_exact(esp, ctx, n, m, B, dtype):
+    _prune_case(esp, ctx, 96, 128, 200, B, n, m, dtype, esp.USE_ALL, 21)
+
+
+def test_prune_ablation_switches(esp, ctx):
+    for flags in (esp.USE_NORM, esp.USE_NORM | esp.USE_ENTROPY, esp.USE_NORM | esp.USE_ENTROPY | esp.USE_GNS,
+                  esp.USE_ENTROPY | esp.USE_LBS):
+        _prune_case(esp, ctx, 64, 64, 128, 32, 2, 4, torch.float16, flags, 22)
+
+
+def test_prune_max_swaps_and_ties(esp, ctx):
+    _prune_case(esp, ctx, 48, 64, 64, 32, 2, 4, torch.float16, esp.USE_ALL, 23, max_swaps=3)
+    # heavy ties: weights on a coarse grid, scores given
+    N, K, B = 40, 64, 32
+    rng = np.random.default_rng(5)
+    W = torch.tensor(rng.integers(-3, 4, size=(N, K)) * 0.25, dtype=torch.float16)
+    s = rng.integers(1, 4, size=K).astype(np.float64)
+    opts = esp.PruneOpts(block=B, alpha=1.0)
+    res = ctx.prune(None, W.cuda(), opts, score=s)
+    theta0 = orc.global_naive_shuffle(W.numpy(), s, 4)
+    theta, swaps = orc.local_block_shuffle_vectorised(W.numpy(), s, theta0, 2, 4, B)
+    assert (res.perm.cpu().numpy() == theta).all() and (res.swaps == swaps).all()
+    assert (res.mask.cpu().numpy() == orc.nm_mask(W.numpy(), s, theta, 2, 4)).all()
+
+
+def test_config1_against_stored_oracle_results(esp, ctx):
+    """Workload configuration 1, complete, against results the oracle wrote to tests/golden."""
+    gold = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "cfg1_oracle.json")))
+    W = wl.weights(1, "linear")
+    Xc = wl.calibration(1, "linear")
+    X = wl.activations(1, "linear", 16)
+    assert _sha(W.numpy()) == gold["inputs_sha256"]["W"] and _sha(Xc.numpy()) == gold["inputs_sha256"]["Xc"]
+    opts = esp.PruneOpts(block=64, alpha=gold["alpha"])
+    print("config 1 prune", flush=True)
+    res = ctx.prune(Xc.cuda(), W.cuda(), opts, want_retained=True)
+    assert res.perm.cpu().tolist() == gold["theta"]
+    assert res.swaps.tolist() == gold["swaps"]
+    assert _sha(res.score) == gold["score_sha256"]
+    assert _sha(res.mask.cpu().numpy()) == gold["mask_sha256"]
+    assert res.retained == gold["retained"]
+    comp = ctx.compress(W.cuda(), res.mask, res.perm)
+    assert _sha(_bits(comp.values)) == gold["values_sha256"]
+    assert _sha(comp.meta.cpu().numpy()) == gold["meta_sha256"]
+    Np_Kp = 512 * 512
+    nat = comp.native.cpu().numpy()
+    assert _sha(nat[:Np_Kp]) == gold["native_values_sha256"] and _sha(nat[Np_Kp:]) == gold["native_meta_sha256"]
+    theta = np.array(gold["theta"])
+    mask = res.mask.cpu().numpy()
+    Yref = orc.spmm_ref(X.numpy(), W.numpy(), theta, mask)
+    for v in range(esp.num_variants()):
+        Y = ctx.spmm(X.cuda(), comp, res.perm, variant=v)
+        err = orc.rowwise_rel_error(_np(Y), Yref)
+        assert err.max() <= 2e-3, (esp.variant_name(v), err.max())
+
+
+# ---------------------------------------------------------------- compression
+@pytest.mark.parametrize("N,K", [(24, 320), (16, 256), (5, 36), (130, 1040)])
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+def test_compress_2_4_bit_exact(esp, ctx, N, K, dtype):
+    W = _rand((N, K), dtype, 31)
+    rng = np.random.default_rng(N * K)
+    s = np.abs(rng.standard_normal(K)) + 0.1
+    theta = rng.permutation(K)
+    mask = orc.nm_mask_vectorised(_np(W), s, theta, 2, 4)
+    print(f"compress N={N} K={K} {dtype}", flush=True)
+    comp = ctx.compress(W.cuda(), torch.tensor(mask).cuda(), torch.tensor(theta, dtype=torch.int32).cuda())
+    Wb = _bits(W).reshape(N, K)
+    values, meta = orc.compress_vectorised(Wb, theta, mask, 2, 4)        # on raw 16-bit patterns
+    assert (_bits(comp.values).reshape(values.shape) == values).all()
+    assert (comp.meta.cpu().numpy().view(np.uint32).reshape(meta.shape) == meta).all()
+    nv, nm = orc.native_tiling(values, meta, N, K)
+    nat = comp.native.cpu().numpy()
+    assert nat.size == esp.compressed_size(N, K, 2, 4)[2]
+    assert (nat[:nv.nbytes].view(np.uint16) == nv).all()
+    assert (nat[nv.nbytes:].view(np.uint16) == nm).all()
+
+
+def test_compress_4_8_and_derived_mask_and_errors(esp, ctx):
+    N, K = 20, 64
+    W = _rand((N, K), torch.float16, 32)
+    rng = np.random.default_rng(9)
+    s = np.abs(rng.standard_normal(K)) + 0.1
+    theta = rng.permutation(K)
+    mask = orc.nm_mask_vectorised(_np(W), s, theta, 4, 8)
+    th = torch.tensor(theta, dtype=torch.int32).cuda()
+    comp = ctx.compress(W.cuda(), torch.tensor(mask).cuda(), th, 4, 8)
+    values, meta = orc.compress_vectorised(_bits(W).reshape(N, K), theta, mask, 4, 8)
+    assert (_bits(comp.values).reshape(values.shape) == values).all()
+    assert (comp.meta.cpu().numpy().reshape(meta.shape) == meta).all()
+    assert comp.native is None
+    # mask = NULL: the mask is read off the zeros of an already pruned weight
+    for n, m in ((2, 4), (4, 8)):
+        mk = orc.nm_mask_vectorised(_np(W), s, theta, n, m)
+        Wz = torch.tensor(_np(W) * orc.mask_to_original_order(mk, theta), dtype=torch.float16)
+        comp = ctx.compress(Wz.cuda(), None, th, n, m)
+        values, meta = orc.compress_vectorised(_bits(Wz).reshape(N, K), theta, mk, n, m)
+        assert (_bits(comp.values).reshape(values.shape) == values).all()
+        assert (comp.meta.cpu().numpy().view(meta.dtype).reshape(meta.shape) == meta).all()
+    # a dense weight has more than n non-zeros per group
+    with pytest.raises(esp.EsparseError) as e:
+        ctx.compress(W.cuda(), None, th, 2, 4)
+    assert e.value.code == -5
+    bad = mask.copy()
+    bad[3, 8:16] = 1
+    with pytest.raises(esp.EsparseError) as e:
+        ctx.compress(W.cuda(), torch.tensor(bad).cuda(), th, 4, 8)
+    assert e.value.code == -5
+    th_bad = th.clone()
+    th_bad[5] = th_bad[6]
+    with pytest.raises(esp.EsparseError) as e:
+        ctx.compress(W.cuda(), torch.tensor(mask).cuda(), th_bad, 4, 8)
+    assert e.value.code == -6
+
+
+# ---------------------------------------------------------------- products
+def _spmm_case(esp, ctx, M, N, K, dtype, seed, use_perm=True):
+    rng = np.random.default_rng(seed)
+    scales = wl.channel_scales("lognormal", K, wl.stream_id("xs", seed))
+    W = _rand((N, K), dtype, seed, scale=K ** -0.5)
+    X = _rand((M, K), dtype, seed + 7, col_scale=scales)
+    s = np.abs(rng.standard_normal(K)) + 0.1
+    theta = rng.permutation(K) if use_perm else np.arange(K)
+    mask = orc.nm_mask_vectorised(_np(W), s, theta, 2, 4)
+    th = torch.tensor(theta, dtype=torch.int32).cuda() if use_perm else None
+    comp = ctx.compress(W.cuda(), torch.tensor(mask).cuda(), th, canonical=False)
+    Yref = orc.spmm_ref(_np(X), _np(W), theta, mask)
+    Ydref = orc.dense_ref(_np(X), _np(W))
+    packed = ctx.dense_pack(W.cuda())
+    Xd = X.cuda()
+    for v in range(esp.num_variants()):
+        print(f"spmm M={M} N={N} K={K} {dtype} perm={use_perm} variant={esp.variant_name(v)}", flush=True)
+        try:
+            Y = ctx.spmm(Xd, comp, th, variant=v)
+        except esp.EsparseError as e:
+            assert e.code == -2
+            continue
+        torch.cuda.synchronize()
+        err = orc.rowwise_rel_error(_np(Y), Yref)
+        assert err.max() <= TOL[dtype], ("sparse", esp.variant_name(v), err.max())
+        Yd = ctx.dense_gemm(Xd, packed, N, variant=v)
+        torch.cuda.synchronize()
+        err = orc.rowwise_rel_error(_np(Yd), Ydref)
+        assert err.max() <= TOL[dtype], ("dense", esp.variant_name(v), err.max())
+    # default variant
+    Y = ctx.spmm(Xd, comp, th)
+    assert orc.rowwise_rel_error(_np(Y), Yref).max() <= TOL[dtype]
+
+
+@pytest.mark.parametrize("M", [1, 8, 16, 33, 130])
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+def test_spmm_small_ragged(esp, ctx, M, dtype):
+    _spmm_case(esp, ctx, M, 72, 576, dtype, 41)
+
+
+def test_spmm_identity_perm_and_multi_tile(esp, ctx):
+    _spmm_case(esp, ctx, 16, 512, 2048, torch.float16, 42, use_perm=False)
+    _spmm_case(esp, ctx, 200, 272, 1280, torch.float16, 43)
+
+
+def test_spmm_one_hot_reads_back_weights_through_theta(esp, ctx):
+    N, K = 48, 256
+    rng = np.random.default_rng(3)
+    W = _rand((N, K), torch.float16, 44)
+    s = np.abs(rng.standard_normal(K)) + 0.1
+    theta = rng.permutation(K)
+    mask = orc.nm_mask_vectorised(_np(W), s, theta, 2, 4)
+    th = torch.tensor(theta, dtype=torch.int32).cuda()
+    comp = ctx.compress(W.cuda(), torch.tensor(mask).cuda(), th)
+    X = torch.eye(K, dtype=torch.float16)
+    Y = ctx.spmm(X.cuda(), comp, th)                      # [K, N]: row c = masked W[:, c]
+    ref = (_np(W) * orc.mask_to_original_order(mask, theta)).T
+    assert (_np(Y) == ref).all()
+    ones = torch.ones((1, K), dtype=torch.float16)
+    Y1 = ctx.spmm(ones.cuda(), comp, th)
+    assert np.allclose(_np(Y1)[0], ref.sum(axis=0), rtol=2e-3, atol=1e-3)
+
+
+def test_spmm_repeat_is_bitwise_identical_and_m0(esp, ctx):
+    N, K, M = 64, 1024, 24
+    W = _rand((N, K), torch.float16, 45, scale=K ** -0.5)
+    X = _rand((M, K), torch.float16, 46)
+    theta = np.random.default_rng(1).permutation(K)
+    mask = orc.nm_mask_vectorised(_np(W), np.ones(K), theta, 2, 4)
+    th = torch.tensor(theta, dtype=torch.int32).cuda()
+    comp = ctx.compress(W.cuda(), torch.tensor(mask).cuda(), th, canonical=False)
+    for v in range(esp.num_variants()):
+        a = _bits(ctx.spmm(X.cuda(), comp, th, variant=v))
+        b = _bits(ctx.spmm(X.cuda(), comp, th, variant=v))
+        assert (a == b).all()
+    Y0 = ctx.spmm(X[:0].cuda(), comp, th)
+    assert Y0.shape == (0, N)
+
+
+def test_workspace_too_small_and_bad_variant(esp, ctx):
+    import ctypes as C
+    N, K, M = 32, 256, 4
+    W = _rand((N, K), torch.float16, 47)
+    comp = ctx.compress(torch.tensor(_np(W) * np.tile([1, 1, 0, 0], (N, K // 4)), dtype=torch.float16).cuda(), None, None)
+    X = _rand((M, K), torch.float16, 48).cuda()
+    Y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    ws = ctx.workspace(1024)
+    lib = esp.load_library()
+    rc = lib.esparse_spmm(ctx._h, X.data_ptr(), M, comp.native.data_ptr(), None, N, K, 0, 2, 4, Y.data_ptr(),
+                          ws.data_ptr(), 1024, -1)
+    assert rc == -7
+    with pytest.raises(esp.EsparseError) as e:
+        ctx.spmm(X, comp, None, variant=999)
+    assert e.value.code == -1
+
+
+def test_tune_picks_a_variant_and_persists(esp, ctx, tmp_path):
+    best, ms = ctx.tune(16, 512, 1024, esp.F16, sparse=True)
+    assert 0 <= best < esp.num_variants() and ms > 0
+    p = str(tmp_path / "tuned.txt")
+    ctx.tune_save(p)
+    c2 = esp.Context(0)
+    c2.tune_load(p)
+    assert esp.variant_name(best) in open(p).read()

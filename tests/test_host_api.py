@@ -1,0 +1,85 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every declared symbol,
+answers its closed-form size queries and rejects bad arguments before touching the GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2310_15929_amd as esp
+from paper_2310_15929_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = esp.load_library()
+    header = open(os.path.join(ROOT, "include", "esparse.h")).read()
+    declared = set(re.findall(r"\b(esparse_[a-z_]+)\s*\(", header))
+    declared -= {"esparse_ctx", "esparse_status", "esparse_dtype", "esparse_prune_opts"}
+    assert declared == set(binding.EXPORTED)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.esparse_version().startswith(b"esparse")
+
+
+def test_size_queries_closed_form():
+    for N, K in [(512, 512), (4096, 11008), (24, 320)]:
+        vb, mb, nb = esp.compressed_size(N, K, 2, 4)
+        assert vb == N * K and mb == N * ((K // 2 + 15) // 16) * 4
+        Np, Kp = -(-N // 16) * 16, -(-K // 256) * 256
+        assert nb == Np * Kp * 9 // 8
+        vb8, mb8, nb8 = esp.compressed_size(N, K - K % 8, 4, 8)
+        assert vb8 == N * (K - K % 8) and mb8 == N * (K - K % 8) // 8 and nb8 == 0
+    vb, mb, _ = esp.compressed_size(4096, 4096, 2, 4)
+    assert (vb + mb) / (2 * 4096 * 4096) == 0.5625
+    assert esp.dense_packed_size(24, 320) == 32 * 512 * 2
+    assert esp.spmm_workspace(16, 512, 512) >= 16 * 512 * 2
+    with pytest.raises(esp.EsparseError):
+        esp.compressed_size(8, 8, 1, 4)
+
+
+def test_argument_errors_need_no_gpu():
+    ctx = esp.Context(0)
+    W = torch.zeros(8, 16, dtype=torch.float16)
+    Xc = torch.zeros(4, 16, dtype=torch.float16)
+
+    def code(fn):
+        with pytest.raises(esp.EsparseError) as e:
+            fn()
+        return e.value.code
+
+    assert code(lambda: ctx.compress(W, None, None, 3, 4)) == -2
+    assert code(lambda: ctx.compress(torch.zeros(8, 18, dtype=torch.float16), None, None, 2, 4)) == -1
+    assert code(lambda: ctx.prune(Xc, W, esp.PruneOpts(block=24))) == -1          # 16 % 24
+    assert code(lambda: ctx.prune(Xc, W, esp.PruneOpts(block=6))) == -1           # block % m
+    assert code(lambda: ctx.prune(Xc, W, esp.PruneOpts(n_keep=1, m_group=4, block=8))) == -2
+    assert code(lambda: ctx.prune(Xc, W, esp.PruneOpts(block=8, bins=0))) == -1
+    assert code(lambda: ctx.prune(Xc, W, esp.PruneOpts(block=8, flags=esp.USE_GNS))) == -1
+    assert code(lambda: ctx.prune(Xc, W, esp.PruneOpts(block=8, max_swaps=-1))) == -1
+    lib = esp.load_library()
+    assert lib.esparse_spmm(ctx._h, None, 4, None, None, 8, 16, 0, 4, 8, None, None, 0, -1) == -2
+    assert lib.esparse_spmm(ctx._h, None, 4, None, None, 8, 16, 0, 2, 4, None, None, 0, -1) == -1
+    assert b"null" in lib.esparse_last_error(ctx._h)
+    assert lib.esparse_spmm(ctx._h, None, 0, None, None, 8, 16, 0, 2, 4, None, None, 0, -1) == 0   # M = 0
+    assert lib.esparse_channel_stats(ctx._h, None, 4, 16, 0, 100, None, None) == -1
+    assert lib.esparse_create(None, 0, None) == -1
+
+
+def test_tune_table_text_roundtrip(tmp_path):
+    ctx = esp.Context(0)
+    p = tmp_path / "t.txt"
+    p.write_text("# comment\n1 0 16 512 512 %s\n" % esp.variant_name(1))
+    ctx.tune_load(str(p))
+    q = tmp_path / "u.txt"
+    ctx.tune_save(str(q))
+    assert "1 0 16 512 512 " + esp.variant_name(1) in q.read_text()
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libesparse.so")
+    with pytest.raises(FileNotFoundError):
+        binding.load_library()
