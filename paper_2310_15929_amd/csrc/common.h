@@ -16,7 +16,7 @@ struct esparse_ctx {
   std::string err;
   // (sparse, dtype, M, N, K) -> variant chosen by esparse_tune
   std::map<std::tuple<int, int, long long, long long, long long>, int> tuned;
-  int* d_flags = nullptr;  // 64 ints of device scratch for error flags / counters
+  int* d_flags = nullptr;     // 64 ints of device scratch for error flags
 };
 
 int esp_fail(esparse_ctx* ctx, int code, const char* fmt, ...);

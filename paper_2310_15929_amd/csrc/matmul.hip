@@ -242,20 +242,110 @@ __global__ void __launch_bounds__(256) k_mm_wave_tile(const uint4* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------------
+// variant "ksplit" (decode sizes, M <= 32, HBM-bound): a workgroup of NW waves owns RT row tiles
+// (16*RT output features) over the WHOLE of K; wave w takes the 64-channel steps w, w+NW, w+2NW, ...
+// so the workgroup reads the compressed rows as contiguous NW KiB runs and has NW*(RT + 2*MT) KiB of
+// loads in flight.  Operands go straight from memory to registers (weights from HBM, the staged
+// activations from L2).  The NW partial tiles meet in LDS and are added in ascending wave order, so
+// the result does not depend on timing and no global synchronisation is needed.
+// grid = ceil(row tiles / RT), block = 64 * NW.
+// ------------------------------------------------------------------------------------------------
+template <int DT, int SPARSE, int MT, int RT, int NW>
+__global__ void __launch_bounds__(NW * 64) k_mm_ksplit(const uint4* __restrict__ A, const uint16_t* __restrict__ meta16,
+                                                        const uint4* __restrict__ Xf, uint16_t* __restrict__ Y, long long M,
+                                                        long long N, long long Mp, long long Np, long long Kp) {
+  extern __shared__ floatx4_t s_red[];  // [NW][RT * MT][64]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
+  const long long rt0 = (long long)blockIdx.x * RT;
+  long long rts[RT];
+#pragma unroll
+  for (int i = 0; i < RT; i++) rts[i] = (rt0 + i < nrt) ? rt0 + i : nrt - 1;
+
+  floatx4_t acc[RT][MT];
+#pragma unroll
+  for (int i = 0; i < RT; i++)
+#pragma unroll
+    for (int j = 0; j < MT; j++) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+  // two steps per trip (all loads of both steps are issued before the first multiply)
+  for (long long ks = wave; ks < nks; ks += 2 * NW) {
+    const bool second = ks + NW < nks;  // wave-uniform
+    const long long kk[2] = {ks, second ? ks + NW : ks};
+    uint4 a[2][RT], a2[2][RT], b0[2][MT], b1[2][MT];
+    int idx[2][RT];
+#pragma unroll
+    for (int u = 0; u < 2; u++) {
+#pragma unroll
+      for (int i = 0; i < RT; i++) {
+        if (SPARSE) {
+          a[u][i] = A[(rts[i] * nks + kk[u]) * 64 + lane];
+          idx[u][i] = (int)meta16[((rts[i] * (nks / 4) + kk[u] / 4) * 64 + lane) * 4 + (kk[u] & 3)];
+        } else {
+          a[u][i] = A[(rts[i] * (2 * nks) + 2 * kk[u]) * 64 + lane];
+          a2[u][i] = A[(rts[i] * (2 * nks) + 2 * kk[u] + 1) * 64 + lane];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < MT; j++) {
+        const long long tt = (j < ntt) ? j : ntt - 1;
+        b0[u][j] = Xf[(tt * (2 * nks) + 2 * kk[u]) * 64 + lane];
+        b1[u][j] = Xf[(tt * (2 * nks) + 2 * kk[u] + 1) * 64 + lane];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2; u++) {
+      if (u == 1 && !second) break;
+#pragma unroll
+      for (int i = 0; i < RT; i++)
+#pragma unroll
+        for (int j = 0; j < MT; j++) {
+          if (SPARSE) {
+            acc[i][j] = smfmac16<DT, 0>(a[u][i], b0[u][j], b1[u][j], acc[i][j], idx[u][i]);
+          } else {
+            acc[i][j] = mfma16<DT>(a[u][i], b0[u][j], acc[i][j]);
+            acc[i][j] = mfma16<DT>(a2[u][i], b1[u][j], acc[i][j]);
+          }
+        }
+    }
+  }
+
+#pragma unroll
+  for (int i = 0; i < RT; i++)
+#pragma unroll
+    for (int j = 0; j < MT; j++) s_red[(wave * (RT * MT) + i * MT + j) * 64 + lane] = acc[i][j];
+  __syncthreads();
+  const int c = lane & 15, g = lane >> 4;
+  for (int q = wave; q < RT * MT; q += NW) {
+    const int i = q / MT, j = q % MT;
+    floatx4_t sum = s_red[q * 64 + lane];
+    for (int w = 1; w < NW; w++) sum += s_red[(w * (RT * MT) + q) * 64 + lane];
+    if (rt0 + i < nrt && j < ntt) store_y4<DT>(Y, M, N, (long long)j * 16 + c, (rt0 + i) * 16 + g * 4, sum);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // variant table and host launcher
 // ------------------------------------------------------------------------------------------------
+enum { KIND_WAVE = 0, KIND_KSPLIT = 1 };
 struct Variant {
   const char* name;
-  int rt, tt;      // row tiles / token tiles per wave
-  int split_mode;  // 0 = never split K, 1 = split K to fill the chip (decode sizes)
+  int kind;
+  int rt, tt;      // row tiles / token tiles per wave (ksplit: row tiles per workgroup, tt unused: MT follows M)
+  int split_mode;  // wave kind: 0 = never split K, 1 = split K over workgroups to fill the chip
+  int nw;          // ksplit kind: waves per workgroup
 };
 static const Variant kVariants[] = {
-    {"wave_r1_t1_splitk", 1, 1, 1},
-    {"wave_r2_t1_splitk", 2, 1, 1},
-    {"wave_r4_t1_splitk", 4, 1, 1},
-    {"wave_r2_t2_splitk", 2, 2, 1},
-    {"wave_r4_t2", 4, 2, 0},
-    {"wave_r4_t4", 4, 4, 0},
+    {"wave_r2_t1_splitk", KIND_WAVE, 2, 1, 1, 0},
+    {"wave_r2_t2_splitk", KIND_WAVE, 2, 2, 1, 0},
+    {"wave_r4_t2", KIND_WAVE, 4, 2, 0, 0},
+    {"wave_r4_t4", KIND_WAVE, 4, 4, 0, 0},
+    {"ksplit_w16_r1", KIND_KSPLIT, 1, 0, 0, 16},
+    {"ksplit_w16_r2", KIND_KSPLIT, 2, 0, 0, 16},
+    {"ksplit_w8_r1", KIND_KSPLIT, 1, 0, 0, 8},
+    {"ksplit_w8_r2", KIND_KSPLIT, 2, 0, 0, 8},
+    {"ksplit_w8_r4", KIND_KSPLIT, 4, 0, 0, 8},
+    {"ksplit_w16_r3", KIND_KSPLIT, 3, 0, 0, 16},
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -267,17 +357,21 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
   (void)K;
   (void)sparse;
   if (v < 0 || v >= kNumVariants) return false;
-  if (kVariants[v].split_mode == 1 && M > 128) return false;  // partial buffers are sized for decode only
+  const Variant& var = kVariants[v];
+  if (var.kind == KIND_WAVE && var.split_mode == 1 && M > 128) return false;  // partial buffers are sized for decode only
+  if (var.kind == KIND_KSPLIT && M > 32) return false;
   return true;
 }
 
 int esp_default_variant(long long M, long long N, long long K, int sparse) {
-  (void)N;
   (void)K;
   (void)sparse;
-  if (M <= 16) return 1;
-  if (M <= 128) return 3;
-  return 5;
+  if (M <= 32) {
+    const long long nrt = esp_round_up(N, 16) / 16;
+    return nrt <= 320 ? 4 : 5;  // ksplit_w16_r1 / ksplit_w16_r2
+  }
+  if (M <= 128) return 1;  // wave_r2_t2_splitk
+  return 3;                // wave_r4_t4
 }
 
 size_t esp_workspace_bytes(long long M, long long N, long long K) {
@@ -295,13 +389,37 @@ static void launch_wave_tile(const Variant& v, dim3 grid, hipStream_t st, const 
 #define LAUNCH(R, T)                                                                                                      \
   hipLaunchKernelGGL((k_mm_wave_tile<DT, SPARSE, R, T>), grid, dim3(256), 0, st, A, meta, Xf, Y, partial, M, N, Mp, Np, Kp, \
                      nsplit, sps, n_items)
-  if (v.rt == 1 && v.tt == 1) LAUNCH(1, 1);
-  else if (v.rt == 2 && v.tt == 1) LAUNCH(2, 1);
-  else if (v.rt == 4 && v.tt == 1) LAUNCH(4, 1);
+  if (v.rt == 2 && v.tt == 1) LAUNCH(2, 1);
   else if (v.rt == 2 && v.tt == 2) LAUNCH(2, 2);
   else if (v.rt == 4 && v.tt == 2) LAUNCH(4, 2);
   else LAUNCH(4, 4);
 #undef LAUNCH
+}
+
+template <int DT, int SPARSE, int MT>
+static void launch_ksplit(const Variant& v, hipStream_t st, const uint4* A, const uint16_t* meta16, const uint4* Xf, uint16_t* Y,
+                          long long M, long long N, long long Mp, long long Np, long long Kp) {
+  const long long nrt = Np / 16;
+  dim3 grid((unsigned)((nrt + v.rt - 1) / v.rt));
+  const size_t smem = (size_t)v.nw * v.rt * MT * 64 * 16;
+#define LAUNCH(R, W) \
+  hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W>), grid, dim3(W * 64), smem, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp)
+  if (v.nw == 16 && v.rt == 1) LAUNCH(1, 16);
+  else if (v.nw == 16 && v.rt == 2) LAUNCH(2, 16);
+  else if (v.nw == 16 && v.rt == 3) LAUNCH(3, 16);
+  else if (v.nw == 8 && v.rt == 1) LAUNCH(1, 8);
+  else if (v.nw == 8 && v.rt == 2) LAUNCH(2, 8);
+  else LAUNCH(4, 8);
+#undef LAUNCH
+}
+
+static int stage_activations(esparse_ctx* ctx, const void* X, const int32_t* perm, long long M, long long K, long long Mp,
+                             long long Kp, uint4* Xf) {
+  const long long units = Mp * Kp / 8;
+  hipLaunchKernelGGL(k_gather_x, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, ctx->stream,
+                     reinterpret_cast<const uint16_t*>(X), perm, M, K, Kp, units, Xf);
+  ESP_HIP(ctx, hipGetLastError());
+  return ESPARSE_OK;
 }
 
 int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, const void* w, const int32_t* perm,
@@ -313,17 +431,32 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
   size_t xbytes = ((size_t)Mp * Kp * 2 + 255) / 256 * 256;
   float* partial = reinterpret_cast<float*>(ws + WS_HEADER_BYTES + xbytes);
   uint16_t* Y = reinterpret_cast<uint16_t*>(Yv);
-
-  // 1. stage the activations (re-ordered through theta, fragment-major)
-  {
-    const long long units = Mp * Kp / 8;
-    hipLaunchKernelGGL(k_gather_x, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, st, reinterpret_cast<const uint16_t*>(X), perm,
-                       M, K, Kp, units, Xf);
-    ESP_HIP(ctx, hipGetLastError());
-  }
-  // 2. the product
+  const uint4* A = reinterpret_cast<const uint4*>(w);
+  const unsigned char* meta_bytes = sparse ? reinterpret_cast<const unsigned char*>(w) + (size_t)Np * Kp : nullptr;
+  const uint2* meta = reinterpret_cast<const uint2*>(meta_bytes);
   const Variant& v = kVariants[variant];
   const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
+  int rc;
+  if ((rc = stage_activations(ctx, X, perm, M, K, Mp, Kp, Xf))) return rc;
+
+  if (v.kind == KIND_KSPLIT) {
+    const uint16_t* meta16 = reinterpret_cast<const uint16_t*>(meta_bytes);
+    if (dtype == ESPARSE_F16) {
+      if (sparse && ntt == 1) launch_ksplit<ESPARSE_F16, 1, 1>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
+      else if (sparse) launch_ksplit<ESPARSE_F16, 1, 2>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
+      else if (ntt == 1) launch_ksplit<ESPARSE_F16, 0, 1>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
+      else launch_ksplit<ESPARSE_F16, 0, 2>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
+    } else {
+      if (sparse && ntt == 1) launch_ksplit<ESPARSE_BF16, 1, 1>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
+      else if (sparse) launch_ksplit<ESPARSE_BF16, 1, 2>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
+      else if (ntt == 1) launch_ksplit<ESPARSE_BF16, 0, 1>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
+      else launch_ksplit<ESPARSE_BF16, 0, 2>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
+    }
+    ESP_HIP(ctx, hipGetLastError());
+    return ESPARSE_OK;
+  }
+
+  // ---- wave-tile kinds
   const long long nrb = (nrt + v.rt - 1) / v.rt, ntb = (ntt + v.tt - 1) / v.tt;
   int nsplit = 1;
   if (v.split_mode == 1) {
@@ -337,8 +470,6 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
   nsplit = (int)((nks + sps - 1) / sps);
   const long long n_items = nrb * ntb * nsplit;
   dim3 grid((unsigned)((n_items + 3) / 4));
-  const uint4* A = reinterpret_cast<const uint4*>(w);
-  const uint2* meta = sparse ? reinterpret_cast<const uint2*>(reinterpret_cast<const unsigned char*>(w) + (size_t)Np * Kp) : nullptr;
   if (dtype == ESPARSE_F16) {
     if (sparse) launch_wave_tile<ESPARSE_F16, 1>(v, grid, st, A, meta, Xf, Y, partial, M, N, Mp, Np, Kp, nsplit, (int)sps, n_items);
     else launch_wave_tile<ESPARSE_F16, 0>(v, grid, st, A, meta, Xf, Y, partial, M, N, Mp, Np, Kp, nsplit, (int)sps, n_items);
@@ -347,7 +478,6 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
     else launch_wave_tile<ESPARSE_BF16, 0>(v, grid, st, A, meta, Xf, Y, partial, M, N, Mp, Np, Kp, nsplit, (int)sps, n_items);
   }
   ESP_HIP(ctx, hipGetLastError());
-  // 3. add the K splits in order
   if (nsplit > 1) {
     const long long e = M * (Np / 4);
     if (dtype == ESPARSE_F16)

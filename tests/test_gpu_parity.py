@@ -287,7 +287,11 @@ def test_spmm_repeat_is_bitwise_identical_and_m0(esp, ctx):
     th = torch.tensor(theta, dtype=torch.int32).cuda()
     comp = ctx.compress(W.cuda(), torch.tensor(mask).cuda(), th, canonical=False)
     for v in range(esp.num_variants()):
-        a = _bits(ctx.spmm(X.cuda(), comp, th, variant=v))
+        try:
+            a = _bits(ctx.spmm(X.cuda(), comp, th, variant=v))
+        except esp.EsparseError as e:
+            assert e.code == -2                      # variant not applicable to this M
+            continue
         b = _bits(ctx.spmm(X.cuda(), comp, th, variant=v))
         assert (a == b).all()
     Y0 = ctx.spmm(X[:0].cuda(), comp, th)
