@@ -17,7 +17,7 @@
  *   - Unless a parameter is marked HOST, every data pointer is a DEVICE pointer owned by the
  *     caller, row-major, contiguous and 16-byte aligned.  The library never frees or keeps them.
  *   - All GPU work is enqueued on the context's stream.  esparse_spmm, esparse_dense_gemm,
- *     esparse_dense_pack and esparse_gather_activations do not synchronise; esparse_prune,
+ *     esparse_dense_pack, esparse_stage_activations and the *_staged products do not synchronise; esparse_prune,
  *     esparse_compress, esparse_channel_stats and esparse_tune do (they return host results).
  *   - Every function returns an esparse_status (0 = ok, negative = error) and never throws.
  *     Arguments are validated before the first GPU call; on an argument error nothing is
@@ -137,6 +137,17 @@ int esparse_spmm_workspace(long long M, long long N, long long K, size_t* bytes)
 int esparse_spmm(esparse_ctx* ctx, const void* X, long long M, const void* native_w,
                  const int32_t* perm, long long N, long long K, esparse_dtype dtype, int n_keep,
                  int m_group, void* Y, void* workspace, size_t workspace_bytes, int variant);
+/* The two halves of esparse_spmm as separate calls, for callers that multiply one activation
+ * matrix with several weight matrices sharing one perm, or that time the multiply alone:
+ * esparse_stage_activations writes X[:, perm] in the kernels' operand order into the workspace
+ * (sized by esparse_spmm_workspace(M, N, K) for the largest N that will use it);
+ * esparse_spmm_staged multiplies what the workspace holds.  Same errors as esparse_spmm. */
+int esparse_stage_activations(esparse_ctx* ctx, const void* X, long long M, const int32_t* perm,
+                              long long N, long long K, esparse_dtype dtype, void* workspace,
+                              size_t workspace_bytes);
+int esparse_spmm_staged(esparse_ctx* ctx, long long M, const void* native_w, long long N, long long K,
+                        esparse_dtype dtype, int n_keep, int m_group, void* Y, void* workspace,
+                        size_t workspace_bytes, int variant);
 int esparse_spmm_num_variants(void);
 const char* esparse_spmm_variant_name(int variant);
 
@@ -150,6 +161,10 @@ int esparse_dense_pack(esparse_ctx* ctx, const void* W, long long N, long long K
 int esparse_dense_gemm(esparse_ctx* ctx, const void* X, long long M, const void* packed_w,
                        long long N, long long K, esparse_dtype dtype, void* Y, void* workspace,
                        size_t workspace_bytes, int variant);
+
+int esparse_dense_gemm_staged(esparse_ctx* ctx, long long M, const void* packed_w, long long N,
+                              long long K, esparse_dtype dtype, void* Y, void* workspace,
+                              size_t workspace_bytes, int variant);
 
 /* ---- Section 4, step 2: pick and remember the fastest variant for a shape --------------------
  * Times every applicable variant of esparse_spmm (sparse != 0) or esparse_dense_gemm on

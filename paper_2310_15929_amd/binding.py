@@ -56,6 +56,9 @@ def load_library():
         "esparse_compress": (i32, [vp, vp, vp, vp, ll, ll, i32, i32, i32, vp, vp, vp]),
         "esparse_spmm_workspace": (i32, [ll, ll, ll, P(sz)]),
         "esparse_spmm": (i32, [vp, vp, ll, vp, vp, ll, ll, i32, i32, i32, vp, vp, sz, i32]),
+        "esparse_stage_activations": (i32, [vp, vp, ll, vp, ll, ll, i32, vp, sz]),
+        "esparse_spmm_staged": (i32, [vp, ll, vp, ll, ll, i32, i32, i32, vp, vp, sz, i32]),
+        "esparse_dense_gemm_staged": (i32, [vp, ll, vp, ll, ll, i32, vp, vp, sz, i32]),
         "esparse_spmm_num_variants": (i32, []),
         "esparse_spmm_variant_name": (C.c_char_p, [i32]),
         "esparse_dense_packed_size": (i32, [ll, ll, P(sz)]),
@@ -76,6 +79,7 @@ def load_library():
 EXPORTED = ["esparse_create", "esparse_destroy", "esparse_set_stream", "esparse_last_error",
             "esparse_version", "esparse_channel_stats", "esparse_prune", "esparse_prune_with_scores",
             "esparse_compressed_size", "esparse_compress", "esparse_spmm_workspace", "esparse_spmm",
+            "esparse_stage_activations", "esparse_spmm_staged", "esparse_dense_gemm_staged",
             "esparse_spmm_num_variants", "esparse_spmm_variant_name", "esparse_dense_packed_size",
             "esparse_dense_pack", "esparse_dense_gemm", "esparse_tune", "esparse_tune_save",
             "esparse_tune_load"]
@@ -267,6 +271,30 @@ class Context:
         self._sync_stream()
         self._check(self._lib.esparse_spmm(self._h, _ptr(X), M, _ptr(comp.native), _ptr(perm), comp.N, K, comp.dtype,
                                            comp.n_keep, comp.m_group, _ptr(Y), _ptr(ws), nbytes, variant))
+        return Y
+
+    def stage_activations(self, X: torch.Tensor, perm: Optional[torch.Tensor], N: int,
+                          ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+        M, K = X.shape
+        nbytes = spmm_workspace(M, N, K)
+        if ws is None:
+            ws = self.workspace(nbytes)
+        self._sync_stream()
+        self._check(self._lib.esparse_stage_activations(self._h, _ptr(X), M, _ptr(perm), N, K, _dtype_code(X),
+                                                        _ptr(ws), ws.numel()))
+        return ws
+
+    def spmm_staged(self, M: int, comp: Compressed, ws: torch.Tensor, Y: torch.Tensor, *, variant: int = -1):
+        self._sync_stream()
+        self._check(self._lib.esparse_spmm_staged(self._h, M, _ptr(comp.native), comp.N, comp.K, comp.dtype,
+                                                  comp.n_keep, comp.m_group, _ptr(Y), _ptr(ws), ws.numel(), variant))
+        return Y
+
+    def dense_gemm_staged(self, M: int, packed: torch.Tensor, N: int, K: int, ws: torch.Tensor, Y: torch.Tensor, *,
+                          variant: int = -1):
+        self._sync_stream()
+        self._check(self._lib.esparse_dense_gemm_staged(self._h, M, _ptr(packed), N, K, _dtype_code(Y), _ptr(Y),
+                                                        _ptr(ws), ws.numel(), variant))
         return Y
 
     def dense_pack(self, W: torch.Tensor) -> torch.Tensor:

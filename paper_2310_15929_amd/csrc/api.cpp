@@ -238,14 +238,16 @@ int esparse_compress(esparse_ctx* ctx, const void* W, const uint8_t* mask, const
 
 static int check_matmul(esparse_ctx* ctx, const void* X, long long M, const void* w, long long N,
                         long long K, int dtype, const void* Y, const void* ws, size_t ws_bytes,
-                        int variant, int sparse) {
+                        int variant, int sparse, int phases = 3) {
   int rc = check_dtype(ctx, dtype);
   if (rc) return rc;
   ESP_REQUIRE(ctx, M >= 0 && M < (1ll << 24), ESPARSE_EINVAL, "M = %lld out of range", M);
   ESP_REQUIRE(ctx, N >= 1 && N < (1ll << 31) && K >= 4 && K < (1ll << 31), ESPARSE_EINVAL, "N or K out of range");
   ESP_REQUIRE(ctx, K % 4 == 0, ESPARSE_EINVAL, "K = %lld is not a multiple of 4", K);
   if (M == 0) return ESPARSE_OK;
-  ESP_REQUIRE(ctx, X && w && Y && ws, ESPARSE_EINVAL, "X / weights / Y / workspace is null");
+  ESP_REQUIRE(ctx, ws && ((phases & ESP_PHASE_STAGE) ? X != nullptr : true) &&
+                       ((phases & ESP_PHASE_MULTIPLY) ? (w && Y) : true),
+              ESPARSE_EINVAL, "X / weights / Y / workspace is null");
   ESP_REQUIRE(ctx, esp_aligned16(X) && esp_aligned16(w) && esp_aligned16(Y), ESPARSE_EINVAL,
               "X / weights / Y is not 16-byte aligned");
   ESP_REQUIRE(ctx, (reinterpret_cast<uintptr_t>(ws) & 255u) == 0, ESPARSE_EINVAL, "workspace is not 256-byte aligned");
@@ -273,18 +275,37 @@ int esparse_spmm_workspace(long long M, long long N, long long K, size_t* bytes)
 int esparse_spmm_num_variants(void) { return esp_num_variants(); }
 const char* esparse_spmm_variant_name(int v) { return (v >= 0 && v < esp_num_variants()) ? esp_variant_name(v) : ""; }
 
-int esparse_spmm(esparse_ctx* ctx, const void* X, long long M, const void* native_w, const int32_t* perm,
-                 long long N, long long K, esparse_dtype dtype, int n, int m, void* Y, void* workspace,
-                 size_t workspace_bytes, int variant) {
+static int spmm_phases(esparse_ctx* ctx, const void* X, long long M, const void* native_w, const int32_t* perm,
+                       long long N, long long K, esparse_dtype dtype, int n, int m, void* Y, void* workspace,
+                       size_t workspace_bytes, int variant, int phases) {
   if (!ctx) return ESPARSE_EINVAL;
   ESP_REQUIRE(ctx, n == 2 && m == 4, ESPARSE_EUNSUPPORTED, "the sparse product exists for 2:4 only (got %d:%d)", n, m);
-  int rc = check_matmul(ctx, X, M, native_w, N, K, dtype, Y, workspace, workspace_bytes, variant, 1);
+  int rc = check_matmul(ctx, X, M, native_w, N, K, dtype, Y, workspace, workspace_bytes, variant, 1, phases);
   if (rc) return rc;
   ESP_REQUIRE(ctx, esp_aligned16(perm), ESPARSE_EINVAL, "perm is not 16-byte aligned");
   if (M == 0) return ESPARSE_OK;
   ESP_HIP(ctx, hipSetDevice(ctx->device));
   return esp_matmul_device(ctx, 1, X, M, native_w, perm, N, K, dtype, Y, workspace,
-                           pick_variant(ctx, 1, dtype, M, N, K, variant));
+                           pick_variant(ctx, 1, dtype, M, N, K, variant), phases);
+}
+
+int esparse_spmm(esparse_ctx* ctx, const void* X, long long M, const void* native_w, const int32_t* perm,
+                 long long N, long long K, esparse_dtype dtype, int n, int m, void* Y, void* workspace,
+                 size_t workspace_bytes, int variant) {
+  return spmm_phases(ctx, X, M, native_w, perm, N, K, dtype, n, m, Y, workspace, workspace_bytes, variant, 3);
+}
+
+int esparse_stage_activations(esparse_ctx* ctx, const void* X, long long M, const int32_t* perm, long long N,
+                              long long K, esparse_dtype dtype, void* workspace, size_t workspace_bytes) {
+  return spmm_phases(ctx, X, M, nullptr, perm, N, K, dtype, 2, 4, nullptr, workspace, workspace_bytes, -1,
+                     ESP_PHASE_STAGE);
+}
+
+int esparse_spmm_staged(esparse_ctx* ctx, long long M, const void* native_w, long long N, long long K,
+                        esparse_dtype dtype, int n, int m, void* Y, void* workspace, size_t workspace_bytes,
+                        int variant) {
+  return spmm_phases(ctx, nullptr, M, native_w, nullptr, N, K, dtype, n, m, Y, workspace, workspace_bytes, variant,
+                     ESP_PHASE_MULTIPLY);
 }
 
 int esparse_dense_packed_size(long long N, long long K, size_t* bytes) {
@@ -306,16 +327,28 @@ int esparse_dense_pack(esparse_ctx* ctx, const void* W, long long N, long long K
   return esp_dense_pack_device(ctx, W, N, K, dtype, packed_out);
 }
 
-int esparse_dense_gemm(esparse_ctx* ctx, const void* X, long long M, const void* packed_w, long long N,
-                       long long K, esparse_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
-                       int variant) {
+static int dense_phases(esparse_ctx* ctx, const void* X, long long M, const void* packed_w, long long N,
+                        long long K, esparse_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
+                        int variant, int phases) {
   if (!ctx) return ESPARSE_EINVAL;
-  int rc = check_matmul(ctx, X, M, packed_w, N, K, dtype, Y, workspace, workspace_bytes, variant, 0);
+  int rc = check_matmul(ctx, X, M, packed_w, N, K, dtype, Y, workspace, workspace_bytes, variant, 0, phases);
   if (rc) return rc;
   if (M == 0) return ESPARSE_OK;
   ESP_HIP(ctx, hipSetDevice(ctx->device));
   return esp_matmul_device(ctx, 0, X, M, packed_w, nullptr, N, K, dtype, Y, workspace,
-                           pick_variant(ctx, 0, dtype, M, N, K, variant));
+                           pick_variant(ctx, 0, dtype, M, N, K, variant), phases);
+}
+
+int esparse_dense_gemm(esparse_ctx* ctx, const void* X, long long M, const void* packed_w, long long N,
+                       long long K, esparse_dtype dtype, void* Y, void* workspace, size_t workspace_bytes,
+                       int variant) {
+  return dense_phases(ctx, X, M, packed_w, N, K, dtype, Y, workspace, workspace_bytes, variant, 3);
+}
+
+int esparse_dense_gemm_staged(esparse_ctx* ctx, long long M, const void* packed_w, long long N, long long K,
+                              esparse_dtype dtype, void* Y, void* workspace, size_t workspace_bytes, int variant) {
+  return dense_phases(ctx, nullptr, M, packed_w, N, K, dtype, Y, workspace, workspace_bytes, variant,
+                      ESP_PHASE_MULTIPLY);
 }
 
 int esparse_tune(esparse_ctx* ctx, long long M, long long N, long long K, esparse_dtype dtype, int sparse,
@@ -344,11 +377,11 @@ int esparse_tune(esparse_ctx* ctx, long long M, long long N, long long K, espars
   for (int v = 0; v < esp_num_variants(); v++) {
     if (!esp_variant_applicable(v, M, N, K, sparse)) continue;
     for (int i = 0; i < 3; i++)
-      if ((rc = esp_matmul_device(ctx, sparse, x.p, M, w.p, nullptr, N, K, dtype, y.p, ws.p, v))) break;
+      if ((rc = esp_matmul_device(ctx, sparse, x.p, M, w.p, nullptr, N, K, dtype, y.p, ws.p, v, 3))) break;
     if (rc) break;
     (void)hipEventRecord(e0, ctx->stream);
     for (int i = 0; i < reps; i++)
-      if ((rc = esp_matmul_device(ctx, sparse, x.p, M, w.p, nullptr, N, K, dtype, y.p, ws.p, v))) break;
+      if ((rc = esp_matmul_device(ctx, sparse, x.p, M, w.p, nullptr, N, K, dtype, y.p, ws.p, v, 3))) break;
     (void)hipEventRecord(e1, ctx->stream);
     if (rc) break;
     if (hipEventSynchronize(e1) != hipSuccess) {

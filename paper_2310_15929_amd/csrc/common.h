@@ -104,9 +104,11 @@ const char* esp_variant_name(int v);
 bool esp_variant_applicable(int v, long long M, long long N, long long K, int sparse);
 int esp_default_variant(long long M, long long N, long long K, int sparse);
 size_t esp_workspace_bytes(long long M, long long N, long long K);
+#define ESP_PHASE_STAGE 1     // gather X through theta into the workspace
+#define ESP_PHASE_MULTIPLY 2  // multiply the staged activations with the weights
 int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, const void* w,
                       const int32_t* perm, long long N, long long K, int dtype, void* Y,
-                      void* workspace, int variant);
+                      void* workspace, int variant, int phases);
 
 // exact accumulation helpers (host)
 // value = sum_b bins[b] * 2^(unit0 + 16*b), rounded once to nearest-even double

@@ -423,7 +423,7 @@ static int stage_activations(esparse_ctx* ctx, const void* X, const int32_t* per
 }
 
 int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, const void* w, const int32_t* perm,
-                      long long N, long long K, int dtype, void* Yv, void* workspace, int variant) {
+                      long long N, long long K, int dtype, void* Yv, void* workspace, int variant, int phases) {
   hipStream_t st = ctx->stream;
   const long long Mp = esp_round_up(M, 16), Np = esp_round_up(N, 16), Kp = esp_round_up(K, 256);
   unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
@@ -437,7 +437,8 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
   const Variant& v = kVariants[variant];
   const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
   int rc;
-  if ((rc = stage_activations(ctx, X, perm, M, K, Mp, Kp, Xf))) return rc;
+  if ((phases & ESP_PHASE_STAGE) && (rc = stage_activations(ctx, X, perm, M, K, Mp, Kp, Xf))) return rc;
+  if (!(phases & ESP_PHASE_MULTIPLY)) return ESPARSE_OK;
 
   if (v.kind == KIND_KSPLIT) {
     const uint16_t* meta16 = reinterpret_cast<const uint16_t*>(meta_bytes);
