@@ -1,6 +1,8 @@
 // Compression of n:m-pruned weights (Section 4, step 1): kept values + 2 bits of index per kept
 // value, written both in the canonical row-major form and in the order the sparse-MFMA kernels
 // stream (the layout is documented in include/esparse.h).  Pure data movement: HBM-bound.
+#include <algorithm>
+
 #include "common.h"
 
 // flags[0] |= 1 : a group does not keep exactly n ; flags[0] |= 2 : perm is not a bijection
@@ -15,74 +17,82 @@ __global__ void k_perm_count(const int32_t* __restrict__ perm, long long K, int*
 }
 
 // ---- 2:4 ----------------------------------------------------------------------------------------
-// One thread per unit = (row, 16 re-ordered channels): 4 groups, 8 kept values, 16 index bits.
+// One unit = (row, 16 re-ordered channels): 4 groups, 8 kept values, 16 index bits.
+// wrow points at the row's weights in ORIGINAL channel order (global memory or an LDS copy).
 // Units beyond N or K (padding of the native tiling) are written as zeros.
-__global__ void __launch_bounds__(256) k_compress_2_4(const uint16_t* __restrict__ W, const uint8_t* __restrict__ mask,
-                                                       const int32_t* __restrict__ perm, long long N, long long K, long long Np,
-                                                       long long Kp, uint16_t* __restrict__ values, uint32_t* __restrict__ meta,
-                                                       uint16_t* __restrict__ nvalues, uint16_t* __restrict__ nmeta,
-                                                       int* __restrict__ flags) {
-  const long long nchunk = Kp / 16;
-  long long u = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (u >= Np * nchunk) return;
-  // native order of the thread index keeps the native stores coalesced:
-  // u = ((rt * (nchunk/4) + ks) * 4 + ga) * 16 + r
-  const int r = (int)(u & 15), ga = (int)((u >> 4) & 3);
-  const long long t = u >> 6;
-  const long long ks = t % (nchunk / 4), rt = t / (nchunk / 4);
-  const long long row = rt * 16 + r, ch = ks * 4 + ga;
+__device__ __forceinline__ void compress_unit_2_4(const uint16_t* wrow, const uint8_t* __restrict__ mrow /*mask row or null*/,
+                                                  const int32_t* __restrict__ perm, bool live, long long row, long long ch,
+                                                  long long K, long long Kp, uint16_t* __restrict__ values,
+                                                  uint32_t* __restrict__ meta, uint16_t* __restrict__ nvalues,
+                                                  uint16_t* __restrict__ nmeta, int* __restrict__ flags) {
   uint16_t kept[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   uint32_t bits = 0;
   int nk = 0;  // kept values in this unit (8 unless the unit is cut by K or is padding)
   const long long p0 = ch * 16;
-  if (row < N && p0 < K) {
+  if (live && p0 < K) {
     const int ngroups = (int)((K - p0) >= 16 ? 4 : (K - p0) / 4);
-    for (int g = 0; g < ngroups; g++) {
-      uint16_t w[4];
-      uint8_t mk[4];
-#pragma unroll
-      for (int i = 0; i < 4; i++) {
-        long long p = p0 + g * 4 + i;
-        long long c = perm ? perm[p] : p;
-        w[i] = W[row * K + c];
-        mk[i] = mask ? mask[row * K + p] : 0;
+    uint32_t mk4[4] = {0, 0, 0, 0};
+    if (mrow) {
+      if (ngroups == 4 && (K & 15) == 0) {
+        const uint4 mv = *reinterpret_cast<const uint4*>(mrow + p0);
+        mk4[0] = mv.x; mk4[1] = mv.y; mk4[2] = mv.z; mk4[3] = mv.w;
+      } else {
+        for (int g = 0; g < ngroups; g++) mk4[g] = *reinterpret_cast<const uint32_t*>(mrow + p0 + g * 4);
       }
-      if (!mask) {
+    }
+    bool bad = false;
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      if (g >= ngroups) break;
+      uint16_t w[4];
+      int c4[4];
+      if (perm) {
+        const int4 pv = *reinterpret_cast<const int4*>(perm + p0 + g * 4);
+        c4[0] = pv.x; c4[1] = pv.y; c4[2] = pv.z; c4[3] = pv.w;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; i++) c4[i] = (int)(p0 + g * 4 + i);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; i++) w[i] = wrow[c4[i]];
+      uint32_t mk;  // one byte per position, non-zero = kept
+      if (mrow) {
+        mk = mk4[g];
+      } else {
         // keep the non-zero weights, topped up with the lowest-position zeros
+        mk = 0;
         int nz = 0;
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
-          mk[i] = (w[i] & 0x7fffu) ? 1 : 0;
-          nz += mk[i];
-        }
-        if (nz > 2) atomicOr(flags, 1);
+        for (int i = 0; i < 4; i++)
+          if (w[i] & 0x7fffu) {
+            mk |= 1u << (8 * i);
+            nz++;
+          }
+        if (nz > 2) bad = true;
 #pragma unroll
         for (int i = 0; i < 4; i++)
-          if (nz < 2 && !mk[i]) {
-            mk[i] = 1;
+          if (nz < 2 && !((mk >> (8 * i)) & 0xffu)) {
+            mk |= 1u << (8 * i);
             nz++;
           }
       }
       int cnt = 0;
 #pragma unroll
       for (int i = 0; i < 4; i++)
-        if (mk[i]) {
+        if ((mk >> (8 * i)) & 0xffu) {
           if (cnt < 2) {
-            kept[nk] = w[i];
-            bits |= (uint32_t)i << (2 * nk);
-            nk++;
+            // nk = 2 g + cnt : compile-time g, so the two slots are selected without dynamic indexing
+            if (cnt == 0) kept[2 * g] = w[i];
+            else kept[2 * g + 1] = w[i];
+            bits |= (uint32_t)i << (2 * (2 * g + cnt));
           }
           cnt++;
         }
-      if (cnt != 2) {
-        atomicOr(flags, 1);
-        while (cnt < 2) {  // keep the layout well-formed; the call reports EBADMASK
-          nk++;
-          cnt++;
-        }
-      }
+      if (cnt != 2) bad = true;  // the call reports EBADMASK; the slot layout stays well-formed
+      nk = 2 * g + 2;
     }
-    // canonical: values[row][ch*8 .. ch*8+nk), meta halves
+    if (bad) atomicOr(flags, 1);
+    // canonical: values[row][ch*8 .. ch*8+nk), index half-words
     if (values) {
       uint16_t* dst = values + row * (K / 2) + ch * 8;
       if (nk == 8 && ((K / 2) % 8 == 0)) {
@@ -93,7 +103,9 @@ __global__ void __launch_bounds__(256) k_compress_2_4(const uint16_t* __restrict
         v.w = kept[6] | ((uint32_t)kept[7] << 16);
         *reinterpret_cast<uint4*>(dst) = v;
       } else {
-        for (int i = 0; i < nk; i++) dst[i] = kept[i];
+#pragma unroll
+        for (int i = 0; i < 8; i++)
+          if (i < nk) dst[i] = kept[i];
       }
     }
     if (meta) {
@@ -104,15 +116,66 @@ __global__ void __launch_bounds__(256) k_compress_2_4(const uint16_t* __restrict
     }
   }
   if (nvalues) {
+    const long long nchunk = Kp / 16;
+    const long long rt = row >> 4, ks = ch >> 2;
+    const int r = (int)(row & 15), ga = (int)(ch & 3);
     uint4 v;
     v.x = kept[0] | ((uint32_t)kept[1] << 16);
     v.y = kept[2] | ((uint32_t)kept[3] << 16);
     v.z = kept[4] | ((uint32_t)kept[5] << 16);
     v.w = kept[6] | ((uint32_t)kept[7] << 16);
-    reinterpret_cast<uint4*>(nvalues)[u] = v;
-    // meta unit order [rt][ks/4][ga][r][ks%4]
-    const long long mi = (((rt * (nchunk / 16) + ks / 4) * 4 + ga) * 16 + r) * 4 + (ks % 4);
-    nmeta[mi] = (uint16_t)bits;
+    reinterpret_cast<uint4*>(nvalues)[((rt * (nchunk / 4) + ks) * 4 + ga) * 16 + r] = v;
+    // index unit order [rt][ks/4][ga][r][ks%4]
+    nmeta[(((rt * (nchunk / 16) + ks / 4) * 4 + ga) * 16 + r) * 4 + (ks & 3)] = (uint16_t)bits;
+  }
+}
+
+// Generic form: one thread per unit, weights gathered from global memory (any K).
+__global__ void __launch_bounds__(256) k_compress_2_4(const uint16_t* __restrict__ W, const uint8_t* __restrict__ mask,
+                                                       const int32_t* __restrict__ perm, long long N, long long K, long long Np,
+                                                       long long Kp, uint16_t* __restrict__ values, uint32_t* __restrict__ meta,
+                                                       uint16_t* __restrict__ nvalues, uint16_t* __restrict__ nmeta,
+                                                       int* __restrict__ flags) {
+  const long long nchunk = Kp / 16;
+  long long u = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (u >= Np * nchunk) return;
+  // thread order = native unit order, so the native stores are coalesced
+  const int r = (int)(u & 15), ga = (int)((u >> 4) & 3);
+  const long long t = u >> 6;
+  const long long ks = t % (nchunk / 4), rt = t / (nchunk / 4);
+  const long long row = rt * 16 + r, ch = ks * 4 + ga;
+  const bool live = row < N;
+  compress_unit_2_4(W + (live ? row : 0) * K, mask ? mask + (live ? row : 0) * K : nullptr, perm, live, row, ch, K, Kp, values,
+                    meta, nvalues, nmeta, flags);
+}
+
+// Fast form: a workgroup copies RB whole rows of W into LDS with coalesced loads and gathers the
+// permuted channels from there, so HBM sees W exactly once, in order.  Needs 2*K*RB bytes of LDS.
+__global__ void __launch_bounds__(512) k_compress_2_4_rows(const uint16_t* __restrict__ W, const uint8_t* __restrict__ mask,
+                                                            const int32_t* __restrict__ perm, long long N, long long K,
+                                                            long long Np, long long Kp, int RB, uint16_t* __restrict__ values,
+                                                            uint32_t* __restrict__ meta, uint16_t* __restrict__ nvalues,
+                                                            uint16_t* __restrict__ nmeta, int* __restrict__ flags) {
+  extern __shared__ uint2 s_w2[];  // [RB][K / 4] groups of 4 weights
+  const int tid = threadIdx.x;
+  const long long row0 = (long long)blockIdx.x * RB;
+  const int k4 = (int)(K / 4);
+  const uint2* W2 = reinterpret_cast<const uint2*>(W);
+  for (int r = 0; r < RB; r++) {
+    const long long row = row0 + r;
+    if (row >= N) break;
+    for (int c = tid; c < k4; c += 512) s_w2[r * k4 + c] = W2[row * k4 + c];
+  }
+  __syncthreads();
+  const uint16_t* s_w = reinterpret_cast<const uint16_t*>(s_w2);
+  const int nchunk = (int)(Kp / 16);
+  for (int e = tid; e < RB * nchunk; e += 512) {
+    const int r = e % RB, ch = e / RB;
+    const long long row = row0 + r;
+    if (row >= Np) continue;
+    const bool live = row < N;
+    compress_unit_2_4(s_w + (size_t)r * K, (mask && live) ? mask + row * K : nullptr, perm, live, row, ch, K, Kp, values, meta,
+                      nvalues, nmeta, flags);
   }
 }
 
@@ -190,8 +253,20 @@ int esp_compress_device(esparse_ctx* ctx, const void* Wv, const uint8_t* mask, c
     uint16_t* nvalues = reinterpret_cast<uint16_t*>(native_out);
     uint16_t* nmeta = native_out ? reinterpret_cast<uint16_t*>(reinterpret_cast<unsigned char*>(native_out) + (size_t)Np * Kp) : nullptr;
     const long long units = Np * (Kp / 16);
-    hipLaunchKernelGGL(k_compress_2_4, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, st, W, mask, perm, N, K, Np, Kp,
-                       reinterpret_cast<uint16_t*>(values_out), reinterpret_cast<uint32_t*>(meta_out), nvalues, nmeta, flags);
+    const size_t row_bytes = (size_t)K * 2;
+    const size_t lds_budget = row_bytes <= 64 * 1024 ? 64 * 1024 : 144 * 1024;
+    int RB = (int)std::min<size_t>(16, lds_budget / row_bytes);
+    if (RB >= 1) {
+      const size_t smem = (size_t)RB * row_bytes;
+      if (smem > 64 * 1024)
+        ESP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_compress_2_4_rows),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      hipLaunchKernelGGL(k_compress_2_4_rows, dim3((unsigned)((Np + RB - 1) / RB)), dim3(512), smem, st, W, mask, perm, N, K, Np, Kp,
+                         RB, reinterpret_cast<uint16_t*>(values_out), reinterpret_cast<uint32_t*>(meta_out), nvalues, nmeta, flags);
+    } else {
+      hipLaunchKernelGGL(k_compress_2_4, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, st, W, mask, perm, N, K, Np, Kp,
+                         reinterpret_cast<uint16_t*>(values_out), reinterpret_cast<uint32_t*>(meta_out), nvalues, nmeta, flags);
+    }
   } else {
     const long long groups = N * (K / 8);
     hipLaunchKernelGGL(k_compress_4_8, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, W, mask, perm, N, K,

@@ -157,7 +157,7 @@ def test_config1_against_stored_oracle_results(esp, ctx):
 
 
 # ---------------------------------------------------------------- compression
-@pytest.mark.parametrize("N,K", [(24, 320), (16, 256), (5, 36), (130, 1040)])
+@pytest.mark.parametrize("N,K", [(24, 320), (16, 256), (5, 36), (130, 1040), (33, 36864), (3, 81920)])
 @pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
 def test_compress_2_4_bit_exact(esp, ctx, N, K, dtype):
     W = _rand((N, K), dtype, 31)
