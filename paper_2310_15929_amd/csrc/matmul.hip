@@ -31,6 +31,31 @@
 #define MAX_SPLIT 16
 
 // ------------------------------------------------------------------------------------------------
+// device-only intrinsics (hipcc also parses kernels in its host pass, where these do not exist)
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ int wave_uniform(int v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_amdgcn_readfirstlane(v);
+#else
+  return v;
+#endif
+}
+// 16 bytes per lane from global memory straight into LDS: lane l lands at lds_wave_base + 16 l
+__device__ __forceinline__ void global_to_lds_16(const uint4* gsrc, uint4* lds_wave_base) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_global_load_lds(gsrc, lds_wave_base, 16, 0, 0);
+#else
+  (void)gsrc;
+  (void)lds_wave_base;
+#endif
+}
+__device__ __forceinline__ void sched_fence() {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_sched_barrier(0);
+#endif
+}
+
+// ------------------------------------------------------------------------------------------------
 // instruction wrappers
 // ------------------------------------------------------------------------------------------------
 template <int DT, int ABID>
@@ -325,9 +350,139 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(const uint4* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------------
+// variant "tile" (prefill sizes, MFMA-bound): a workgroup of 4 waves (2 x 2) owns a macro tile of
+// 32*TR output rows x 32*TC tokens; each wave owns TR x TC tiles of 16 x 16 (TR = TC = 8: 128 x 128,
+// 256 accumulator registers).  Per 64-channel stage the workgroup copies the macro tile's slice of the
+// staged activations (2*TC KiB per 16 tokens... 4*TC KiB in all) into LDS, double buffered, one barrier
+// per stage; every wave takes its TR compressed weight operands (and their index halves) straight from
+// memory into registers one stage ahead, and walks its TC token tiles reading each B operand from
+// LDS once for TR multiplies.  Macro tiles are numbered so that the workgroups of one XCD
+// (blockIdx % 8) cover neighbouring tiles and share weight rows in that XCD's L2.
+// ------------------------------------------------------------------------------------------------
+template <int DT, int SPARSE, int TR, int TC>
+__global__ void __launch_bounds__(256) k_mm_tile(const uint4* __restrict__ A, const uint16_t* __restrict__ meta16,
+                                                  const uint4* __restrict__ Xf, uint16_t* __restrict__ Y, long long M,
+                                                  long long N, long long Mp, long long Np, long long Kp, long long n_tiles,
+                                                  long long ntb) {
+  extern __shared__ uint4 s_b[];  // [2 buffers][2 * TC token tiles][2 half steps][64 lanes]
+  constexpr int NTT = 2 * TC;     // token tiles of 16 in the macro tile
+  constexpr int STAGE_UNITS = NTT * 128;
+  constexpr int COPIES = STAGE_UNITS / 256;  // 16-byte units per thread per stage
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = wave_uniform(tid >> 6);  // wave-uniform: keeps the operand bases in SGPRs
+  const int wr = wave >> 1, wc = wave & 1;
+  const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
+  // XCD-aware numbering: XCD x (= blockIdx % 8) works through tiles [x * per, (x + 1) * per)
+  const long long per = (n_tiles + 7) / 8;
+  const long long tile = (long long)(blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if ((long long)(blockIdx.x >> 3) >= per || tile >= n_tiles) return;
+  const long long rb = tile / ntb, tb = tile % ntb;
+  const long long rt_base = rb * (2 * TR) + wr * TR;  // first row tile of this wave
+  const long long tt_base = tb * NTT;                 // first token tile of the macro tile
+
+  // wave-uniform operand bases; per-lane offsets are 32-bit
+  const uint4* a_ptr[TR];
+  const uint16_t* m_ptr[TR];
+#pragma unroll
+  for (int i = 0; i < TR; i++) {
+    const long long rt = (rt_base + i < nrt) ? rt_base + i : nrt - 1;
+    a_ptr[i] = A + (SPARSE ? rt * nks : rt * (2 * nks)) * 64;
+    m_ptr[i] = meta16 + rt * (nks / 4) * 256;
+  }
+  const uint4* x_ptr[COPIES];
+#pragma unroll
+  for (int p = 0; p < COPIES; p++) {
+    const long long ttl = 2 * p + (wave >> 1);  // token tile (within the macro tile) of this wave's p-th copy
+    const long long tt = (tt_base + ttl < ntt) ? tt_base + ttl : ntt - 1;
+    x_ptr[p] = Xf + tt * (2 * nks) * 64;
+  }
+  const unsigned x_lane = (unsigned)(tid & 127);
+  const unsigned nks32 = (unsigned)nks;
+
+  floatx4_t acc[TR][TC];
+#pragma unroll
+  for (int i = 0; i < TR; i++)
+#pragma unroll
+    for (int j = 0; j < TC; j++) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+  uint4 a[2][TR], a2[2][TR];
+  int idx[2][TR];
+
+  // prologue: stage 0.  The activations go from global memory straight into LDS (16 bytes per lane,
+  // lane l of a wave lands at the wave's LDS base + 16 l), so they never occupy registers.
+#pragma unroll
+  for (int p = 0; p < COPIES; p++)
+    global_to_lds_16(x_ptr[p] + x_lane, s_b + 256 * p + wave * 64);
+#pragma unroll
+  for (int i = 0; i < TR; i++) {
+    if (SPARSE) {
+      a[0][i] = a_ptr[i][lane];
+      idx[0][i] = (int)m_ptr[i][lane * 4];
+    } else {
+      a[0][i] = a_ptr[i][lane];
+      a2[0][i] = a_ptr[i][lane + 64];
+    }
+  }
+  __syncthreads();
+
+  for (unsigned ks = 0; ks < nks32; ks += 2) {
+#pragma unroll
+    for (int par = 0; par < 2; par++) {
+      const unsigned k = ks + par;
+      // loads of the next stage (the last stage reloads itself: no branch, the copy is never used)
+      const unsigned kn = (k + 1 < nks32) ? k + 1 : k;
+#pragma unroll
+      for (int p = 0; p < COPIES; p++)
+        global_to_lds_16(x_ptr[p] + (kn * 128u + x_lane), s_b + (par ^ 1) * STAGE_UNITS + 256 * p + wave * 64);
+#pragma unroll
+      for (int i = 0; i < TR; i++) {
+        if (SPARSE) {
+          a[par ^ 1][i] = a_ptr[i][kn * 64u + lane];
+          idx[par ^ 1][i] = (int)m_ptr[i][(kn >> 2) * 256u + lane * 4u + (kn & 3u)];
+        } else {
+          a[par ^ 1][i] = a_ptr[i][kn * 128u + lane];
+          a2[par ^ 1][i] = a_ptr[i][kn * 128u + 64u + lane];
+        }
+      }
+      sched_fence();  // keep the next stage's loads ahead of this stage's multiplies
+      // multiply stage k out of LDS buffer `par`
+      const uint4* sb = s_b + par * STAGE_UNITS + (wc * TC) * 128 + lane;
+#pragma unroll
+      for (int j = 0; j < TC; j++) {
+        const uint4 b0 = sb[j * 128];
+        const uint4 b1 = sb[j * 128 + 64];
+#pragma unroll
+        for (int i = 0; i < TR; i++) {
+          if (SPARSE) {
+            acc[i][j] = smfmac16<DT, 0>(a[par][i], b0, b1, acc[i][j], idx[par][i]);
+          } else {
+            acc[i][j] = mfma16<DT>(a[par][i], b0, acc[i][j]);
+            acc[i][j] = mfma16<DT>(a2[par][i], b1, acc[i][j]);
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+
+  const int c = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < TR; i++) {
+    const long long rt = rt_base + i;
+    if (rt >= nrt) continue;
+#pragma unroll
+    for (int j = 0; j < TC; j++) {
+      const long long tt = tt_base + wc * TC + j;
+      if (tt >= ntt) continue;
+      store_y4<DT>(Y, M, N, tt * 16 + c, rt * 16 + g * 4, acc[i][j]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // variant table and host launcher
 // ------------------------------------------------------------------------------------------------
-enum { KIND_WAVE = 0, KIND_KSPLIT = 1 };
+enum { KIND_WAVE = 0, KIND_KSPLIT = 1, KIND_TILE = 2 };
 struct Variant {
   const char* name;
   int kind;
@@ -346,6 +501,9 @@ static const Variant kVariants[] = {
     {"ksplit_w8_r2", KIND_KSPLIT, 2, 0, 0, 8},
     {"ksplit_w8_r4", KIND_KSPLIT, 4, 0, 0, 8},
     {"ksplit_w16_r3", KIND_KSPLIT, 3, 0, 0, 16},
+    {"tile_256x256", KIND_TILE, 8, 8, 0, 0},
+    {"tile_256x128", KIND_TILE, 8, 4, 0, 0},
+    {"tile_128x128", KIND_TILE, 4, 4, 0, 0},
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -360,6 +518,7 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
   const Variant& var = kVariants[v];
   if (var.kind == KIND_WAVE && var.split_mode == 1 && M > 128) return false;  // partial buffers are sized for decode only
   if (var.kind == KIND_KSPLIT && M > 32) return false;
+  if (var.kind == KIND_TILE && M < 64) return false;
   return true;
 }
 
@@ -371,7 +530,7 @@ int esp_default_variant(long long M, long long N, long long K, int sparse) {
     return nrt <= 320 ? 4 : 5;  // ksplit_w16_r1 / ksplit_w16_r2
   }
   if (M <= 128) return 1;  // wave_r2_t2_splitk
-  return 3;                // wave_r4_t4
+  return 12;               // tile_128x128
 }
 
 size_t esp_workspace_bytes(long long M, long long N, long long K) {
@@ -411,6 +570,30 @@ static void launch_ksplit(const Variant& v, hipStream_t st, const uint4* A, cons
   else if (v.nw == 8 && v.rt == 2) LAUNCH(2, 8);
   else LAUNCH(4, 8);
 #undef LAUNCH
+}
+
+template <int DT, int SPARSE>
+static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const uint4* A, const uint16_t* meta16, const uint4* Xf,
+                       uint16_t* Y, long long M, long long N, long long Mp, long long Np, long long Kp) {
+  const long long nrt = Np / 16, ntt = Mp / 16;
+  const long long nrb = (nrt + 2 * v.rt - 1) / (2 * v.rt), ntb = (ntt + 2 * v.tt - 1) / (2 * v.tt);
+  const long long n_tiles = nrb * ntb;
+  const long long per = (n_tiles + 7) / 8;
+  dim3 grid((unsigned)(per * 8));
+  const size_t smem = (size_t)2 * (2 * v.tt) * 128 * 16;
+#define LAUNCH(R, T)                                                                                                   \
+  do {                                                                                                                 \
+    if (smem > 48 * 1024)                                                                                              \
+      ESP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_mm_tile<DT, SPARSE, R, T>),                    \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));                        \
+    hipLaunchKernelGGL((k_mm_tile<DT, SPARSE, R, T>), grid, dim3(256), smem, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp, n_tiles, ntb); \
+  } while (0)
+  if (v.rt == 8 && v.tt == 8) LAUNCH(8, 8);
+  else if (v.rt == 8 && v.tt == 4) LAUNCH(8, 4);
+  else LAUNCH(4, 4);
+#undef LAUNCH
+  ESP_HIP(ctx, hipGetLastError());
+  return ESPARSE_OK;
 }
 
 static int stage_activations(esparse_ctx* ctx, const void* X, const int32_t* perm, long long M, long long K, long long Mp,
@@ -455,6 +638,15 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
     }
     ESP_HIP(ctx, hipGetLastError());
     return ESPARSE_OK;
+  }
+
+  if (v.kind == KIND_TILE) {
+    const uint16_t* meta16 = reinterpret_cast<const uint16_t*>(meta_bytes);
+    if (dtype == ESPARSE_F16)
+      return sparse ? launch_tile<ESPARSE_F16, 1>(ctx, v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp)
+                    : launch_tile<ESPARSE_F16, 0>(ctx, v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
+    return sparse ? launch_tile<ESPARSE_BF16, 1>(ctx, v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp)
+                  : launch_tile<ESPARSE_BF16, 0>(ctx, v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
   }
 
   // ---- wave-tile kinds

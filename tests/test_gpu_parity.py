@@ -151,7 +151,11 @@ def test_config1_against_stored_oracle_results(esp, ctx):
     mask = res.mask.cpu().numpy()
     Yref = orc.spmm_ref(X.numpy(), W.numpy(), theta, mask)
     for v in range(esp.num_variants()):
-        Y = ctx.spmm(X.cuda(), comp, res.perm, variant=v)
+        try:
+            Y = ctx.spmm(X.cuda(), comp, res.perm, variant=v)
+        except esp.EsparseError as e:
+            assert e.code == -2                      # variant not applicable to this M
+            continue
         err = orc.rowwise_rel_error(_np(Y), Yref)
         assert err.max() <= 2e-3, (esp.variant_name(v), err.max())
 
