@@ -49,6 +49,23 @@ __device__ __forceinline__ void global_to_lds_16(const uint4* gsrc, uint4* lds_w
   (void)lds_wave_base;
 #endif
 }
+// scheduling hint: the next SIZE instructions of class MASK (0x008 matrix, 0x100 LDS read) form one
+// group; consecutive groups are issued in the order the hints are written
+template <int MASK, int SIZE>
+__device__ __forceinline__ void sched_group() {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_sched_group_barrier(MASK, SIZE, 0);
+#endif
+}
+// 4 bytes per lane from global memory straight into LDS: lane l lands at lds_wave_base + 4 l
+__device__ __forceinline__ void global_to_lds_4(const uint32_t* gsrc, uint32_t* lds_wave_base) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_global_load_lds(gsrc, lds_wave_base, 4, 0, 0);
+#else
+  (void)gsrc;
+  (void)lds_wave_base;
+#endif
+}
 __device__ __forceinline__ void sched_fence() {
 #if defined(__HIP_DEVICE_COMPILE__)
   __builtin_amdgcn_sched_barrier(0);
@@ -351,132 +368,215 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(const uint4* __restrict__
 
 // ------------------------------------------------------------------------------------------------
 // variant "tile" (prefill sizes, MFMA-bound): a workgroup of 4 waves (2 x 2) owns a macro tile of
-// 32*TR output rows x 32*TC tokens; each wave owns TR x TC tiles of 16 x 16 (TR = TC = 8: 128 x 128,
-// 256 accumulator registers).  Per 64-channel stage the workgroup copies the macro tile's slice of the
-// staged activations (2*TC KiB per 16 tokens... 4*TC KiB in all) into LDS, double buffered, one barrier
-// per stage; every wave takes its TR compressed weight operands (and their index halves) straight from
-// memory into registers one stage ahead, and walks its TC token tiles reading each B operand from
-// LDS once for TR multiplies.  Macro tiles are numbered so that the workgroups of one XCD
-// (blockIdx % 8) cover neighbouring tiles and share weight rows in that XCD's L2.
+// RTM row tiles x 2*TC token tiles (of 16); each wave owns TR x TC tiles (sparse: TR = TC = 8, i.e.
+// 128 x 128 outputs and 256 accumulator registers, one wave per SIMD; RTM = 2 TR).
+// The K loop runs in 64-channel stages, software pipelined TWO stages ahead:
+//   - the macro tile's slice of the staged activations (4*TC KiB per stage), of the weights (16 KiB
+//     per stage) and of the index words (4 KiB per stage pair) are copied by DMA from global memory
+//     straight into LDS (three buffers each, no registers involved);
+//   - a stage ends with a counted wait (all vector-memory operations but the newest stage's DMA have
+//     finished, so the next stage's buffers are full) and a barrier.
+// The LDS buffers are separate __shared__ arrays handed to the pipeline as __restrict__ pointers:
+// that is what lets the compiler see that reading buffer k does not have to wait for the DMA into
+// buffer k+2.  Each wave reads its TR A operands once per stage and each B operand once for TR
+// multiplies.  Macro tiles are numbered so that the workgroups of one XCD (blockIdx % 8) cover
+// neighbouring tiles and share weight rows in that XCD's L2.
 // ------------------------------------------------------------------------------------------------
+template <int TR, int TC>
+struct TileState {
+  static constexpr int BCOPIES = (2 * TC * 128) / 256;  // 16-byte units of activations per lane and stage
+  static constexpr int ACOPIES = 4;                     // 1024 units of weights per stage
+  floatx4_t acc[TR][TC];
+  const uint4* a_src[ACOPIES];  // wave-uniform global bases of this wave's DMA copies
+  const uint4* x_src[BCOPIES];
+  const uint32_t* m_src[ACOPIES];  // index words (two stages of index halves per lane) of the copied row tiles
+  unsigned lane, x_lane, wave, wr, wc, nks;
+};
+
+template <int SPARSE, int TR, int TC>
+__device__ __forceinline__ void tile_prefetch(TileState<TR, TC>& st, uint4* sa, uint4* sb, uint32_t* sm, unsigned kn) {
+  // every vector-memory operation of the pipeline is a DMA into LDS: they keep their program order,
+  // which the stage-end wait counts on
+#pragma unroll
+  for (int p = 0; p < TileState<TR, TC>::BCOPIES; p++)
+    global_to_lds_16(st.x_src[p] + (kn * 128u + st.x_lane), sb + 256 * p + st.wave * 64);
+#pragma unroll
+  for (int p = 0; p < TileState<TR, TC>::ACOPIES; p++) {
+    // sparse: copy p of wave w is row tile 4 p + w (64 units); dense: row tile 2 p + w / 2, half w % 2
+    const unsigned off = SPARSE ? kn * 64u + st.lane : kn * 128u + (st.wave & 1u) * 64u + st.lane;
+    global_to_lds_16(st.a_src[p] + off, sa + 256 * p + st.wave * 64);
+    // the lane's index word holding stage kn: 8 bytes per lane and group of 4 stages, word (kn % 4) / 2
+    if (SPARSE) global_to_lds_4(st.m_src[p] + ((kn >> 2) * 128u + st.lane * 2u + ((kn >> 1) & 1u)), sm + 256 * p + st.wave * 64);
+  }
+}
+
 template <int DT, int SPARSE, int TR, int TC>
-__global__ void __launch_bounds__(256) k_mm_tile(const uint4* __restrict__ A, const uint16_t* __restrict__ meta16,
-                                                  const uint4* __restrict__ Xf, uint16_t* __restrict__ Y, long long M,
-                                                  long long N, long long Mp, long long Np, long long Kp, long long n_tiles,
-                                                  long long ntb) {
-  extern __shared__ uint4 s_b[];  // [2 buffers][2 * TC token tiles][2 half steps][64 lanes]
-  constexpr int NTT = 2 * TC;     // token tiles of 16 in the macro tile
-  constexpr int STAGE_UNITS = NTT * 128;
-  constexpr int COPIES = STAGE_UNITS / 256;  // 16-byte units per thread per stage
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = wave_uniform(tid >> 6);  // wave-uniform: keeps the operand bases in SGPRs
-  const int wr = wave >> 1, wc = wave & 1;
+__device__ __forceinline__ void tile_multiply(TileState<TR, TC>& st, const uint4* sa, const uint4* sb, const uint32_t* sm,
+                                              unsigned k) {
+  uint4 a[SPARSE ? TR : 2 * TR];
+  int idx[TR];
+  if (SPARSE) {
+    const unsigned sh = (k & 1u) * 16u;  // the word holds the index halves of an even and an odd stage
+#pragma unroll
+    for (int i = 0; i < TR; i++) idx[i] = (int)(sm[(st.wr * TR + i) * 64 + st.lane] >> sh);
+  }
+#pragma unroll
+  for (int i = 0; i < TR; i++) {
+    if (SPARSE) {
+      a[i] = sa[(st.wr * TR + i) * 64 + st.lane];
+    } else {
+      a[2 * i] = sa[(st.wr * TR + i) * 128 + st.lane];
+      a[2 * i + 1] = sa[(st.wr * TR + i) * 128 + 64 + st.lane];
+    }
+  }
+  const uint4* b = sb + (st.wc * TC) * 128 + st.lane;
+  // B operands are read one token tile ahead of the multiplies that use them
+  uint4 b0 = b[0], b1 = b[64];
+#pragma unroll
+  for (int j = 0; j < TC; j++) {
+    uint4 n0 = b0, n1 = b1;
+    if (j + 1 < TC) {
+      n0 = b[(j + 1) * 128];
+      n1 = b[(j + 1) * 128 + 64];
+    }
+#pragma unroll
+    for (int i = 0; i < TR; i++) {
+      if (SPARSE) {
+        st.acc[i][j] = smfmac16<DT, 0>(a[i], b0, b1, st.acc[i][j], idx[i]);
+      } else {
+        st.acc[i][j] = mfma16<DT>(a[2 * i], b0, st.acc[i][j]);
+        st.acc[i][j] = mfma16<DT>(a[2 * i + 1], b1, st.acc[i][j]);
+      }
+    }
+    b0 = n0;
+    b1 = n1;
+  }
+  // the order wanted for this region: all A operands and the first B operand, then for every token
+  // tile "read the next B operand, multiply with the current one"
+  sched_group<0x100, (SPARSE ? 2 * TR : 2 * TR) + 2>();
+#pragma unroll
+  for (int j = 0; j < TC; j++) {
+    if (j + 1 < TC) sched_group<0x100, 2>();
+    sched_group<0x008, SPARSE ? TR : 2 * TR>();
+  }
+}
+
+// End of a stage: wait until at most the DMA operations of the newest prefetch are outstanding (they
+// are the last vector-memory operations issued, and DMA keeps its program order), so every older DMA
+// - in particular the one that filled the next stage's buffers - has landed; then meet the other waves.
+template <int DMA_PER_STAGE>
+__device__ __forceinline__ void tile_arrive() {
+#if defined(__HIP_DEVICE_COMPILE__)
+  // s_waitcnt: vmcnt = DMA_PER_STAGE (6 bits, split 3:0 / 15:14), expcnt and lgkmcnt left at "do not wait"
+  __builtin_amdgcn_s_waitcnt((DMA_PER_STAGE & 15) | ((DMA_PER_STAGE >> 4) << 14) | 0x0F70);
+  __builtin_amdgcn_s_barrier();
+#endif
+}
+
+// one pipeline stage: prefetch stage k+2 into the PRE buffers, multiply stage k out of the CUR buffers,
+// make sure stage k+1 has landed for everybody
+template <int DT, int SPARSE, int TR, int TC>
+__device__ __forceinline__ void tile_stage(TileState<TR, TC>& st, const uint4* sa_cur, const uint4* sb_cur,
+                                           const uint32_t* sm_cur, uint4* sa_pre, uint4* sb_pre, uint32_t* sm_pre,
+                                           unsigned k) {
+  constexpr int DMA = TileState<TR, TC>::BCOPIES + (SPARSE ? 2 : 1) * TileState<TR, TC>::ACOPIES;
+  const unsigned kn = (k + 2 < st.nks) ? k + 2 : st.nks - 1;  // past the end: reload the last stage (never used)
+  tile_prefetch<SPARSE, TR, TC>(st, sa_pre, sb_pre, sm_pre, kn);
+  sched_fence();  // keep the prefetch ahead of this stage's multiplies
+  tile_multiply<DT, SPARSE, TR, TC>(st, sa_cur, sb_cur, sm_cur, k);
+  sched_fence();
+  tile_arrive<DMA>();
+}
+
+template <int DT, int SPARSE, int TR, int TC>
+__device__ __attribute__((always_inline)) void tile_pipeline(
+    uint4* __restrict__ sa0, uint4* __restrict__ sa1, uint4* __restrict__ sa2, uint4* __restrict__ sb0, uint4* __restrict__ sb1,
+    uint4* __restrict__ sb2, uint32_t* __restrict__ sm0, uint32_t* __restrict__ sm1, uint32_t* __restrict__ sm2,
+    const uint4* __restrict__ A, const uint16_t* __restrict__ meta16, const uint4* __restrict__ Xf,
+    uint16_t* __restrict__ Y, long long M, long long N, long long Mp, long long Np, long long Kp, long long n_tiles,
+    long long ntb) {
+  constexpr int NTT = 2 * TC;                 // token tiles of 16 in the macro tile
+  constexpr int RTM = 2 * TR;                 // row tiles of 16 in the macro tile (sparse 16, dense 8)
+  using State = TileState<TR, TC>;
+  const int tid = threadIdx.x;
+  State st;
+  st.lane = (unsigned)(tid & 63);
+  st.wave = (unsigned)wave_uniform(tid >> 6);  // wave-uniform: keeps the operand bases in SGPRs
+  st.wr = st.wave >> 1;
+  st.wc = st.wave & 1u;
   const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
+  st.nks = (unsigned)nks;
   // XCD-aware numbering: XCD x (= blockIdx % 8) works through tiles [x * per, (x + 1) * per)
   const long long per = (n_tiles + 7) / 8;
   const long long tile = (long long)(blockIdx.x & 7) * per + (blockIdx.x >> 3);
   if ((long long)(blockIdx.x >> 3) >= per || tile >= n_tiles) return;
   const long long rb = tile / ntb, tb = tile % ntb;
-  const long long rt_base = rb * (2 * TR) + wr * TR;  // first row tile of this wave
-  const long long tt_base = tb * NTT;                 // first token tile of the macro tile
-
-  // wave-uniform operand bases; per-lane offsets are 32-bit
-  const uint4* a_ptr[TR];
-  const uint16_t* m_ptr[TR];
+  const long long rt_macro = rb * RTM;  // first row tile of the macro tile
+  const long long tt_base = tb * NTT;   // first token tile of the macro tile
 #pragma unroll
-  for (int i = 0; i < TR; i++) {
-    const long long rt = (rt_base + i < nrt) ? rt_base + i : nrt - 1;
-    a_ptr[i] = A + (SPARSE ? rt * nks : rt * (2 * nks)) * 64;
-    m_ptr[i] = meta16 + rt * (nks / 4) * 256;
+  for (int p = 0; p < State::ACOPIES; p++) {
+    const long long rtl = SPARSE ? 4 * p + st.wave : 2 * p + (st.wave >> 1);  // row tile this wave copies
+    const long long rt = (rt_macro + rtl < nrt) ? rt_macro + rtl : nrt - 1;
+    st.a_src[p] = A + (SPARSE ? rt * nks : rt * (2 * nks)) * 64;
+    st.m_src[p] = reinterpret_cast<const uint32_t*>(meta16) + rt * (nks / 4) * 128;
   }
-  const uint4* x_ptr[COPIES];
 #pragma unroll
-  for (int p = 0; p < COPIES; p++) {
-    const long long ttl = 2 * p + (wave >> 1);  // token tile (within the macro tile) of this wave's p-th copy
+  for (int p = 0; p < State::BCOPIES; p++) {
+    const long long ttl = 2 * p + (st.wave >> 1);  // token tile (within the macro tile) of this wave's p-th copy
     const long long tt = (tt_base + ttl < ntt) ? tt_base + ttl : ntt - 1;
-    x_ptr[p] = Xf + tt * (2 * nks) * 64;
+    st.x_src[p] = Xf + tt * (2 * nks) * 64;
   }
-  const unsigned x_lane = (unsigned)(tid & 127);
-  const unsigned nks32 = (unsigned)nks;
-
-  floatx4_t acc[TR][TC];
+  st.x_lane = (unsigned)(tid & 127);
 #pragma unroll
   for (int i = 0; i < TR; i++)
 #pragma unroll
-    for (int j = 0; j < TC; j++) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < TC; j++) st.acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
-  uint4 a[2][TR], a2[2][TR];
-  int idx[2][TR];
+  // prologue: stages 0 and 1 in flight, then wait for stage 0
+  tile_prefetch<SPARSE, TR, TC>(st, sa0, sb0, sm0, 0u);
+  tile_prefetch<SPARSE, TR, TC>(st, sa1, sb1, sm1, st.nks > 1 ? 1u : 0u);
+  sched_fence();
+  tile_arrive<State::BCOPIES + (SPARSE ? 2 : 1) * State::ACOPIES>();
+  unsigned k = 0;
+  for (; k + 3 <= st.nks; k += 3) {
+    tile_stage<DT, SPARSE, TR, TC>(st, sa0, sb0, sm0, sa2, sb2, sm2, k);
+    tile_stage<DT, SPARSE, TR, TC>(st, sa1, sb1, sm1, sa0, sb0, sm0, k + 1);
+    tile_stage<DT, SPARSE, TR, TC>(st, sa2, sb2, sm2, sa1, sb1, sm1, k + 2);
+  }
+  if (k < st.nks) tile_stage<DT, SPARSE, TR, TC>(st, sa0, sb0, sm0, sa2, sb2, sm2, k);
+  if (k + 1 < st.nks) tile_stage<DT, SPARSE, TR, TC>(st, sa1, sb1, sm1, sa0, sb0, sm0, k + 1);
 
-  // prologue: stage 0.  The activations go from global memory straight into LDS (16 bytes per lane,
-  // lane l of a wave lands at the wave's LDS base + 16 l), so they never occupy registers.
-#pragma unroll
-  for (int p = 0; p < COPIES; p++)
-    global_to_lds_16(x_ptr[p] + x_lane, s_b + 256 * p + wave * 64);
+  const int c = (int)(st.lane & 15), g = (int)(st.lane >> 4);
 #pragma unroll
   for (int i = 0; i < TR; i++) {
-    if (SPARSE) {
-      a[0][i] = a_ptr[i][lane];
-      idx[0][i] = (int)m_ptr[i][lane * 4];
-    } else {
-      a[0][i] = a_ptr[i][lane];
-      a2[0][i] = a_ptr[i][lane + 64];
-    }
-  }
-  __syncthreads();
-
-  for (unsigned ks = 0; ks < nks32; ks += 2) {
-#pragma unroll
-    for (int par = 0; par < 2; par++) {
-      const unsigned k = ks + par;
-      // loads of the next stage (the last stage reloads itself: no branch, the copy is never used)
-      const unsigned kn = (k + 1 < nks32) ? k + 1 : k;
-#pragma unroll
-      for (int p = 0; p < COPIES; p++)
-        global_to_lds_16(x_ptr[p] + (kn * 128u + x_lane), s_b + (par ^ 1) * STAGE_UNITS + 256 * p + wave * 64);
-#pragma unroll
-      for (int i = 0; i < TR; i++) {
-        if (SPARSE) {
-          a[par ^ 1][i] = a_ptr[i][kn * 64u + lane];
-          idx[par ^ 1][i] = (int)m_ptr[i][(kn >> 2) * 256u + lane * 4u + (kn & 3u)];
-        } else {
-          a[par ^ 1][i] = a_ptr[i][kn * 128u + lane];
-          a2[par ^ 1][i] = a_ptr[i][kn * 128u + 64u + lane];
-        }
-      }
-      sched_fence();  // keep the next stage's loads ahead of this stage's multiplies
-      // multiply stage k out of LDS buffer `par`
-      const uint4* sb = s_b + par * STAGE_UNITS + (wc * TC) * 128 + lane;
-#pragma unroll
-      for (int j = 0; j < TC; j++) {
-        const uint4 b0 = sb[j * 128];
-        const uint4 b1 = sb[j * 128 + 64];
-#pragma unroll
-        for (int i = 0; i < TR; i++) {
-          if (SPARSE) {
-            acc[i][j] = smfmac16<DT, 0>(a[par][i], b0, b1, acc[i][j], idx[par][i]);
-          } else {
-            acc[i][j] = mfma16<DT>(a[par][i], b0, acc[i][j]);
-            acc[i][j] = mfma16<DT>(a2[par][i], b1, acc[i][j]);
-          }
-        }
-      }
-      __syncthreads();
-    }
-  }
-
-  const int c = lane & 15, g = lane >> 4;
-#pragma unroll
-  for (int i = 0; i < TR; i++) {
-    const long long rt = rt_base + i;
+    const long long rt = rt_macro + st.wr * TR + i;
     if (rt >= nrt) continue;
 #pragma unroll
     for (int j = 0; j < TC; j++) {
-      const long long tt = tt_base + wc * TC + j;
+      const long long tt = tt_base + st.wc * TC + j;
       if (tt >= ntt) continue;
-      store_y4<DT>(Y, M, N, tt * 16 + c, rt * 16 + g * 4, acc[i][j]);
+      store_y4<DT>(Y, M, N, tt * 16 + c, rt * 16 + g * 4, st.acc[i][j]);
     }
   }
+}
+
+// sparse: TR = 8 (macro tile of 16 row tiles); dense: TR = 4 (8 row tiles, operands twice as wide).
+template <int DT, int SPARSE, int TR, int TC>
+__global__ void __launch_bounds__(256) k_mm_tile(const uint4* __restrict__ A, const uint16_t* __restrict__ meta16,
+                                                  const uint4* __restrict__ Xf, uint16_t* __restrict__ Y, long long M,
+                                                  long long N, long long Mp, long long Np, long long Kp, long long n_tiles,
+                                                  long long ntb) {
+  __shared__ uint4 s_a0[1024];  // one stage of weights each (16 KiB)
+  __shared__ uint4 s_a1[1024];
+  __shared__ uint4 s_a2[1024];
+  __shared__ uint4 s_b0[2 * TC * 128];  // one stage of activations each: [2 TC token tiles][2 half steps][64 lanes]
+  __shared__ uint4 s_b1[2 * TC * 128];
+  __shared__ uint4 s_b2[2 * TC * 128];
+  __shared__ uint32_t s_m0[SPARSE ? 1024 : 1];  // one stage pair of index words each: [16 row tiles][64 lanes]
+  __shared__ uint32_t s_m1[SPARSE ? 1024 : 1];
+  __shared__ uint32_t s_m2[SPARSE ? 1024 : 1];
+  tile_pipeline<DT, SPARSE, TR, TC>(s_a0, s_a1, s_a2, s_b0, s_b1, s_b2, s_m0, s_m1, s_m2, A, meta16, Xf, Y, M, N, Mp, Np, Kp,
+                                    n_tiles, ntb);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -501,9 +601,8 @@ static const Variant kVariants[] = {
     {"ksplit_w8_r2", KIND_KSPLIT, 2, 0, 0, 8},
     {"ksplit_w8_r4", KIND_KSPLIT, 4, 0, 0, 8},
     {"ksplit_w16_r3", KIND_KSPLIT, 3, 0, 0, 16},
-    {"tile_256x256", KIND_TILE, 8, 8, 0, 0},
-    {"tile_256x128", KIND_TILE, 8, 4, 0, 0},
-    {"tile_128x128", KIND_TILE, 4, 4, 0, 0},
+    {"tile_t256", KIND_TILE, 8, 8, 0, 0},  // 256 rows (dense 128) x 256 tokens per workgroup
+    {"tile_t128", KIND_TILE, 8, 4, 0, 0},  // 256 rows (dense 128) x 128 tokens per workgroup
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -530,7 +629,7 @@ int esp_default_variant(long long M, long long N, long long K, int sparse) {
     return nrt <= 320 ? 4 : 5;  // ksplit_w16_r1 / ksplit_w16_r2
   }
   if (M <= 128) return 1;  // wave_r2_t2_splitk
-  return 12;               // tile_128x128
+  return 10;               // tile_t256
 }
 
 size_t esp_workspace_bytes(long long M, long long N, long long K) {
@@ -575,23 +674,16 @@ static void launch_ksplit(const Variant& v, hipStream_t st, const uint4* A, cons
 template <int DT, int SPARSE>
 static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const uint4* A, const uint16_t* meta16, const uint4* Xf,
                        uint16_t* Y, long long M, long long N, long long Mp, long long Np, long long Kp) {
+  constexpr int TR = SPARSE ? 8 : 4;  // the dense operand is twice as wide: half the row tiles per wave
   const long long nrt = Np / 16, ntt = Mp / 16;
-  const long long nrb = (nrt + 2 * v.rt - 1) / (2 * v.rt), ntb = (ntt + 2 * v.tt - 1) / (2 * v.tt);
+  const long long nrb = (nrt + 2 * TR - 1) / (2 * TR), ntb = (ntt + 2 * v.tt - 1) / (2 * v.tt);
   const long long n_tiles = nrb * ntb;
   const long long per = (n_tiles + 7) / 8;
   dim3 grid((unsigned)(per * 8));
-  const size_t smem = (size_t)2 * (2 * v.tt) * 128 * 16;
-#define LAUNCH(R, T)                                                                                                   \
-  do {                                                                                                                 \
-    if (smem > 48 * 1024)                                                                                              \
-      ESP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_mm_tile<DT, SPARSE, R, T>),                    \
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));                        \
-    hipLaunchKernelGGL((k_mm_tile<DT, SPARSE, R, T>), grid, dim3(256), smem, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp, n_tiles, ntb); \
-  } while (0)
-  if (v.rt == 8 && v.tt == 8) LAUNCH(8, 8);
-  else if (v.rt == 8 && v.tt == 4) LAUNCH(8, 4);
-  else LAUNCH(4, 4);
-#undef LAUNCH
+  if (v.tt == 8)
+    hipLaunchKernelGGL((k_mm_tile<DT, SPARSE, TR, 8>), grid, dim3(256), 0, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp, n_tiles, ntb);
+  else
+    hipLaunchKernelGGL((k_mm_tile<DT, SPARSE, TR, 4>), grid, dim3(256), 0, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp, n_tiles, ntb);
   ESP_HIP(ctx, hipGetLastError());
   return ESPARSE_OK;
 }
