@@ -247,11 +247,13 @@ def test_config4_all_layers_resident(esp, ctx):
     dense_bytes = 0
     closed_form = 0
     for L in range(LAYERS):
-        inst = 0
         for layer, count in kinds:
             N, K = c["layers"][layer]
             for j in range(count):
                 W = wl.weights(cfg, layer, instance=L * 8 + j, device="cuda")
+                # hand the generator's temporaries back to the driver first: a long-lived tensor carved out
+                # of a larger cached block would keep the whole block counted as in use
+                torch.cuda.empty_cache()
                 flags = esp.USE_ALL if L == 0 else (esp.USE_ENTROPY | esp.USE_NORM | esp.USE_GNS)
                 res = ctx.prune(None, W, esp.PruneOpts(block=64, alpha=alpha, flags=flags), score=scores[layer])
                 comp = ctx.compress(W, res.mask, res.perm, canonical=False)
@@ -259,9 +261,9 @@ def test_config4_all_layers_resident(esp, ctx):
                 dense_bytes += N * K * 2
                 closed_form += sum(orc.compressed_bytes(N, K, 2, 4))
                 del W, res
-                inst += 1
         if L % 10 == 9:
-            _log(f"{L + 1} layers compressed and resident", t0)
+            _log(f"{L + 1} layers compressed and resident; device memory taken {(free0 - torch.cuda.mem_get_info()[0]) / 1e9:.2f} GB, "
+                 f"tensors {torch.cuda.memory_allocated() / 1e9:.2f} GB", t0)
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
     free1, _ = torch.cuda.mem_get_info()
