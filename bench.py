@@ -1,10 +1,11 @@
 #!/usr/bin/env python3
 """Benchmark of the E-Sparse hot path on one MI355X.
 
-Workload: configuration 2 of the build's workload list, the linear layers of a LLaMA-7B-shaped
+Default workload: configuration 2 of the build's workload list, the linear layers of a LLaMA-7B-shaped
 decoder layer in fp16 (q/k/v/o 4096x4096, gate/up 11008x4096, down 4096x11008) at decode sizes
 M in {1, 8, 32}, pruned 2:4 with the entropy + norm metric, global naive shuffle and local block
-shuffle (blocks of 64), compressed, and multiplied with the sparse-MFMA kernels.
+shuffle (blocks of 64), compressed, and multiplied with the sparse-MFMA kernels.  --config 3/4/5
+runs the same measurement on the other full-size workloads (prefill sizes among them).
 
 One step = every linear layer of LAYERS distinct layer instances at every M (LAYERS x 7 x 3 sparse
 products).  The instances' compressed weights total > 512 MB, so the 256 MB last-level cache cannot
@@ -29,12 +30,23 @@ import numpy as np  # noqa: E402
 import torch  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
-LAYERS = 3
-M_LIST = (1, 8, 32)
-CFG = 2
-# (name, layer-shape key, calibration / activation stream)
-MATS = [("q", "qkvo", "attn_in"), ("k", "qkvo", "attn_in"), ("v", "qkvo", "attn_in"), ("o", "qkvo", "o_in"),
-        ("gate", "gate_up", "mlp_in"), ("up", "gate_up", "mlp_in"), ("down", "down", "down_in")]
+# HBM bytes per launch of the dominant product kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on
+# `bench.py --counter-probe` and scaled by the same counters' reading for a copy kernel of known size;
+# key (config, M, N, K).  The summaries are kept under profiles/.
+MEASURED_TRAFFIC = {}
+SPARSE_MFMA_PEAK_TFLOPS = 5000.0   # dense-equivalent flops of the 2:4 MFMA path: twice the dense 16-bit peak of 2.5 PFLOP/s
+DEFAULT_LAYERS = 3
+# (name, layer-shape key, calibration / activation stream, products per layer with this shape)
+MATS_LLAMA = [("q", "qkvo", "attn_in"), ("k", "qkvo", "attn_in"), ("v", "qkvo", "attn_in"), ("o", "qkvo", "o_in"),
+              ("gate", "gate_up", "mlp_in"), ("up", "gate_up", "mlp_in"), ("down", "down", "down_in")]
+MATS_OPT = [("q", "qkv_out", "attn_in"), ("k", "qkv_out", "attn_in"), ("v", "qkv_out", "attn_in"), ("out", "qkv_out", "o_in"),
+            ("fc1", "fc1", "mlp_in"), ("fc2", "fc2", "fc2_in")]
+WORKLOAD_TEXT = {
+    2: "config 2: LLaMA-7B-shaped decoder linears (q/k/v/o 4096x4096, gate/up 11008x4096, down 4096x11008), fp16, M in {1,8,32}",
+    3: "config 3: LLaMA-13B-shaped linears (q/k/v/o 5120x5120, gate/up 13824x5120, down 5120x13824), fp16, M in {512,2048}",
+    4: "config 4: LLaMA-65B-shaped linears (q/k/v/o 8192x8192, gate/up 22016x8192, down 8192x22016), bf16, M in {1,16,128,2048}",
+    5: "config 5: OPT-66B-shaped linears (q/k/v/out 9216x9216, fc1 36864x9216, fc2 9216x36864), fp16, M in {1,64,1024}",
+}
 
 
 def main():
@@ -44,6 +56,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--calib-tokens", type=int, default=128 * 2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--config", type=int, default=2, choices=(2, 3, 4, 5),
+                    help="workload configuration (default 2, the one the headline metric is quoted on)")
+    ap.add_argument("--layers", type=int, default=DEFAULT_LAYERS, help="distinct layer instances per step")
+    ap.add_argument("--counter-probe", action="store_true",
+                    help="launch a copy kernel of known size and each product kernel a few times, eagerly, and exit: "
+                         "the program to put under rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -58,8 +76,18 @@ def main():
     torch.cuda.set_device(0)
     ctx = esp.Context(0)
     lib = esp.load_library()
+    CFG = args.config
+    LAYERS = args.layers
+    M_LIST = tuple(wl.CONFIGS[CFG]["M"])
+    MATS = MATS_OPT if CFG == 5 else MATS_LLAMA
+    tdtype = wl.TORCH_DTYPE[wl.CONFIGS[CFG]["dtype"]]
+    act_law = {"lognormal": "lognormal", "student3": "student3"}[wl.CONFIGS[CFG]["act"]]
+    tol = 2e-3 if tdtype == torch.float16 else 1e-2
     shapes = wl.CONFIGS[CFG]["layers"]
     T = args.calib_tokens
+    if args.counter_probe:
+        T = min(T, 4096)
+        LAYERS = 1
     alpha = wl.default_alpha(T)
     opts = esp.PruneOpts(n_keep=2, m_group=4, block=wl.CONFIGS[CFG]["block"], bins=100, alpha=alpha)
 
@@ -76,8 +104,8 @@ def main():
             W = wl.weights(CFG, f"{name}", instance=li, device=dev, shape=(N, K))
             if stream not in calibs:
                 calibs = {stream: wl.normal_matrix(T, K, wl.stream_id("Xc", CFG, stream, li),
-                                                   col_scale=wl.channel_scales("lognormal", K, wl.stream_id("scale", CFG, stream)),
-                                                   dtype=torch.float16, device=dev)}
+                                                   col_scale=wl.channel_scales(act_law, K, wl.stream_id("scale", CFG, stream)),
+                                                   dtype=tdtype, device=dev)}
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             res = ctx.prune(calibs[stream], W, opts)
@@ -90,8 +118,8 @@ def main():
             t_compress += t2 - t1
             swaps_total += int(res.swaps.sum())
             packed = ctx.dense_pack(W)
-            if li == 0:
-                keep_dense_for_oracle[name] = (W.cpu(), res.perm.cpu().numpy().astype(np.int64), res.mask.cpu())
+            if (li == 0 or CFG == 2) and not args.no_cpu_baseline and not args.counter_probe:
+                keep_dense_for_oracle[(li, name)] = (W.cpu(), res.perm.cpu().numpy().astype(np.int64), res.mask.cpu())
             mats[name] = dict(N=N, K=K, comp=comp, perm=res.perm, packed=packed, W=W, stream=stream)
             del res
         del calibs
@@ -105,9 +133,9 @@ def main():
         for M in M_LIST:
             if (stream, M) not in acts:
                 acts[(stream, M)] = wl.normal_matrix(M, K, wl.stream_id("X", CFG, stream),
-                                                     col_scale=wl.channel_scales("lognormal", K, wl.stream_id("scale", CFG, stream)),
-                                                     dtype=torch.float16, device=dev)
-    outs = {(name, M): torch.empty((M, shapes[skey][0]), dtype=torch.float16, device=dev)
+                                                     col_scale=wl.channel_scales(act_law, K, wl.stream_id("scale", CFG, stream)),
+                                                     dtype=tdtype, device=dev)
+    outs = {(name, M): torch.empty((M, shapes[skey][0]), dtype=tdtype, device=dev)
             for name, skey, _ in MATS for M in M_LIST}
     ws_bytes = max(esp.spmm_workspace(M, shapes[skey][0], shapes[skey][1]) for _, skey, _ in MATS for M in M_LIST)
     ws = ctx.workspace(ws_bytes)
@@ -157,6 +185,35 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
+    # ------------------------------------------------------------------ counter probe (for rocprofv3 --pmc runs)
+    if args.counter_probe:
+        nbytes = 256 << 20
+        src = torch.empty(nbytes // 2, dtype=torch.float16, device=dev).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        print(f"counter probe: 3 x copy kernel, {nbytes} bytes read + {nbytes} bytes written each", flush=True)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        done = set()
+        for name, skey, stream in MATS:
+            if skey in done:
+                continue
+            done.add(skey)
+            N, K = shapes[skey]
+            for M in M_LIST:
+                m = layers[0][name]
+                print(f"counter probe: M={M} N={N} K={K}: 1 x stage, 3 x sparse product, 3 x dense product "
+                      f"(algorithmic bytes sparse {int(1.125 * N * K + 2 * M * K + 2 * M * N)}, dense {int(2 * N * K + 2 * M * K + 2 * M * N)})",
+                      flush=True)
+                ctx.stage_activations(acts[(stream, M)], m["perm"], N, ws)
+                for _ in range(3):
+                    ctx.spmm_staged(M, m["comp"], ws, outs[(name, M)])
+                for _ in range(3):
+                    ctx.dense_gemm_staged(M, m["packed"], N, K, ws, outs[(name, M)])
+                torch.cuda.synchronize()
+        return
+
     flops_step = sum(2.0 * M * shapes[skey][0] * shapes[skey][1] for _, skey, _ in MATS for M in M_LIST) * LAYERS
     g_sparse = capture(step_sparse)
     t_sparse = timed(g_sparse, args.steps, args.warmup)
@@ -166,7 +223,7 @@ def main():
     t_ref = timed(g_ref, args.steps, args.warmup)
 
     # ------------------------------------------------------------------ per-kernel durations (HIP events on the launch stream)
-    def kernel_time(launch, reps=48):
+    def kernel_time(launch, reps):
         """Average duration of one launch: `reps` launches (rotating over the layer instances) captured in
         a HIP graph, replayed between two HIP events on the launch stream."""
         launch(0)
@@ -190,8 +247,20 @@ def main():
             torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / (3 * reps)
 
+    def kernel_name(M, sparse=True):
+        if M <= 32:
+            return "k_mm_ksplit" + ("" if sparse else " (dense)")
+        if M <= 128:
+            return "k_mm_wave_tile" + ("" if sparse else " (dense)")
+        return "k_mm_tile" + ("" if sparse else " (dense)")
+
     per_shape = []
-    for name, skey, stream in (MATS[0], MATS[4], MATS[6]):
+    seen = set()
+    for name, skey, stream in MATS:
+        if skey in seen:
+            continue
+        seen.add(skey)
+        count = sum(1 for _, k2, _ in MATS if k2 == skey)
         N, K = shapes[skey]
         for M in M_LIST:
             X = acts[(stream, M)]
@@ -207,23 +276,45 @@ def main():
             def stage(i, X=X, name=name, N=N):
                 ctx.stage_activations(X, layers[i % LAYERS][name]["perm"], N, ws)
 
-            ts, td, tg = kernel_time(sp), kernel_time(dn), kernel_time(stage)
-            count = {"qkvo": 4, "gate_up": 2, "down": 1}[skey]
+            def lt(i, X=X, name=name, Y=Y):
+                torch.matmul(X, layers[i % LAYERS][name]["W"].t(), out=Y)
+
+            reps = 48 if M <= 128 else 12
+            ts, td, tg, tl = kernel_time(sp, reps), kernel_time(dn, reps), kernel_time(stage, reps), kernel_time(lt, reps)
             bytes_alg = 1.125 * N * K + 2.0 * M * K + 2.0 * M * N
-            per_shape.append(dict(layer=skey, N=N, K=K, M=M, count_per_layer=count,
-                                  spmm_kernel_us=round(ts * 1e6, 2), dense_kernel_us=round(td * 1e6, 2),
-                                  stage_kernel_us=round(tg * 1e6, 2),
-                                  eff_tflops=round(2.0 * M * N * K / (ts + tg) / 1e12, 2),
-                                  kernel_gbs=round(bytes_alg / ts / 1e9, 1),
-                                  frac_hbm_peak=round(bytes_alg / ts / 1e9 / HBM_PEAK_GBS, 3),
-                                  speedup_vs_dense_kernel=round(td / ts, 3), alg_bytes=int(bytes_alg)))
-    # dominant kernel = the multiply kernel of the shape class with the largest total time per step
+            flops = 2.0 * M * N * K
+            mfma_bound = M >= 512
+            row = dict(layer=skey, N=N, K=K, M=M, count_per_layer=count, bound="mfma" if mfma_bound else "hbm",
+                       kernel=kernel_name(M),
+                       spmm_kernel_us=round(ts * 1e6, 2), dense_kernel_us=round(td * 1e6, 2),
+                       stage_kernel_us=round(tg * 1e6, 2), hipblaslt_dense_us=round(tl * 1e6, 2),
+                       eff_tflops=round(flops / (ts + tg) / 1e12, 2),
+                       eff_tflops_kernel=round(flops / ts / 1e12, 2),
+                       frac_sparse_mfma_peak=round(flops / ts / 1e12 / SPARSE_MFMA_PEAK_TFLOPS, 4),
+                       kernel_gbs=round(bytes_alg / ts / 1e9, 1),
+                       frac_hbm_peak=round(bytes_alg / ts / 1e9 / HBM_PEAK_GBS, 3),
+                       speedup_vs_dense_kernel=round(td / ts, 3),
+                       speedup_vs_dense_incl_stage=round((td + tg) / (ts + tg), 3),
+                       alg_bytes=int(bytes_alg), flops=flops)
+            per_shape.append(row)
+    # dominant kernel = the multiply kernel of the (shape, M) class with the largest total time per step
     dom = max(per_shape, key=lambda r: r["spmm_kernel_us"] * r["count_per_layer"])
-    roofline = dict(bound="hbm", kernel="k_mm_ksplit (2:4 sparse product, staged activations)",
-                    shape=f"M={dom['M']} N={dom['N']} K={dom['K']}",
-                    achieved=round(dom["alg_bytes"] / (dom["spmm_kernel_us"] * 1e-6) / 1e9, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(dom["alg_bytes"] / (dom["spmm_kernel_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
-                    alg_bytes_per_launch=dom["alg_bytes"], avg_launch_us=dom["spmm_kernel_us"], traffic=None)
+    if dom["bound"] == "hbm":
+        ach = dom["alg_bytes"] / (dom["spmm_kernel_us"] * 1e-6) / 1e9
+        roofline = dict(bound="hbm", kernel=dom["kernel"] + " (2:4 sparse product, staged activations)",
+                        shape=f"M={dom['M']} N={dom['N']} K={dom['K']}", achieved=round(ach, 1), peak=HBM_PEAK_GBS,
+                        unit="GB/s", frac=round(ach / HBM_PEAK_GBS, 4), alg_bytes_per_launch=dom["alg_bytes"],
+                        avg_launch_us=dom["spmm_kernel_us"], traffic=MEASURED_TRAFFIC.get((CFG, dom["M"], dom["N"], dom["K"])))
+    else:
+        ach = dom["flops"] / (dom["spmm_kernel_us"] * 1e-6) / 1e12
+        roofline = dict(bound="mfma", kernel=dom["kernel"] + " (2:4 sparse product, staged activations)",
+                        shape=f"M={dom['M']} N={dom['N']} K={dom['K']}", achieved=round(ach, 1),
+                        peak=SPARSE_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=round(ach / SPARSE_MFMA_PEAK_TFLOPS, 4),
+                        flops_per_launch=dom["flops"], avg_launch_us=dom["spmm_kernel_us"],
+                        note="dense-equivalent flops 2 M N K against twice the dense 16-bit MFMA peak",
+                        traffic=MEASURED_TRAFFIC.get((CFG, dom["M"], dom["N"], dom["K"])))
+    for r in per_shape:
+        del r["flops"]
 
     # ------------------------------------------------------------------ CPU oracle on a bounded sample + parity of that sample
     cpu_baseline = None
@@ -235,27 +326,50 @@ def main():
             nthreads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             nthreads = os.cpu_count()
-        M = 32
+        budget_s = 15.0
+        feat_cap = 1024          # output features per product the oracle computes when the product is large
         worst = 0.0
         fl = 0.0
         t_cpu = 0.0
-        for name, skey, stream in MATS:
-            Wc, theta, mask = keep_dense_for_oracle[name]
-            X = acts[(stream, M)].cpu().numpy()
-            t0 = time.perf_counter()
-            Yref = orc.spmm_ref(X, Wc.numpy(), theta, mask.numpy())
-            t_cpu += time.perf_counter() - t0
-            fl += 2.0 * M * Wc.shape[0] * Wc.shape[1]
-            Y = ctx.spmm(acts[(stream, M)], layers[0][name]["comp"], layers[0][name]["perm"])
-            torch.cuda.synchronize()
-            worst = max(worst, float(orc.rowwise_rel_error(Y.float().cpu().numpy(), Yref).max()))
+        done = 0
+        sampled = False
+        rng = np.random.default_rng(7)
+        for (li, name), (Wc, theta, mask) in keep_dense_for_oracle.items():
+            stream = [m[2] for m in MATS if m[0] == name][0]
+            for M in reversed(M_LIST):
+                if t_cpu > budget_s:
+                    break
+                N, K = Wc.shape
+                Wn = Wc.float().numpy() if Wc.dtype == torch.bfloat16 else Wc.numpy()
+                mk = mask.numpy()
+                feat = None
+                if float(M) * N * K > 2e10:
+                    feat = np.sort(rng.choice(N, feat_cap, replace=False))
+                    Wn, mk = Wn[feat], mk[feat]
+                    sampled = True
+                Xg = acts[(stream, M)]
+                X = Xg.float().cpu().numpy() if Xg.dtype == torch.bfloat16 else Xg.cpu().numpy()
+                t0 = time.perf_counter()
+                Yref = orc.spmm_ref(X, Wn, theta, mk)
+                t_cpu += time.perf_counter() - t0
+                fl += 2.0 * M * Wn.shape[0] * K
+                Y = ctx.spmm(Xg, layers[li][name]["comp"], layers[li][name]["perm"])
+                torch.cuda.synchronize()
+                Yc = Y.float().cpu().numpy()
+                if feat is not None:
+                    Yc = Yc[:, feat]
+                worst = max(worst, float(orc.rowwise_rel_error(Yc, Yref).max()))
+                done += 1
         cpu_baseline = dict(value=round(fl / t_cpu / 1e12, 5), unit="TFLOP/s", cores=int(nthreads), kind="oracle",
-                            sample="oracle spmm_ref (float64) on the 7 linear layers of layer instance 0 at M=32, "
-                                   f"{t_cpu:.1f} s of CPU time")
-        parity = dict(max_row_rel_err=worst, tol=2e-3, ok=bool(worst <= 2e-3))
+                            sample=f"oracle spmm_ref (float64) on {done} products of this workload (largest M first"
+                                   + (f", {feat_cap} sampled output features of the large ones" if sampled else "")
+                                   + f"), {t_cpu:.1f} s of CPU time")
+        parity = dict(max_row_rel_err=worst, tol=tol, ok=bool(worst <= tol), products_checked=done)
 
+    n_prod = LAYERS * len(MATS) * len(M_LIST)
     out = {
-        "metric": "effective TFLOP/s (2 M N K / t) of the 2:4 SpMM at LLaMA-7B decoder-layer shapes, decode M in {1,8,32}",
+        "metric": "effective TFLOP/s (2 M N K / t) of the 2:4 SpMM at the workload's linear-layer shapes; "
+                  "speedup vs the in-repo dense MFMA GEMM beside it",
         "value": round(flops_step / t_sparse / 1e12, 3),
         "unit": "TFLOP/s",
         "n_gpus": 1,
@@ -265,11 +379,10 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f16",
+        "dtype": "f16" if tdtype == torch.float16 else "bf16",
         "data": "synthetic",
-        "config": {"workload": "config 2: LLaMA-7B-shaped decoder linears (q/k/v/o 4096x4096, gate/up 11008x4096, down "
-                               "4096x11008), fp16, M in {1,8,32}, 2:4 along K, entropy+norm metric, GNS + LBS(64); "
-                               f"{LAYERS} layer instances per step ({LAYERS * 7 * len(M_LIST)} products), one HIP graph per step",
+        "config": {"workload": WORKLOAD_TEXT[CFG] + ", 2:4 along K, entropy+norm metric, GNS + LBS(64); "
+                               f"{LAYERS} layer instances per step ({n_prod} products), one HIP graph per step",
                    "calib_tokens": T, "alpha": alpha},
         "speedup_vs_inrepo_dense": round(t_dense / t_sparse, 3),
         "dense_inrepo_ms_per_step": round(t_dense * 1e3, 4),
@@ -277,14 +390,15 @@ def main():
         "hbm_gbs_whole_step": round(sum((1.125 * shapes[skey][0] * shapes[skey][1] + 2.0 * M * shapes[skey][1] +
                                          2.0 * M * shapes[skey][0] + 4.0 * shapes[skey][1])
                                         for _, skey, _ in MATS for M in M_LIST) * LAYERS / t_sparse / 1e9, 1),
-        "offline": {"prune_ms_per_matrix": round(t_prune / (LAYERS * 7) * 1e3, 2),
-                    "compress_ms_per_matrix": round(t_compress / (LAYERS * 7) * 1e3, 3),
-                    "lbs_swaps_per_matrix": swaps_total // (LAYERS * 7)},
+        "offline": {"prune_ms_per_matrix": round(t_prune / (LAYERS * len(MATS)) * 1e3, 2),
+                    "compress_ms_per_matrix": round(t_compress / (LAYERS * len(MATS)) * 1e3, 3),
+                    "lbs_swaps_per_matrix": swaps_total // (LAYERS * len(MATS))},
         "per_shape": per_shape,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "parity": parity,
-        "paper_context": "paper reports 1.24-1.53x over dense fp16 on one A100 40GB (Table 5); not comparable hardware",
+        "paper_context": "paper reports 1.24-1.53x over dense fp16 on one A100 40GB (Table 5) and up to 43.52 % memory "
+                         "saving (Table 6); other hardware, context only",
     }
     print(json.dumps(out))
 

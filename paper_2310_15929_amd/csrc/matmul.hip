@@ -382,10 +382,12 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(const uint4* __restrict__
 // multiplies.  Macro tiles are numbered so that the workgroups of one XCD (blockIdx % 8) cover
 // neighbouring tiles and share weight rows in that XCD's L2.
 // ------------------------------------------------------------------------------------------------
-template <int TR, int TC>
+template <int TR, int TC, int NWC>
 struct TileState {
-  static constexpr int BCOPIES = (2 * TC * 128) / 256;  // 16-byte units of activations per lane and stage
-  static constexpr int ACOPIES = 4;                     // 1024 units of weights per stage
+  static constexpr int NW = 2 * NWC;                        // waves: 2 along the rows x NWC along the tokens
+  static constexpr int NT = 64 * NW;                        // threads
+  static constexpr int BCOPIES = (NWC * TC * 128) / NT;     // 16-byte units of activations per lane and stage
+  static constexpr int ACOPIES = 1024 / NT;                 // 1024 units of weights per stage
   floatx4_t acc[TR][TC];
   const uint4* a_src[ACOPIES];  // wave-uniform global bases of this wave's DMA copies
   const uint4* x_src[BCOPIES];
@@ -393,25 +395,27 @@ struct TileState {
   unsigned lane, x_lane, wave, wr, wc, nks;
 };
 
-template <int SPARSE, int TR, int TC>
-__device__ __forceinline__ void tile_prefetch(TileState<TR, TC>& st, uint4* sa, uint4* sb, uint32_t* sm, unsigned kn) {
+template <int SPARSE, int TR, int TC, int NWC>
+__device__ __forceinline__ void tile_prefetch(TileState<TR, TC, NWC>& st, uint4* sa, uint4* sb, uint32_t* sm, unsigned kn) {
+  using State = TileState<TR, TC, NWC>;
   // every vector-memory operation of the pipeline is a DMA into LDS: they keep their program order,
   // which the stage-end wait counts on
 #pragma unroll
-  for (int p = 0; p < TileState<TR, TC>::BCOPIES; p++)
-    global_to_lds_16(st.x_src[p] + (kn * 128u + st.x_lane), sb + 256 * p + st.wave * 64);
+  for (int p = 0; p < State::BCOPIES; p++)
+    global_to_lds_16(st.x_src[p] + (kn * 128u + st.x_lane), sb + State::NT * p + st.wave * 64);
 #pragma unroll
-  for (int p = 0; p < TileState<TR, TC>::ACOPIES; p++) {
-    // sparse: copy p of wave w is row tile 4 p + w (64 units); dense: row tile 2 p + w / 2, half w % 2
+  for (int p = 0; p < State::ACOPIES; p++) {
+    // chunk q = NW p + w of 64 units.  sparse: row tile q; dense: row tile q / 2, half q % 2 (NW is even: half w % 2)
     const unsigned off = SPARSE ? kn * 64u + st.lane : kn * 128u + (st.wave & 1u) * 64u + st.lane;
-    global_to_lds_16(st.a_src[p] + off, sa + 256 * p + st.wave * 64);
+    global_to_lds_16(st.a_src[p] + off, sa + State::NT * p + st.wave * 64);
     // the lane's index word holding stage kn: 8 bytes per lane and group of 4 stages, word (kn % 4) / 2
-    if (SPARSE) global_to_lds_4(st.m_src[p] + ((kn >> 2) * 128u + st.lane * 2u + ((kn >> 1) & 1u)), sm + 256 * p + st.wave * 64);
+    if (SPARSE)
+      global_to_lds_4(st.m_src[p] + ((kn >> 2) * 128u + st.lane * 2u + ((kn >> 1) & 1u)), sm + State::NT * p + st.wave * 64);
   }
 }
 
-template <int DT, int SPARSE, int TR, int TC>
-__device__ __forceinline__ void tile_multiply(TileState<TR, TC>& st, const uint4* sa, const uint4* sb, const uint32_t* sm,
+template <int DT, int SPARSE, int TR, int TC, int NWC>
+__device__ __forceinline__ void tile_multiply(TileState<TR, TC, NWC>& st, const uint4* sa, const uint4* sb, const uint32_t* sm,
                                               unsigned k) {
   uint4 a[SPARSE ? TR : 2 * TR];
   int idx[TR];
@@ -452,12 +456,17 @@ __device__ __forceinline__ void tile_multiply(TileState<TR, TC>& st, const uint4
     b1 = n1;
   }
   // the order wanted for this region: all A operands and the first B operand, then for every token
-  // tile "read the next B operand, multiply with the current one"
+  // tile "read the next B operand, multiply with the current one, issue a share of the prefetch DMA":
+  // a wave that issued all its DMA in one burst would sit at the (bandwidth-limited) vector-memory
+  // issue while the matrix pipe runs dry
+  constexpr int DMA = TileState<TR, TC, NWC>::BCOPIES + (SPARSE ? 2 : 1) * TileState<TR, TC, NWC>::ACOPIES;
+  constexpr int DPJ = (DMA + TC - 1) / TC;
   sched_group<0x100, (SPARSE ? 2 * TR : 2 * TR) + 2>();
 #pragma unroll
   for (int j = 0; j < TC; j++) {
     if (j + 1 < TC) sched_group<0x100, 2>();
     sched_group<0x008, SPARSE ? TR : 2 * TR>();
+    sched_group<0x010, DPJ>();
   }
 }
 
@@ -475,35 +484,34 @@ __device__ __forceinline__ void tile_arrive() {
 
 // one pipeline stage: prefetch stage k+2 into the PRE buffers, multiply stage k out of the CUR buffers,
 // make sure stage k+1 has landed for everybody
-template <int DT, int SPARSE, int TR, int TC>
-__device__ __forceinline__ void tile_stage(TileState<TR, TC>& st, const uint4* sa_cur, const uint4* sb_cur,
+template <int DT, int SPARSE, int TR, int TC, int NWC>
+__device__ __forceinline__ void tile_stage(TileState<TR, TC, NWC>& st, const uint4* sa_cur, const uint4* sb_cur,
                                            const uint32_t* sm_cur, uint4* sa_pre, uint4* sb_pre, uint32_t* sm_pre,
                                            unsigned k) {
-  constexpr int DMA = TileState<TR, TC>::BCOPIES + (SPARSE ? 2 : 1) * TileState<TR, TC>::ACOPIES;
+  constexpr int DMA = TileState<TR, TC, NWC>::BCOPIES + (SPARSE ? 2 : 1) * TileState<TR, TC, NWC>::ACOPIES;
   const unsigned kn = (k + 2 < st.nks) ? k + 2 : st.nks - 1;  // past the end: reload the last stage (never used)
-  tile_prefetch<SPARSE, TR, TC>(st, sa_pre, sb_pre, sm_pre, kn);
-  sched_fence();  // keep the prefetch ahead of this stage's multiplies
-  tile_multiply<DT, SPARSE, TR, TC>(st, sa_cur, sb_cur, sm_cur, k);
+  tile_prefetch<SPARSE, TR, TC, NWC>(st, sa_pre, sb_pre, sm_pre, kn);
+  tile_multiply<DT, SPARSE, TR, TC, NWC>(st, sa_cur, sb_cur, sm_cur, k);  // same scheduling region: the DMA is spread over it
   sched_fence();
   tile_arrive<DMA>();
 }
 
-template <int DT, int SPARSE, int TR, int TC>
+template <int DT, int SPARSE, int TR, int TC, int NWC>
 __device__ __attribute__((always_inline)) void tile_pipeline(
     uint4* __restrict__ sa0, uint4* __restrict__ sa1, uint4* __restrict__ sa2, uint4* __restrict__ sb0, uint4* __restrict__ sb1,
     uint4* __restrict__ sb2, uint32_t* __restrict__ sm0, uint32_t* __restrict__ sm1, uint32_t* __restrict__ sm2,
     const uint4* __restrict__ A, const uint16_t* __restrict__ meta16, const uint4* __restrict__ Xf,
     uint16_t* __restrict__ Y, long long M, long long N, long long Mp, long long Np, long long Kp, long long n_tiles,
     long long ntb) {
-  constexpr int NTT = 2 * TC;                 // token tiles of 16 in the macro tile
+  constexpr int NTT = NWC * TC;               // token tiles of 16 in the macro tile
   constexpr int RTM = 2 * TR;                 // row tiles of 16 in the macro tile (sparse 16, dense 8)
-  using State = TileState<TR, TC>;
+  using State = TileState<TR, TC, NWC>;
   const int tid = threadIdx.x;
   State st;
   st.lane = (unsigned)(tid & 63);
   st.wave = (unsigned)wave_uniform(tid >> 6);  // wave-uniform: keeps the operand bases in SGPRs
-  st.wr = st.wave >> 1;
-  st.wc = st.wave & 1u;
+  st.wr = st.wave / NWC;
+  st.wc = st.wave % NWC;
   const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
   st.nks = (unsigned)nks;
   // XCD-aware numbering: XCD x (= blockIdx % 8) works through tiles [x * per, (x + 1) * per)
@@ -515,36 +523,36 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
   const long long tt_base = tb * NTT;   // first token tile of the macro tile
 #pragma unroll
   for (int p = 0; p < State::ACOPIES; p++) {
-    const long long rtl = SPARSE ? 4 * p + st.wave : 2 * p + (st.wave >> 1);  // row tile this wave copies
+    const long long rtl = SPARSE ? State::NW * p + st.wave : (State::NW / 2) * p + (st.wave >> 1);  // row tile this wave copies
     const long long rt = (rt_macro + rtl < nrt) ? rt_macro + rtl : nrt - 1;
     st.a_src[p] = A + (SPARSE ? rt * nks : rt * (2 * nks)) * 64;
     st.m_src[p] = reinterpret_cast<const uint32_t*>(meta16) + rt * (nks / 4) * 128;
   }
 #pragma unroll
   for (int p = 0; p < State::BCOPIES; p++) {
-    const long long ttl = 2 * p + (st.wave >> 1);  // token tile (within the macro tile) of this wave's p-th copy
+    const long long ttl = (State::NW / 2) * p + (st.wave >> 1);  // token tile (within the macro tile) of this wave's p-th copy
     const long long tt = (tt_base + ttl < ntt) ? tt_base + ttl : ntt - 1;
     st.x_src[p] = Xf + tt * (2 * nks) * 64;
   }
-  st.x_lane = (unsigned)(tid & 127);
+  st.x_lane = (unsigned)(tid & 127);  // chunk q = NW p + w is half q % 2 = w % 2 of its token tile
 #pragma unroll
   for (int i = 0; i < TR; i++)
 #pragma unroll
     for (int j = 0; j < TC; j++) st.acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
   // prologue: stages 0 and 1 in flight, then wait for stage 0
-  tile_prefetch<SPARSE, TR, TC>(st, sa0, sb0, sm0, 0u);
-  tile_prefetch<SPARSE, TR, TC>(st, sa1, sb1, sm1, st.nks > 1 ? 1u : 0u);
+  tile_prefetch<SPARSE, TR, TC, NWC>(st, sa0, sb0, sm0, 0u);
+  tile_prefetch<SPARSE, TR, TC, NWC>(st, sa1, sb1, sm1, st.nks > 1 ? 1u : 0u);
   sched_fence();
   tile_arrive<State::BCOPIES + (SPARSE ? 2 : 1) * State::ACOPIES>();
   unsigned k = 0;
   for (; k + 3 <= st.nks; k += 3) {
-    tile_stage<DT, SPARSE, TR, TC>(st, sa0, sb0, sm0, sa2, sb2, sm2, k);
-    tile_stage<DT, SPARSE, TR, TC>(st, sa1, sb1, sm1, sa0, sb0, sm0, k + 1);
-    tile_stage<DT, SPARSE, TR, TC>(st, sa2, sb2, sm2, sa1, sb1, sm1, k + 2);
+    tile_stage<DT, SPARSE, TR, TC, NWC>(st, sa0, sb0, sm0, sa2, sb2, sm2, k);
+    tile_stage<DT, SPARSE, TR, TC, NWC>(st, sa1, sb1, sm1, sa0, sb0, sm0, k + 1);
+    tile_stage<DT, SPARSE, TR, TC, NWC>(st, sa2, sb2, sm2, sa1, sb1, sm1, k + 2);
   }
-  if (k < st.nks) tile_stage<DT, SPARSE, TR, TC>(st, sa0, sb0, sm0, sa2, sb2, sm2, k);
-  if (k + 1 < st.nks) tile_stage<DT, SPARSE, TR, TC>(st, sa1, sb1, sm1, sa0, sb0, sm0, k + 1);
+  if (k < st.nks) tile_stage<DT, SPARSE, TR, TC, NWC>(st, sa0, sb0, sm0, sa2, sb2, sm2, k);
+  if (k + 1 < st.nks) tile_stage<DT, SPARSE, TR, TC, NWC>(st, sa1, sb1, sm1, sa0, sb0, sm0, k + 1);
 
   const int c = (int)(st.lane & 15), g = (int)(st.lane >> 4);
 #pragma unroll
@@ -561,21 +569,21 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
 }
 
 // sparse: TR = 8 (macro tile of 16 row tiles); dense: TR = 4 (8 row tiles, operands twice as wide).
-template <int DT, int SPARSE, int TR, int TC>
-__global__ void __launch_bounds__(256) k_mm_tile(const uint4* __restrict__ A, const uint16_t* __restrict__ meta16,
+template <int DT, int SPARSE, int TR, int TC, int NWC>
+__global__ void __launch_bounds__(128 * NWC) k_mm_tile(const uint4* __restrict__ A, const uint16_t* __restrict__ meta16,
                                                   const uint4* __restrict__ Xf, uint16_t* __restrict__ Y, long long M,
                                                   long long N, long long Mp, long long Np, long long Kp, long long n_tiles,
                                                   long long ntb) {
   __shared__ uint4 s_a0[1024];  // one stage of weights each (16 KiB)
   __shared__ uint4 s_a1[1024];
   __shared__ uint4 s_a2[1024];
-  __shared__ uint4 s_b0[2 * TC * 128];  // one stage of activations each: [2 TC token tiles][2 half steps][64 lanes]
-  __shared__ uint4 s_b1[2 * TC * 128];
-  __shared__ uint4 s_b2[2 * TC * 128];
+  __shared__ uint4 s_b0[NWC * TC * 128];  // one stage of activations each: [NWC TC token tiles][2 half steps][64 lanes]
+  __shared__ uint4 s_b1[NWC * TC * 128];
+  __shared__ uint4 s_b2[NWC * TC * 128];
   __shared__ uint32_t s_m0[SPARSE ? 1024 : 1];  // one stage pair of index words each: [16 row tiles][64 lanes]
   __shared__ uint32_t s_m1[SPARSE ? 1024 : 1];
   __shared__ uint32_t s_m2[SPARSE ? 1024 : 1];
-  tile_pipeline<DT, SPARSE, TR, TC>(s_a0, s_a1, s_a2, s_b0, s_b1, s_b2, s_m0, s_m1, s_m2, A, meta16, Xf, Y, M, N, Mp, Np, Kp,
+  tile_pipeline<DT, SPARSE, TR, TC, NWC>(s_a0, s_a1, s_a2, s_b0, s_b1, s_b2, s_m0, s_m1, s_m2, A, meta16, Xf, Y, M, N, Mp, Np, Kp,
                                     n_tiles, ntb);
 }
 
@@ -588,7 +596,7 @@ struct Variant {
   int kind;
   int rt, tt;      // row tiles / token tiles per wave (ksplit: row tiles per workgroup, tt unused: MT follows M)
   int split_mode;  // wave kind: 0 = never split K, 1 = split K over workgroups to fill the chip
-  int nw;          // ksplit kind: waves per workgroup
+  int nw;          // ksplit kind: waves per workgroup; tile kind: waves along the tokens (the workgroup has 2 x nw waves)
 };
 static const Variant kVariants[] = {
     {"wave_r2_t1_splitk", KIND_WAVE, 2, 1, 1, 0},
@@ -601,8 +609,10 @@ static const Variant kVariants[] = {
     {"ksplit_w8_r2", KIND_KSPLIT, 2, 0, 0, 8},
     {"ksplit_w8_r4", KIND_KSPLIT, 4, 0, 0, 8},
     {"ksplit_w16_r3", KIND_KSPLIT, 3, 0, 0, 16},
-    {"tile_t256", KIND_TILE, 8, 8, 0, 0},  // 256 rows (dense 128) x 256 tokens per workgroup
-    {"tile_t128", KIND_TILE, 8, 4, 0, 0},  // 256 rows (dense 128) x 128 tokens per workgroup
+    {"tile_t256", KIND_TILE, 8, 8, 0, 2},     // 256 rows (dense 128) x 256 tokens per workgroup, 4 waves
+    {"tile_t128", KIND_TILE, 8, 4, 0, 2},     // 256 rows (dense 128) x 128 tokens per workgroup, 4 waves
+    {"tile_w8_t256", KIND_TILE, 8, 4, 0, 4},  // 256 rows (dense 128) x 256 tokens per workgroup, 8 waves (two per SIMD)
+    {"tile_w8_t128", KIND_TILE, 8, 2, 0, 4},  // 256 rows (dense 128) x 128 tokens per workgroup, 8 waves
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -676,14 +686,20 @@ static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const
                        uint16_t* Y, long long M, long long N, long long Mp, long long Np, long long Kp) {
   constexpr int TR = SPARSE ? 8 : 4;  // the dense operand is twice as wide: half the row tiles per wave
   const long long nrt = Np / 16, ntt = Mp / 16;
-  const long long nrb = (nrt + 2 * TR - 1) / (2 * TR), ntb = (ntt + 2 * v.tt - 1) / (2 * v.tt);
+  const long long cols = (long long)v.nw * v.tt;  // token tiles per macro tile
+  const long long nrb = (nrt + 2 * TR - 1) / (2 * TR), ntb = (ntt + cols - 1) / cols;
   const long long n_tiles = nrb * ntb;
   const long long per = (n_tiles + 7) / 8;
   dim3 grid((unsigned)(per * 8));
-  if (v.tt == 8)
-    hipLaunchKernelGGL((k_mm_tile<DT, SPARSE, TR, 8>), grid, dim3(256), 0, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp, n_tiles, ntb);
-  else
-    hipLaunchKernelGGL((k_mm_tile<DT, SPARSE, TR, 4>), grid, dim3(256), 0, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp, n_tiles, ntb);
+#define ESP_TILE(TCv, NWCv)                                                                                                  \
+  hipLaunchKernelGGL((k_mm_tile<DT, SPARSE, TR, TCv, NWCv>), grid, dim3(128 * NWCv), 0, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp, \
+                     n_tiles, ntb)
+  if (v.nw == 2 && v.tt == 8) ESP_TILE(8, 2);
+  else if (v.nw == 2 && v.tt == 4) ESP_TILE(4, 2);
+  else if (v.nw == 4 && v.tt == 4) ESP_TILE(4, 4);
+  else if (v.nw == 4 && v.tt == 2) ESP_TILE(2, 4);
+  else return esp_fail(ctx, ESPARSE_EINVAL, "unknown tile variant");
+#undef ESP_TILE
   ESP_HIP(ctx, hipGetLastError());
   return ESPARSE_OK;
 }
