@@ -141,6 +141,66 @@ __global__ void __launch_bounds__(256) k_gather_x(const uint16_t* __restrict__ X
   Xf[u] = o;
 }
 
+// The same staging for many tokens: a workgroup copies TOK whole rows of X into LDS with coalesced
+// 16-byte reads and gathers through theta out of LDS (the element-wise gather above reads 2 bytes per
+// lane from 64 different cache lines per instruction).  Rows are padded by 8 elements so that the TOK
+// tokens of one channel sit in different banks.  Lane l of a wave works on token l % TOK and 8-channel
+// unit l / TOK, so consecutive lanes write consecutive 16-byte units of X'.  Needs K % 8 == 0.
+template <int TOK>
+__global__ void __launch_bounds__(512) k_gather_rows(const uint16_t* __restrict__ X, const int32_t* __restrict__ perm, long long M,
+                                                      long long K, long long Kp, uint4* __restrict__ Xf) {
+  extern __shared__ uint4 s_rows4[];
+  uint16_t* s_rows = reinterpret_cast<uint16_t*>(s_rows4);
+  const int tid = threadIdx.x;
+  const long long t0 = (long long)blockIdx.x * TOK;
+  const int stride = (int)K + 8;
+  const long long nrows = (M - t0) < TOK ? (M - t0 > 0 ? M - t0 : 0) : TOK;
+  const int kc = (int)(K / 8);  // 16-byte chunks per row
+  const uint4* src = reinterpret_cast<const uint4*>(X + t0 * K);
+  for (int i = tid; i < (int)nrows * kc; i += 512) {
+    const int row = i / kc, col = i - row * kc;
+    s_rows4[(row * stride) / 8 + col] = src[i];
+  }
+  __syncthreads();
+  constexpr int UPW = 64 / TOK;  // units per wave and pass
+  const int lane = tid & 63, wave = tid >> 6;
+  const int c = lane % TOK, q = lane / TOK;
+  const long long t = t0 + c;
+  const long long ns = Kp / 32;
+  const long long obase = (t / 16) * ns * 64 + (t % 16);
+  const uint16_t* row = s_rows + c * stride;
+  const bool live = t < M;
+  const int nunits = (int)(Kp / 8);
+  for (int u = wave * UPW + q; u < nunits; u += 8 * UPW) {
+    const int k0 = u * 8;
+    uint16_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (live && k0 < K) {  // K % 8 == 0: a unit is entirely inside or outside the real channels
+      if (perm) {
+        const int4 p0 = *reinterpret_cast<const int4*>(perm + k0);
+        const int4 p1 = *reinterpret_cast<const int4*>(perm + k0 + 4);
+        v[0] = row[p0.x];
+        v[1] = row[p0.y];
+        v[2] = row[p0.z];
+        v[3] = row[p0.w];
+        v[4] = row[p1.x];
+        v[5] = row[p1.y];
+        v[6] = row[p1.z];
+        v[7] = row[p1.w];
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; e++) v[e] = row[k0 + e];
+      }
+    }
+    uint4 o;
+    o.x = v[0] | ((uint32_t)v[1] << 16);
+    o.y = v[2] | ((uint32_t)v[3] << 16);
+    o.z = v[4] | ((uint32_t)v[5] << 16);
+    o.w = v[6] | ((uint32_t)v[7] << 16);
+    // unit u = 4 s32 + g of token tile t / 16: X' unit (tt ns + s32) 64 + 16 g + t % 16
+    Xf[obase + (long long)(u >> 2) * 64 + (u & 3) * 16] = o;
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // epilogue helpers
 // ------------------------------------------------------------------------------------------------
@@ -395,14 +455,19 @@ struct TileState {
   unsigned lane, x_lane, wave, wr, wc, nks;
 };
 
-template <int SPARSE, int TR, int TC, int NWC>
-__device__ __forceinline__ void tile_prefetch(TileState<TR, TC, NWC>& st, uint4* sa, uint4* sb, uint32_t* sm, unsigned kn) {
+// every vector-memory operation of the pipeline is a DMA into LDS: they keep their program order,
+// which the stage-end wait counts on
+template <int TR, int TC, int NWC>
+__device__ __forceinline__ void tile_prefetch_b(TileState<TR, TC, NWC>& st, uint4* sb, unsigned kn) {
   using State = TileState<TR, TC, NWC>;
-  // every vector-memory operation of the pipeline is a DMA into LDS: they keep their program order,
-  // which the stage-end wait counts on
 #pragma unroll
   for (int p = 0; p < State::BCOPIES; p++)
     global_to_lds_16(st.x_src[p] + (kn * 128u + st.x_lane), sb + State::NT * p + st.wave * 64);
+}
+
+template <int SPARSE, int TR, int TC, int NWC>
+__device__ __forceinline__ void tile_prefetch_a(TileState<TR, TC, NWC>& st, uint4* sa, uint32_t* sm, unsigned kn) {
+  using State = TileState<TR, TC, NWC>;
 #pragma unroll
   for (int p = 0; p < State::ACOPIES; p++) {
     // chunk q = NW p + w of 64 units.  sparse: row tile q; dense: row tile q / 2, half q % 2 (NW is even: half w % 2)
@@ -414,24 +479,36 @@ __device__ __forceinline__ void tile_prefetch(TileState<TR, TC, NWC>& st, uint4*
   }
 }
 
-template <int DT, int SPARSE, int TR, int TC, int NWC>
-__device__ __forceinline__ void tile_multiply(TileState<TR, TC, NWC>& st, const uint4* sa, const uint4* sb, const uint32_t* sm,
-                                              unsigned k) {
+// the A side of one stage in registers: the wave's TR weight operands and their raw index words
+template <int SPARSE, int TR>
+struct TileRegs {
   uint4 a[SPARSE ? TR : 2 * TR];
+  uint32_t m[SPARSE ? TR : 1];
+};
+
+template <int SPARSE, int TR, int TC, int NWC>
+__device__ __forceinline__ void tile_load_a(TileState<TR, TC, NWC>& st, const uint4* sa, const uint32_t* sm,
+                                            TileRegs<SPARSE, TR>& r) {
+#pragma unroll
+  for (int i = 0; i < TR; i++) {
+    if (SPARSE) {
+      r.a[i] = sa[(st.wr * TR + i) * 64 + st.lane];
+      r.m[i] = sm[(st.wr * TR + i) * 64 + st.lane];
+    } else {
+      r.a[2 * i] = sa[(st.wr * TR + i) * 128 + st.lane];
+      r.a[2 * i + 1] = sa[(st.wr * TR + i) * 128 + 64 + st.lane];
+    }
+  }
+}
+
+template <int DT, int SPARSE, int TR, int TC, int NWC>
+__device__ __forceinline__ void tile_multiply(TileState<TR, TC, NWC>& st, const TileRegs<SPARSE, TR>& r, const uint4* sb,
+                                              unsigned k) {
   int idx[TR];
   if (SPARSE) {
     const unsigned sh = (k & 1u) * 16u;  // the word holds the index halves of an even and an odd stage
 #pragma unroll
-    for (int i = 0; i < TR; i++) idx[i] = (int)(sm[(st.wr * TR + i) * 64 + st.lane] >> sh);
-  }
-#pragma unroll
-  for (int i = 0; i < TR; i++) {
-    if (SPARSE) {
-      a[i] = sa[(st.wr * TR + i) * 64 + st.lane];
-    } else {
-      a[2 * i] = sa[(st.wr * TR + i) * 128 + st.lane];
-      a[2 * i + 1] = sa[(st.wr * TR + i) * 128 + 64 + st.lane];
-    }
+    for (int i = 0; i < TR; i++) idx[i] = (int)(r.m[i] >> sh);
   }
   const uint4* b = sb + (st.wc * TC) * 128 + st.lane;
   // B operands are read one token tile ahead of the multiplies that use them
@@ -446,52 +523,64 @@ __device__ __forceinline__ void tile_multiply(TileState<TR, TC, NWC>& st, const 
 #pragma unroll
     for (int i = 0; i < TR; i++) {
       if (SPARSE) {
-        st.acc[i][j] = smfmac16<DT, 0>(a[i], b0, b1, st.acc[i][j], idx[i]);
+        st.acc[i][j] = smfmac16<DT, 0>(r.a[i], b0, b1, st.acc[i][j], idx[i]);
       } else {
-        st.acc[i][j] = mfma16<DT>(a[2 * i], b0, st.acc[i][j]);
-        st.acc[i][j] = mfma16<DT>(a[2 * i + 1], b1, st.acc[i][j]);
+        st.acc[i][j] = mfma16<DT>(r.a[2 * i], b0, st.acc[i][j]);
+        st.acc[i][j] = mfma16<DT>(r.a[2 * i + 1], b1, st.acc[i][j]);
       }
     }
     b0 = n0;
     b1 = n1;
   }
-  // the order wanted for this region: all A operands and the first B operand, then for every token
-  // tile "read the next B operand, multiply with the current one, issue a share of the prefetch DMA":
-  // a wave that issued all its DMA in one burst would sit at the (bandwidth-limited) vector-memory
-  // issue while the matrix pipe runs dry
-  constexpr int DMA = TileState<TR, TC, NWC>::BCOPIES + (SPARSE ? 2 : 1) * TileState<TR, TC, NWC>::ACOPIES;
-  constexpr int DPJ = (DMA + TC - 1) / TC;
-  sched_group<0x100, (SPARSE ? 2 * TR : 2 * TR) + 2>();
+}
+
+// End of a stage: wait until at most the DMA operations of the newest prefetch are outstanding (they
+// are the last vector-memory operations issued, and DMA keeps its program order), so every older DMA
+// - in particular the ones that filled the next stage's buffers - has landed, and until this wave's
+// LDS reads have returned (the buffer they read is overwritten by the next stage's DMA); then meet
+// the other waves.
+template <int DMA_PER_STAGE>
+__device__ __forceinline__ void tile_arrive() {
+#if defined(__HIP_DEVICE_COMPILE__)
+  // s_waitcnt: vmcnt = DMA_PER_STAGE (6 bits, split 3:0 / 15:14), lgkmcnt = 0, expcnt left at "do not wait"
+  __builtin_amdgcn_s_waitcnt((DMA_PER_STAGE & 15) | ((DMA_PER_STAGE >> 4) << 14) | 0x0070);
+  __builtin_amdgcn_s_barrier();
+#endif
+}
+
+// One pipeline stage k.  On entry the wave holds the A side of stage k in `cur`; the LDS buffers hold
+// B(k) (b_cur), A(k+1) (a_nxt / m_nxt) and, landed or landing, B(k+1) and A(k+2).  The stage
+//   - issues the DMA of B(k+2) into the buffer B(k-1) was in and of A(k+3) into the buffer A(k) was in,
+//   - copies A(k+1) from LDS to `nxt` (off the critical path: those registers are used one stage on),
+//   - multiplies stage k: B operands stream from LDS one token tile ahead,
+//   - waits for the DMA issued in stage k-1 (B(k+1), A(k+2)) and meets the other waves.
+// After a barrier a wave can thus start multiplying as soon as its first B operand is read.
+template <int DT, int SPARSE, int TR, int TC, int NWC>
+__device__ __forceinline__ void tile_stage(TileState<TR, TC, NWC>& st, const TileRegs<SPARSE, TR>& cur,
+                                           TileRegs<SPARSE, TR>& nxt, const uint4* b_cur, const uint4* a_nxt,
+                                           const uint32_t* m_nxt, uint4* b_pre, uint4* a_pre, uint32_t* m_pre, unsigned k) {
+  using State = TileState<TR, TC, NWC>;
+  constexpr int DMA = State::BCOPIES + (SPARSE ? 2 : 1) * State::ACOPIES;
+  constexpr int DPJ = (DMA + TC - 1) / TC;                   // DMA operations issued per token tile
+  constexpr int AREADS = SPARSE ? 2 * TR : 2 * TR;           // LDS reads of tile_load_a
+  constexpr int APJ = (AREADS + TC - 1) / TC;
+  const unsigned last = st.nks - 1;                          // past the end: reload the last stage (never used)
+  tile_prefetch_b<TR, TC, NWC>(st, b_pre, k + 2 < st.nks ? k + 2 : last);
+  tile_prefetch_a<SPARSE, TR, TC, NWC>(st, a_pre, m_pre, k + 3 < st.nks ? k + 3 : last);
+  tile_multiply<DT, SPARSE, TR, TC, NWC>(st, cur, b_cur, k);
+  tile_load_a<SPARSE, TR, TC, NWC>(st, a_nxt, m_nxt, nxt);
+  // the order wanted within the stage: first B operand; then per token tile "read the next B operand,
+  // multiply, issue a share of the DMA, read a share of the next stage's A side".  A wave that issued
+  // its DMA in one burst would sit at the (bandwidth-limited) vector-memory issue while the matrix
+  // pipe runs dry.
+  sched_group<0x100, 2>();
 #pragma unroll
   for (int j = 0; j < TC; j++) {
     if (j + 1 < TC) sched_group<0x100, 2>();
     sched_group<0x008, SPARSE ? TR : 2 * TR>();
     sched_group<0x010, DPJ>();
+    sched_group<0x100, APJ>();
   }
-}
-
-// End of a stage: wait until at most the DMA operations of the newest prefetch are outstanding (they
-// are the last vector-memory operations issued, and DMA keeps its program order), so every older DMA
-// - in particular the one that filled the next stage's buffers - has landed; then meet the other waves.
-template <int DMA_PER_STAGE>
-__device__ __forceinline__ void tile_arrive() {
-#if defined(__HIP_DEVICE_COMPILE__)
-  // s_waitcnt: vmcnt = DMA_PER_STAGE (6 bits, split 3:0 / 15:14), expcnt and lgkmcnt left at "do not wait"
-  __builtin_amdgcn_s_waitcnt((DMA_PER_STAGE & 15) | ((DMA_PER_STAGE >> 4) << 14) | 0x0F70);
-  __builtin_amdgcn_s_barrier();
-#endif
-}
-
-// one pipeline stage: prefetch stage k+2 into the PRE buffers, multiply stage k out of the CUR buffers,
-// make sure stage k+1 has landed for everybody
-template <int DT, int SPARSE, int TR, int TC, int NWC>
-__device__ __forceinline__ void tile_stage(TileState<TR, TC, NWC>& st, const uint4* sa_cur, const uint4* sb_cur,
-                                           const uint32_t* sm_cur, uint4* sa_pre, uint4* sb_pre, uint32_t* sm_pre,
-                                           unsigned k) {
-  constexpr int DMA = TileState<TR, TC, NWC>::BCOPIES + (SPARSE ? 2 : 1) * TileState<TR, TC, NWC>::ACOPIES;
-  const unsigned kn = (k + 2 < st.nks) ? k + 2 : st.nks - 1;  // past the end: reload the last stage (never used)
-  tile_prefetch<SPARSE, TR, TC, NWC>(st, sa_pre, sb_pre, sm_pre, kn);
-  tile_multiply<DT, SPARSE, TR, TC, NWC>(st, sa_cur, sb_cur, sm_cur, k);  // same scheduling region: the DMA is spread over it
   sched_fence();
   tile_arrive<DMA>();
 }
@@ -540,19 +629,28 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
 #pragma unroll
     for (int j = 0; j < TC; j++) st.acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
-  // prologue: stages 0 and 1 in flight, then wait for stage 0
-  tile_prefetch<SPARSE, TR, TC, NWC>(st, sa0, sb0, sm0, 0u);
-  tile_prefetch<SPARSE, TR, TC, NWC>(st, sa1, sb1, sm1, st.nks > 1 ? 1u : 0u);
+  // prologue: B(0), B(1), A(0), A(1), A(2) in flight; wait for all of them; A(0) to registers
+  const unsigned last = st.nks - 1;
+  tile_prefetch_b<TR, TC, NWC>(st, sb0, 0u);
+  tile_prefetch_a<SPARSE, TR, TC, NWC>(st, sa0, sm0, 0u);
+  tile_prefetch_b<TR, TC, NWC>(st, sb1, 1u < st.nks ? 1u : last);
+  tile_prefetch_a<SPARSE, TR, TC, NWC>(st, sa1, sm1, 1u < st.nks ? 1u : last);
+  tile_prefetch_a<SPARSE, TR, TC, NWC>(st, sa2, sm2, 2u < st.nks ? 2u : last);
   sched_fence();
-  tile_arrive<State::BCOPIES + (SPARSE ? 2 : 1) * State::ACOPIES>();
+  tile_arrive<0>();
+  TileRegs<SPARSE, TR> r0, r1;
+  tile_load_a<SPARSE, TR, TC, NWC>(st, sa0, sm0, r0);
+  sched_fence();
+  tile_arrive<0>();  // every wave has A(0) in registers before stage 0 overwrites its buffer
   unsigned k = 0;
   for (; k + 3 <= st.nks; k += 3) {
-    tile_stage<DT, SPARSE, TR, TC, NWC>(st, sa0, sb0, sm0, sa2, sb2, sm2, k);
-    tile_stage<DT, SPARSE, TR, TC, NWC>(st, sa1, sb1, sm1, sa0, sb0, sm0, k + 1);
-    tile_stage<DT, SPARSE, TR, TC, NWC>(st, sa2, sb2, sm2, sa1, sb1, sm1, k + 2);
+    tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, sb0, sa1, sm1, sb2, sa0, sm0, k);
+    tile_stage<DT, SPARSE, TR, TC, NWC>(st, r1, r0, sb1, sa2, sm2, sb0, sa1, sm1, k + 1);
+    tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, sb2, sa0, sm0, sb1, sa2, sm2, k + 2);
+    r0 = r1;
   }
-  if (k < st.nks) tile_stage<DT, SPARSE, TR, TC, NWC>(st, sa0, sb0, sm0, sa2, sb2, sm2, k);
-  if (k + 1 < st.nks) tile_stage<DT, SPARSE, TR, TC, NWC>(st, sa1, sb1, sm1, sa0, sb0, sm0, k + 1);
+  if (k < st.nks) tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, sb0, sa1, sm1, sb2, sa0, sm0, k);
+  if (k + 1 < st.nks) tile_stage<DT, SPARSE, TR, TC, NWC>(st, r1, r0, sb1, sa2, sm2, sb0, sa1, sm1, k + 1);
 
   const int c = (int)(st.lane & 15), g = (int)(st.lane >> 4);
 #pragma unroll
@@ -633,13 +731,15 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
 
 int esp_default_variant(long long M, long long N, long long K, int sparse) {
   (void)K;
-  (void)sparse;
   if (M <= 32) {
     const long long nrt = esp_round_up(N, 16) / 16;
     return nrt <= 320 ? 4 : 5;  // ksplit_w16_r1 / ksplit_w16_r2
   }
   if (M <= 128) return 1;  // wave_r2_t2_splitk
-  return 10;               // tile_t256
+  // 8-wave tile kernels: 256-token macro tiles once they give most of the 256 CUs a tile, else 128-token ones
+  const long long rows = sparse ? 256 : 128;
+  const long long tiles256 = ((N + rows - 1) / rows) * ((M + 255) / 256);
+  return tiles256 >= 200 ? 12 : 13;  // tile_w8_t256 / tile_w8_t128
 }
 
 size_t esp_workspace_bytes(long long M, long long N, long long K) {
@@ -704,11 +804,49 @@ static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const
   return ESPARSE_OK;
 }
 
+// rows of X per workgroup of k_gather_rows: the largest power of two <= 16 whose padded rows fit the
+// LDS budget, lowered while that leaves fewer than ~2 workgroups per CU
+static int gather_rows_tok(long long Mp, long long K) {
+  const long long budget = 144 * 1024;
+  int tok = 16;
+  while (tok > 1 && (long long)tok * (K + 8) * 2 > budget) tok >>= 1;
+  if ((long long)tok * (K + 8) * 2 > budget) return 0;
+  while (tok > 1 && Mp / tok < 512) tok >>= 1;
+  return tok;
+}
+
+template <int TOK>
+static hipError_t launch_gather_rows(hipStream_t st, const uint16_t* X, const int32_t* perm, long long M, long long K,
+                                     long long Mp, long long Kp, uint4* Xf) {
+  const size_t smem = (size_t)TOK * (K + 8) * 2;
+  static bool raised = false;  // once per process: allow the kernel more than the default 64 KiB of dynamic LDS
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gather_rows<TOK>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  hipLaunchKernelGGL(k_gather_rows<TOK>, dim3((unsigned)(Mp / TOK)), dim3(512), smem, st, X, perm, M, K, Kp, Xf);
+  return hipGetLastError();
+}
+
 static int stage_activations(esparse_ctx* ctx, const void* X, const int32_t* perm, long long M, long long K, long long Mp,
                              long long Kp, uint4* Xf) {
+  const uint16_t* Xh = reinterpret_cast<const uint16_t*>(X);
+  const int tok = (M >= 64 && K % 8 == 0) ? gather_rows_tok(Mp, K) : 0;
+  if (tok) {
+    hipStream_t st = ctx->stream;
+    switch (tok) {
+      case 16: ESP_HIP(ctx, launch_gather_rows<16>(st, Xh, perm, M, K, Mp, Kp, Xf)); break;
+      case 8: ESP_HIP(ctx, launch_gather_rows<8>(st, Xh, perm, M, K, Mp, Kp, Xf)); break;
+      case 4: ESP_HIP(ctx, launch_gather_rows<4>(st, Xh, perm, M, K, Mp, Kp, Xf)); break;
+      case 2: ESP_HIP(ctx, launch_gather_rows<2>(st, Xh, perm, M, K, Mp, Kp, Xf)); break;
+      default: ESP_HIP(ctx, launch_gather_rows<1>(st, Xh, perm, M, K, Mp, Kp, Xf)); break;
+    }
+    return ESPARSE_OK;
+  }
   const long long units = Mp * Kp / 8;
-  hipLaunchKernelGGL(k_gather_x, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, ctx->stream,
-                     reinterpret_cast<const uint16_t*>(X), perm, M, K, Kp, units, Xf);
+  hipLaunchKernelGGL(k_gather_x, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, ctx->stream, Xh, perm, M, K, Kp, units, Xf);
   ESP_HIP(ctx, hipGetLastError());
   return ESPARSE_OK;
 }
