@@ -240,9 +240,12 @@ def test_config4_all_layers_resident(esp, ctx):
         Xc = wl.calibration(cfg, layer, T=T_SUB, device="cuda")
         scores[layer] = orc.channel_score(_np(Xc), alpha, 100)
         del Xc
+    import gc
+    gc.collect()                                       # tensors of earlier tests that sit in reference cycles
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
     free0, total = torch.cuda.mem_get_info()
+    alloc0 = torch.cuda.memory_allocated()
     resident = []                                      # (layer kind, instance, Compressed, theta)
     dense_bytes = 0
     closed_form = 0
@@ -268,14 +271,18 @@ def test_config4_all_layers_resident(esp, ctx):
     torch.cuda.empty_cache()
     free1, _ = torch.cuda.mem_get_info()
     used = free0 - free1
+    held = torch.cuda.memory_allocated() - alloc0      # bytes of the tensors this test keeps
     params = dense_bytes // 2
     print(f"    parameters {params / 1e9:.2f} G, dense {dense_bytes / 1e9:.2f} GB, closed form {closed_form / 1e9:.2f} GB, "
           f"device memory taken {used / 1e9:.2f} GB of {total / 1e9:.1f} GB", flush=True)
     assert len(resident) == LAYERS * 7
     assert closed_form * 16 == dense_bytes * 9
     perm_bytes = sum(4 * r[3].numel() for r in resident)
-    # allocator granularity (2 MiB per tensor) and the permutations are all that may come on top
-    assert closed_form <= used <= closed_form + perm_bytes + len(resident) * 2 * (4 << 20)
+    slack = perm_bytes + len(resident) * 2 * (4 << 20)      # allocator granularity and the permutations
+    assert closed_form <= held <= closed_form + slack
+    # what the driver reports: no hidden overhead on top; the runtime may hand out memory that it still counted
+    # as in use when the baseline was read (freed scratch of earlier calls), hence the 2 % below
+    assert 0.98 * closed_form <= used <= closed_form + slack
     assert used < 0.57 * dense_bytes
 
     # the resident matrices still multiply correctly: first, middle and last layer, sampled outputs
