@@ -32,8 +32,14 @@ import torch  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant product kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on
 # `bench.py --counter-probe` and scaled by the same counters' reading for a copy kernel of known size;
-# key (config, M, N, K).  The summaries are kept under profiles/.
-MEASURED_TRAFFIC = {}
+# key (config, M, N, K), value = fetched + written bytes.  The summaries are kept under profiles/.
+MEASURED_TRAFFIC = {
+    (2, 1, 4096, 4096): 19974609, (2, 8, 4096, 4096): 20030503, (2, 32, 4096, 4096): 21278653,
+    (2, 1, 11008, 4096): 51866143, (2, 8, 11008, 4096): 52021023, (2, 32, 11008, 4096): 54076166,
+    (2, 1, 4096, 11008): 53591110, (2, 8, 4096, 11008): 53647089, (2, 32, 4096, 11008): 56664533,
+    (3, 512, 5120, 5120): 82745824, (3, 2048, 5120, 5120): 314272462, (3, 512, 13824, 5120): 144935671,
+    (3, 2048, 13824, 5120): 504618024, (3, 512, 5120, 13824): 220277027, (3, 2048, 5120, 13824): 842458894,
+}
 SPARSE_MFMA_PEAK_TFLOPS = 5000.0   # dense-equivalent flops of the 2:4 MFMA path: twice the dense 16-bit peak of 2.5 PFLOP/s
 DEFAULT_LAYERS = 3
 # (name, layer-shape key, calibration / activation stream, products per layer with this shape)
@@ -139,6 +145,16 @@ def main():
             for name, skey, _ in MATS for M in M_LIST}
     ws_bytes = max(esp.spmm_workspace(M, shapes[skey][0], shapes[skey][1]) for _, skey, _ in MATS for M in M_LIST)
     ws = ctx.workspace(ws_bytes)
+
+    # every shape gets the variant the library's own tuner finds fastest (sparse and dense alike)
+    tuned = {}
+    dcode = esp.F16 if tdtype == torch.float16 else esp.BF16
+    for skey in {m[1] for m in MATS}:
+        N, K = shapes[skey]
+        for M in M_LIST:
+            vs, _ = ctx.tune(M, N, K, dcode, True)
+            vd, _ = ctx.tune(M, N, K, dcode, False)
+            tuned[f"{skey}/M={M}"] = [esp.variant_name(vs), esp.variant_name(vd)]
 
     # ------------------------------------------------------------------ steps
     def step_sparse():
@@ -247,12 +263,9 @@ def main():
             torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / (3 * reps)
 
-    def kernel_name(M, sparse=True):
-        if M <= 32:
-            return "k_mm_ksplit" + ("" if sparse else " (dense)")
-        if M <= 128:
-            return "k_mm_wave_tile" + ("" if sparse else " (dense)")
-        return "k_mm_tile" + ("" if sparse else " (dense)")
+    def kernel_name(skey, M):
+        v = tuned[f"{skey}/M={M}"][0]
+        return {"ksplit": "k_mm_ksplit", "wave": "k_mm_wave_tile", "tile": "k_mm_tile"}[v.split("_")[0]] + f" [{v}]"
 
     per_shape = []
     seen = set()
@@ -285,7 +298,7 @@ def main():
             flops = 2.0 * M * N * K
             mfma_bound = M >= 512
             row = dict(layer=skey, N=N, K=K, M=M, count_per_layer=count, bound="mfma" if mfma_bound else "hbm",
-                       kernel=kernel_name(M),
+                       kernel=kernel_name(skey, M),
                        spmm_kernel_us=round(ts * 1e6, 2), dense_kernel_us=round(td * 1e6, 2),
                        stage_kernel_us=round(tg * 1e6, 2), hipblaslt_dense_us=round(tl * 1e6, 2),
                        eff_tflops=round(flops / (ts + tg) / 1e12, 2),
@@ -393,6 +406,7 @@ def main():
         "offline": {"prune_ms_per_matrix": round(t_prune / (LAYERS * len(MATS)) * 1e3, 2),
                     "compress_ms_per_matrix": round(t_compress / (LAYERS * len(MATS)) * 1e3, 3),
                     "lbs_swaps_per_matrix": swaps_total // (LAYERS * len(MATS))},
+        "tuned_variants_sparse_dense": tuned,
         "per_shape": per_shape,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,

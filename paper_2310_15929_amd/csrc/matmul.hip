@@ -736,10 +736,10 @@ int esp_default_variant(long long M, long long N, long long K, int sparse) {
     return nrt <= 320 ? 4 : 5;  // ksplit_w16_r1 / ksplit_w16_r2
   }
   if (M <= 128) return 1;  // wave_r2_t2_splitk
-  // 8-wave tile kernels: 256-token macro tiles once they give most of the 256 CUs a tile, else 128-token ones
+  // 8-wave tile kernels: 256-token macro tiles once they give half of the 256 CUs a tile, else 128-token ones
   const long long rows = sparse ? 256 : 128;
   const long long tiles256 = ((N + rows - 1) / rows) * ((M + 255) / 256);
-  return tiles256 >= 200 ? 12 : 13;  // tile_w8_t256 / tile_w8_t128
+  return tiles256 >= 128 ? 12 : 13;  // tile_w8_t256 / tile_w8_t128
 }
 
 size_t esp_workspace_bytes(long long M, long long N, long long K) {
