@@ -442,32 +442,36 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(const uint4* __restrict__
 // multiplies.  Macro tiles are numbered so that the workgroups of one XCD (blockIdx % 8) cover
 // neighbouring tiles and share weight rows in that XCD's L2.
 // ------------------------------------------------------------------------------------------------
-template <int TR, int TC, int NWC>
+template <int SPARSE, int TR, int TC, int NWC>
 struct TileState {
   static constexpr int NW = 2 * NWC;                        // waves: 2 along the rows x NWC along the tokens
   static constexpr int NT = 64 * NW;                        // threads
   static constexpr int BCOPIES = (NWC * TC * 128) / NT;     // 16-byte units of activations per lane and stage
-  static constexpr int ACOPIES = 1024 / NT;                 // 1024 units of weights per stage
+  static constexpr int RTM = 2 * TR;                        // row tiles of 16 in the macro tile
+  static constexpr int AUNITS = RTM * (SPARSE ? 64 : 128);  // 16-byte units of weights per stage
+  static constexpr int ACOPIES = AUNITS / NT;               // ... per lane
+  static_assert(AUNITS % NT == 0 && (NWC * TC * 128) % NT == 0, "every wave copies whole 64-unit chunks");
   floatx4_t acc[TR][TC];
   const uint4* a_src[ACOPIES];  // wave-uniform global bases of this wave's DMA copies
   const uint4* x_src[BCOPIES];
   const uint32_t* m_src[ACOPIES];  // index words (two stages of index halves per lane) of the copied row tiles
-  unsigned lane, x_lane, wave, wr, wc, nks;
+  unsigned lane, x_lane, wave, wr, wc;
+  unsigned k0, k1;  // this workgroup's stages [k0, k1) of the K loop (all of them unless K is split)
 };
 
 // every vector-memory operation of the pipeline is a DMA into LDS: they keep their program order,
 // which the stage-end wait counts on
-template <int TR, int TC, int NWC>
-__device__ __forceinline__ void tile_prefetch_b(TileState<TR, TC, NWC>& st, uint4* sb, unsigned kn) {
-  using State = TileState<TR, TC, NWC>;
+template <int SPARSE, int TR, int TC, int NWC>
+__device__ __forceinline__ void tile_prefetch_b(TileState<SPARSE, TR, TC, NWC>& st, uint4* sb, unsigned kn) {
+  using State = TileState<SPARSE, TR, TC, NWC>;
 #pragma unroll
   for (int p = 0; p < State::BCOPIES; p++)
     global_to_lds_16(st.x_src[p] + (kn * 128u + st.x_lane), sb + State::NT * p + st.wave * 64);
 }
 
 template <int SPARSE, int TR, int TC, int NWC>
-__device__ __forceinline__ void tile_prefetch_a(TileState<TR, TC, NWC>& st, uint4* sa, uint32_t* sm, unsigned kn) {
-  using State = TileState<TR, TC, NWC>;
+__device__ __forceinline__ void tile_prefetch_a(TileState<SPARSE, TR, TC, NWC>& st, uint4* sa, uint32_t* sm, unsigned kn) {
+  using State = TileState<SPARSE, TR, TC, NWC>;
 #pragma unroll
   for (int p = 0; p < State::ACOPIES; p++) {
     // chunk q = NW p + w of 64 units.  sparse: row tile q; dense: row tile q / 2, half q % 2 (NW is even: half w % 2)
@@ -487,7 +491,7 @@ struct TileRegs {
 };
 
 template <int SPARSE, int TR, int TC, int NWC>
-__device__ __forceinline__ void tile_load_a(TileState<TR, TC, NWC>& st, const uint4* sa, const uint32_t* sm,
+__device__ __forceinline__ void tile_load_a(TileState<SPARSE, TR, TC, NWC>& st, const uint4* sa, const uint32_t* sm,
                                             TileRegs<SPARSE, TR>& r) {
 #pragma unroll
   for (int i = 0; i < TR; i++) {
@@ -502,7 +506,7 @@ __device__ __forceinline__ void tile_load_a(TileState<TR, TC, NWC>& st, const ui
 }
 
 template <int DT, int SPARSE, int TR, int TC, int NWC>
-__device__ __forceinline__ void tile_multiply(TileState<TR, TC, NWC>& st, const TileRegs<SPARSE, TR>& r, const uint4* sb,
+__device__ __forceinline__ void tile_multiply(TileState<SPARSE, TR, TC, NWC>& st, const TileRegs<SPARSE, TR>& r, const uint4* sb,
                                               unsigned k) {
   int idx[TR];
   if (SPARSE) {
@@ -556,17 +560,17 @@ __device__ __forceinline__ void tile_arrive() {
 //   - waits for the DMA issued in stage k-1 (B(k+1), A(k+2)) and meets the other waves.
 // After a barrier a wave can thus start multiplying as soon as its first B operand is read.
 template <int DT, int SPARSE, int TR, int TC, int NWC>
-__device__ __forceinline__ void tile_stage(TileState<TR, TC, NWC>& st, const TileRegs<SPARSE, TR>& cur,
+__device__ __forceinline__ void tile_stage(TileState<SPARSE, TR, TC, NWC>& st, const TileRegs<SPARSE, TR>& cur,
                                            TileRegs<SPARSE, TR>& nxt, const uint4* b_cur, const uint4* a_nxt,
                                            const uint32_t* m_nxt, uint4* b_pre, uint4* a_pre, uint32_t* m_pre, unsigned k) {
-  using State = TileState<TR, TC, NWC>;
+  using State = TileState<SPARSE, TR, TC, NWC>;
   constexpr int DMA = State::BCOPIES + (SPARSE ? 2 : 1) * State::ACOPIES;
   constexpr int DPJ = (DMA + TC - 1) / TC;                   // DMA operations issued per token tile
   constexpr int AREADS = SPARSE ? 2 * TR : 2 * TR;           // LDS reads of tile_load_a
   constexpr int APJ = (AREADS + TC - 1) / TC;
-  const unsigned last = st.nks - 1;                          // past the end: reload the last stage (never used)
-  tile_prefetch_b<TR, TC, NWC>(st, b_pre, k + 2 < st.nks ? k + 2 : last);
-  tile_prefetch_a<SPARSE, TR, TC, NWC>(st, a_pre, m_pre, k + 3 < st.nks ? k + 3 : last);
+  const unsigned last = st.k1 - 1;                           // past the end: reload the last stage (never used)
+  tile_prefetch_b<SPARSE, TR, TC, NWC>(st, b_pre, k + 2 < st.k1 ? k + 2 : last);
+  tile_prefetch_a<SPARSE, TR, TC, NWC>(st, a_pre, m_pre, k + 3 < st.k1 ? k + 3 : last);
   tile_multiply<DT, SPARSE, TR, TC, NWC>(st, cur, b_cur, k);
   tile_load_a<SPARSE, TR, TC, NWC>(st, a_nxt, m_nxt, nxt);
   // the order wanted within the stage: first B operand; then per token tile "read the next B operand,
@@ -590,11 +594,11 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
     uint4* __restrict__ sa0, uint4* __restrict__ sa1, uint4* __restrict__ sa2, uint4* __restrict__ sb0, uint4* __restrict__ sb1,
     uint4* __restrict__ sb2, uint32_t* __restrict__ sm0, uint32_t* __restrict__ sm1, uint32_t* __restrict__ sm2,
     const uint4* __restrict__ A, const uint16_t* __restrict__ meta16, const uint4* __restrict__ Xf,
-    uint16_t* __restrict__ Y, long long M, long long N, long long Mp, long long Np, long long Kp, long long n_tiles,
-    long long ntb) {
+    uint16_t* __restrict__ Y, float* __restrict__ partial, long long M, long long N, long long Mp, long long Np, long long Kp,
+    long long n_tiles, long long ntb, int nsplit, int sps) {
   constexpr int NTT = NWC * TC;               // token tiles of 16 in the macro tile
-  constexpr int RTM = 2 * TR;                 // row tiles of 16 in the macro tile (sparse 16, dense 8)
-  using State = TileState<TR, TC, NWC>;
+  constexpr int RTM = 2 * TR;                 // row tiles of 16 in the macro tile
+  using State = TileState<SPARSE, TR, TC, NWC>;
   const int tid = threadIdx.x;
   State st;
   st.lane = (unsigned)(tid & 63);
@@ -602,11 +606,16 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
   st.wr = st.wave / NWC;
   st.wc = st.wave % NWC;
   const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
-  st.nks = (unsigned)nks;
-  // XCD-aware numbering: XCD x (= blockIdx % 8) works through tiles [x * per, (x + 1) * per)
-  const long long per = (n_tiles + 7) / 8;
-  const long long tile = (long long)(blockIdx.x & 7) * per + (blockIdx.x >> 3);
-  if ((long long)(blockIdx.x >> 3) >= per || tile >= n_tiles) return;
+  // XCD-aware numbering: XCD x (= blockIdx % 8) works through items [x * per, (x + 1) * per); an item is
+  // a macro tile and one of the nsplit ranges of K stages (the split varies fastest)
+  const long long n_items = n_tiles * nsplit;
+  const long long per = (n_items + 7) / 8;
+  const long long item = (long long)(blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if ((long long)(blockIdx.x >> 3) >= per || item >= n_items) return;
+  const long long tile = item / nsplit;
+  const int split = (int)(item % nsplit);
+  st.k0 = (unsigned)((long long)split * sps);
+  st.k1 = (unsigned)(((long long)(split + 1) * sps < nks) ? (long long)(split + 1) * sps : nks);
   const long long rb = tile / ntb, tb = tile % ntb;
   const long long rt_macro = rb * RTM;  // first row tile of the macro tile
   const long long tt_base = tb * NTT;   // first token tile of the macro tile
@@ -629,28 +638,32 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
 #pragma unroll
     for (int j = 0; j < TC; j++) st.acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
-  // prologue: B(0), B(1), A(0), A(1), A(2) in flight; wait for all of them; A(0) to registers
-  const unsigned last = st.nks - 1;
-  tile_prefetch_b<TR, TC, NWC>(st, sb0, 0u);
-  tile_prefetch_a<SPARSE, TR, TC, NWC>(st, sa0, sm0, 0u);
-  tile_prefetch_b<TR, TC, NWC>(st, sb1, 1u < st.nks ? 1u : last);
-  tile_prefetch_a<SPARSE, TR, TC, NWC>(st, sa1, sm1, 1u < st.nks ? 1u : last);
-  tile_prefetch_a<SPARSE, TR, TC, NWC>(st, sa2, sm2, 2u < st.nks ? 2u : last);
+  // prologue: B and A of the first two stages and A of the third in flight; wait for all of them; the first A side to registers
+  const unsigned last = st.k1 - 1;
+  const unsigned kb = st.k0;
+  tile_prefetch_b<SPARSE, TR, TC, NWC>(st, sb0, kb);
+  tile_prefetch_a<SPARSE, TR, TC, NWC>(st, sa0, sm0, kb);
+  tile_prefetch_b<SPARSE, TR, TC, NWC>(st, sb1, kb + 1 < st.k1 ? kb + 1 : last);
+  tile_prefetch_a<SPARSE, TR, TC, NWC>(st, sa1, sm1, kb + 1 < st.k1 ? kb + 1 : last);
+  tile_prefetch_a<SPARSE, TR, TC, NWC>(st, sa2, sm2, kb + 2 < st.k1 ? kb + 2 : last);
   sched_fence();
   tile_arrive<0>();
   TileRegs<SPARSE, TR> r0, r1;
   tile_load_a<SPARSE, TR, TC, NWC>(st, sa0, sm0, r0);
   sched_fence();
-  tile_arrive<0>();  // every wave has A(0) in registers before stage 0 overwrites its buffer
-  unsigned k = 0;
-  for (; k + 3 <= st.nks; k += 3) {
+  tile_arrive<0>();  // every wave has its first A side in registers before the first stage overwrites its buffer
+  unsigned k = kb;
+  for (; k + 3 <= st.k1; k += 3) {
     tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, sb0, sa1, sm1, sb2, sa0, sm0, k);
     tile_stage<DT, SPARSE, TR, TC, NWC>(st, r1, r0, sb1, sa2, sm2, sb0, sa1, sm1, k + 1);
     tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, sb2, sa0, sm0, sb1, sa2, sm2, k + 2);
     r0 = r1;
   }
-  if (k < st.nks) tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, sb0, sa1, sm1, sb2, sa0, sm0, k);
-  if (k + 1 < st.nks) tile_stage<DT, SPARSE, TR, TC, NWC>(st, r1, r0, sb1, sa2, sm2, sb0, sa1, sm1, k + 1);
+  if (k < st.k1) tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, sb0, sa1, sm1, sb2, sa0, sm0, k);
+  if (k + 1 < st.k1) tile_stage<DT, SPARSE, TR, TC, NWC>(st, r1, r0, sb1, sa2, sm2, sb0, sa1, sm1, k + 1);
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no DMA into this workgroup's LDS is left in flight when the wave ends
+#endif
 
   const int c = (int)(st.lane & 15), g = (int)(st.lane >> 4);
 #pragma unroll
@@ -661,28 +674,33 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
     for (int j = 0; j < TC; j++) {
       const long long tt = tt_base + st.wc * TC + j;
       if (tt >= ntt) continue;
-      store_y4<DT>(Y, M, N, tt * 16 + c, rt * 16 + g * 4, st.acc[i][j]);
+      if (nsplit > 1)  // fp32 partial tile of this K split; k_reduce_splits adds the splits in ascending order
+        *reinterpret_cast<floatx4_t*>(partial + ((long long)split * Mp + tt * 16 + c) * Np + rt * 16 + g * 4) = st.acc[i][j];
+      else
+        store_y4<DT>(Y, M, N, tt * 16 + c, rt * 16 + g * 4, st.acc[i][j]);
     }
   }
 }
 
-// sparse: TR = 8 (macro tile of 16 row tiles); dense: TR = 4 (8 row tiles, operands twice as wide).
+// sparse: TR = 8 (macro tile of 16 row tiles) or 4; dense: half of that (operands twice as wide).
 template <int DT, int SPARSE, int TR, int TC, int NWC>
 __global__ void __launch_bounds__(128 * NWC) k_mm_tile(const uint4* __restrict__ A, const uint16_t* __restrict__ meta16,
-                                                  const uint4* __restrict__ Xf, uint16_t* __restrict__ Y, long long M,
-                                                  long long N, long long Mp, long long Np, long long Kp, long long n_tiles,
-                                                  long long ntb) {
-  __shared__ uint4 s_a0[1024];  // one stage of weights each (16 KiB)
-  __shared__ uint4 s_a1[1024];
-  __shared__ uint4 s_a2[1024];
+                                                        const uint4* __restrict__ Xf, uint16_t* __restrict__ Y,
+                                                        float* __restrict__ partial, long long M, long long N, long long Mp,
+                                                        long long Np, long long Kp, long long n_tiles, long long ntb, int nsplit,
+                                                        int sps) {
+  constexpr int AUNITS = TileState<SPARSE, TR, TC, NWC>::AUNITS;
+  __shared__ uint4 s_a0[AUNITS];  // one stage of weights each
+  __shared__ uint4 s_a1[AUNITS];
+  __shared__ uint4 s_a2[AUNITS];
   __shared__ uint4 s_b0[NWC * TC * 128];  // one stage of activations each: [NWC TC token tiles][2 half steps][64 lanes]
   __shared__ uint4 s_b1[NWC * TC * 128];
   __shared__ uint4 s_b2[NWC * TC * 128];
-  __shared__ uint32_t s_m0[SPARSE ? 1024 : 1];  // one stage pair of index words each: [16 row tiles][64 lanes]
-  __shared__ uint32_t s_m1[SPARSE ? 1024 : 1];
-  __shared__ uint32_t s_m2[SPARSE ? 1024 : 1];
-  tile_pipeline<DT, SPARSE, TR, TC, NWC>(s_a0, s_a1, s_a2, s_b0, s_b1, s_b2, s_m0, s_m1, s_m2, A, meta16, Xf, Y, M, N, Mp, Np, Kp,
-                                    n_tiles, ntb);
+  __shared__ uint32_t s_m0[SPARSE ? 2 * TR * 64 : 1];  // one stage pair of index words each: [row tiles][64 lanes]
+  __shared__ uint32_t s_m1[SPARSE ? 2 * TR * 64 : 1];
+  __shared__ uint32_t s_m2[SPARSE ? 2 * TR * 64 : 1];
+  tile_pipeline<DT, SPARSE, TR, TC, NWC>(s_a0, s_a1, s_a2, s_b0, s_b1, s_b2, s_m0, s_m1, s_m2, A, meta16, Xf, Y, partial, M, N, Mp,
+                                         Np, Kp, n_tiles, ntb, nsplit, sps);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -693,7 +711,7 @@ struct Variant {
   const char* name;
   int kind;
   int rt, tt;      // row tiles / token tiles per wave (ksplit: row tiles per workgroup, tt unused: MT follows M)
-  int split_mode;  // wave kind: 0 = never split K, 1 = split K over workgroups to fill the chip
+  int split_mode;  // wave and tile kinds: 0 = never split K, 1 = split K over workgroups to fill the chip
   int nw;          // ksplit kind: waves per workgroup; tile kind: waves along the tokens (the workgroup has 2 x nw waves)
 };
 static const Variant kVariants[] = {
@@ -711,6 +729,9 @@ static const Variant kVariants[] = {
     {"tile_t128", KIND_TILE, 8, 4, 0, 2},     // 256 rows (dense 128) x 128 tokens per workgroup, 4 waves
     {"tile_w8_t256", KIND_TILE, 8, 4, 0, 4},  // 256 rows (dense 128) x 256 tokens per workgroup, 8 waves (two per SIMD)
     {"tile_w8_t128", KIND_TILE, 8, 2, 0, 4},  // 256 rows (dense 128) x 128 tokens per workgroup, 8 waves
+    {"tile_w8_r128_t128", KIND_TILE, 4, 2, 0, 4},         // 128 rows (dense 64) x 128 tokens per workgroup, 8 waves
+    {"tile_w8_r128_t128_splitk", KIND_TILE, 4, 2, 1, 4},  // ... with K split over workgroups (M <= 128)
+    {"tile_w8_r128_t64_splitk", KIND_TILE, 4, 1, 1, 4},   // 128 rows (dense 64) x 64 tokens, K split (M <= 128)
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -723,8 +744,12 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
   (void)sparse;
   if (v < 0 || v >= kNumVariants) return false;
   const Variant& var = kVariants[v];
-  if (var.kind == KIND_WAVE && var.split_mode == 1 && M > 128) return false;  // partial buffers are sized for decode only
-  if (var.kind == KIND_KSPLIT && M > 32) return false;
+  if (var.split_mode == 1 && M > 128) return false;  // partial buffers are sized for M <= 128 only
+  if (var.kind == KIND_KSPLIT) {
+    if (M > 64) return false;
+    const long long mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);  // token tiles; the waves' partial tiles must fit the LDS
+    if ((long long)var.nw * var.rt * mt * 1024 > 160 * 1024) return false;
+  }
   if (var.kind == KIND_TILE && M < 64) return false;
   return true;
 }
@@ -735,11 +760,14 @@ int esp_default_variant(long long M, long long N, long long K, int sparse) {
     const long long nrt = esp_round_up(N, 16) / 16;
     return nrt <= 320 ? 4 : 5;  // ksplit_w16_r1 / ksplit_w16_r2
   }
-  if (M <= 128) return 1;  // wave_r2_t2_splitk
-  // 8-wave tile kernels: 256-token macro tiles once they give half of the 256 CUs a tile, else 128-token ones
+  if (M <= 64) return 16;   // tile_w8_r128_t64_splitk
+  if (M <= 128) return 15;  // tile_w8_r128_t128_splitk
+  // 8-wave tile kernels: the largest macro tile that still gives half of the 256 CUs a tile
   const long long rows = sparse ? 256 : 128;
-  const long long tiles256 = ((N + rows - 1) / rows) * ((M + 255) / 256);
-  return tiles256 >= 128 ? 12 : 13;  // tile_w8_t256 / tile_w8_t128
+  const long long nrb = (N + rows - 1) / rows;
+  if (nrb * ((M + 255) / 256) >= 128) return 12;  // tile_w8_t256
+  if (nrb * ((M + 127) / 128) >= 128) return 13;  // tile_w8_t128
+  return 14;                                       // tile_w8_r128_t128
 }
 
 size_t esp_workspace_bytes(long long M, long long N, long long K) {
@@ -783,24 +811,45 @@ static void launch_ksplit(const Variant& v, hipStream_t st, const uint4* A, cons
 
 template <int DT, int SPARSE>
 static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const uint4* A, const uint16_t* meta16, const uint4* Xf,
-                       uint16_t* Y, long long M, long long N, long long Mp, long long Np, long long Kp) {
-  constexpr int TR = SPARSE ? 8 : 4;  // the dense operand is twice as wide: half the row tiles per wave
-  const long long nrt = Np / 16, ntt = Mp / 16;
+                       uint16_t* Y, float* partial, long long M, long long N, long long Mp, long long Np, long long Kp) {
+  // the dense operand is twice as wide: half the row tiles per wave
+  const long long rtm = SPARSE ? 2 * v.rt : v.rt;  // row tiles per macro tile
+  const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
   const long long cols = (long long)v.nw * v.tt;  // token tiles per macro tile
-  const long long nrb = (nrt + 2 * TR - 1) / (2 * TR), ntb = (ntt + cols - 1) / cols;
+  const long long nrb = (nrt + rtm - 1) / rtm, ntb = (ntt + cols - 1) / cols;
   const long long n_tiles = nrb * ntb;
-  const long long per = (n_tiles + 7) / 8;
+  int nsplit = 1;
+  long long sps = nks;
+  if (v.split_mode == 1) {
+    // about two workgroups per CU, splits of at least 8 stages (512 channels); no split once the macro
+    // tiles alone cover half of the CUs (the fp32 partial tiles and their reduction then cost more)
+    const long long want = n_tiles >= 128 ? 1 : (512 + n_tiles - 1) / n_tiles;
+    nsplit = (int)std::max<long long>(1, std::min<long long>(std::min<long long>(want, nks / 8), MAX_SPLIT));
+    sps = ((nks + nsplit - 1) / nsplit + 3) / 4 * 4;
+    nsplit = (int)((nks + sps - 1) / sps);
+  }
+  const long long per = (n_tiles * nsplit + 7) / 8;
   dim3 grid((unsigned)(per * 8));
-#define ESP_TILE(TCv, NWCv)                                                                                                  \
-  hipLaunchKernelGGL((k_mm_tile<DT, SPARSE, TR, TCv, NWCv>), grid, dim3(128 * NWCv), 0, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp, \
-                     n_tiles, ntb)
-  if (v.nw == 2 && v.tt == 8) ESP_TILE(8, 2);
-  else if (v.nw == 2 && v.tt == 4) ESP_TILE(4, 2);
-  else if (v.nw == 4 && v.tt == 4) ESP_TILE(4, 4);
-  else if (v.nw == 4 && v.tt == 2) ESP_TILE(2, 4);
+#define ESP_TILE(TRv, TCv, NWCv)                                                                                             \
+  hipLaunchKernelGGL((k_mm_tile<DT, SPARSE, (SPARSE ? TRv : TRv / 2), TCv, NWCv>), grid, dim3(128 * NWCv), 0, st, A, meta16, Xf, Y, \
+                     partial, M, N, Mp, Np, Kp, n_tiles, ntb, nsplit, (int)sps)
+  if (v.rt == 8 && v.nw == 2 && v.tt == 8) ESP_TILE(8, 8, 2);
+  else if (v.rt == 8 && v.nw == 2 && v.tt == 4) ESP_TILE(8, 4, 2);
+  else if (v.rt == 8 && v.nw == 4 && v.tt == 4) ESP_TILE(8, 4, 4);
+  else if (v.rt == 8 && v.nw == 4 && v.tt == 2) ESP_TILE(8, 2, 4);
+  else if (v.rt == 4 && v.nw == 4 && v.tt == 2) ESP_TILE(4, 2, 4);
+  else if (v.rt == 4 && v.nw == 4 && v.tt == 1) ESP_TILE(4, 1, 4);
   else return esp_fail(ctx, ESPARSE_EINVAL, "unknown tile variant");
 #undef ESP_TILE
   ESP_HIP(ctx, hipGetLastError());
+  if (nsplit > 1) {
+    const long long e = M * (Np / 4);
+    if (DT == ESPARSE_F16)
+      hipLaunchKernelGGL(k_reduce_splits<ESPARSE_F16>, dim3((unsigned)((e + 255) / 256)), dim3(256), 0, st, partial, nsplit, M, N, Mp, Np, Y);
+    else
+      hipLaunchKernelGGL(k_reduce_splits<ESPARSE_BF16>, dim3((unsigned)((e + 255) / 256)), dim3(256), 0, st, partial, nsplit, M, N, Mp, Np, Y);
+    ESP_HIP(ctx, hipGetLastError());
+  }
   return ESPARSE_OK;
 }
 
@@ -871,17 +920,20 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
 
   if (v.kind == KIND_KSPLIT) {
     const uint16_t* meta16 = reinterpret_cast<const uint16_t*>(meta_bytes);
+#define ESP_KSPLIT(DTv, SPv)                                                                  \
+  do {                                                                                        \
+    if (ntt == 1) launch_ksplit<DTv, SPv, 1>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);      \
+    else if (ntt == 2) launch_ksplit<DTv, SPv, 2>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp); \
+    else launch_ksplit<DTv, SPv, 4>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);               \
+  } while (0)
     if (dtype == ESPARSE_F16) {
-      if (sparse && ntt == 1) launch_ksplit<ESPARSE_F16, 1, 1>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
-      else if (sparse) launch_ksplit<ESPARSE_F16, 1, 2>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
-      else if (ntt == 1) launch_ksplit<ESPARSE_F16, 0, 1>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
-      else launch_ksplit<ESPARSE_F16, 0, 2>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
+      if (sparse) ESP_KSPLIT(ESPARSE_F16, 1);
+      else ESP_KSPLIT(ESPARSE_F16, 0);
     } else {
-      if (sparse && ntt == 1) launch_ksplit<ESPARSE_BF16, 1, 1>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
-      else if (sparse) launch_ksplit<ESPARSE_BF16, 1, 2>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
-      else if (ntt == 1) launch_ksplit<ESPARSE_BF16, 0, 1>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
-      else launch_ksplit<ESPARSE_BF16, 0, 2>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
+      if (sparse) ESP_KSPLIT(ESPARSE_BF16, 1);
+      else ESP_KSPLIT(ESPARSE_BF16, 0);
     }
+#undef ESP_KSPLIT
     ESP_HIP(ctx, hipGetLastError());
     return ESPARSE_OK;
   }
@@ -889,10 +941,10 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
   if (v.kind == KIND_TILE) {
     const uint16_t* meta16 = reinterpret_cast<const uint16_t*>(meta_bytes);
     if (dtype == ESPARSE_F16)
-      return sparse ? launch_tile<ESPARSE_F16, 1>(ctx, v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp)
-                    : launch_tile<ESPARSE_F16, 0>(ctx, v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
-    return sparse ? launch_tile<ESPARSE_BF16, 1>(ctx, v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp)
-                  : launch_tile<ESPARSE_BF16, 0>(ctx, v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);
+      return sparse ? launch_tile<ESPARSE_F16, 1>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp)
+                    : launch_tile<ESPARSE_F16, 0>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp);
+    return sparse ? launch_tile<ESPARSE_BF16, 1>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp)
+                  : launch_tile<ESPARSE_BF16, 0>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp);
   }
 
   // ---- wave-tile kinds

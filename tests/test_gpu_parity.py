@@ -264,6 +264,13 @@ def test_spmm_identity_perm_and_multi_tile(esp, ctx):
     _spmm_case(esp, ctx, 200, 272, 1280, torch.float16, 43)
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+def test_spmm_k_split_over_workgroups(esp, ctx, dtype):
+    # K long enough (64 stages of 64 channels) for the split-K variants to really split; ragged M and N
+    _spmm_case(esp, ctx, 100, 300, 4096, dtype, 49)
+    _spmm_case(esp, ctx, 64, 144, 2304, dtype, 50)
+
+
 def test_spmm_one_hot_reads_back_weights_through_theta(esp, ctx):
     N, K = 48, 256
     rng = np.random.default_rng(3)
