@@ -41,7 +41,7 @@ MEASURED_TRAFFIC = {
     (3, 2048, 13824, 5120): 504618024, (3, 512, 5120, 13824): 220277027, (3, 2048, 5120, 13824): 842458894,
 }
 SPARSE_MFMA_PEAK_TFLOPS = 5000.0   # dense-equivalent flops of the 2:4 MFMA path: twice the dense 16-bit peak of 2.5 PFLOP/s
-DEFAULT_LAYERS = 3
+DEFAULT_LAYERS = {2: 6, 3: 3, 4: 2, 5: 2}   # enough instances that every shape rotates over > 256 MB of weights
 # (name, layer-shape key, calibration / activation stream, products per layer with this shape)
 MATS_LLAMA = [("q", "qkvo", "attn_in"), ("k", "qkvo", "attn_in"), ("v", "qkvo", "attn_in"), ("o", "qkvo", "o_in"),
               ("gate", "gate_up", "mlp_in"), ("up", "gate_up", "mlp_in"), ("down", "down", "down_in")]
@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--config", type=int, default=2, choices=(2, 3, 4, 5),
                     help="workload configuration (default 2, the one the headline metric is quoted on)")
-    ap.add_argument("--layers", type=int, default=DEFAULT_LAYERS, help="distinct layer instances per step")
+    ap.add_argument("--layers", type=int, default=0, help="distinct layer instances per step (0 = the workload's default)")
     ap.add_argument("--counter-probe", action="store_true",
                     help="launch a copy kernel of known size and each product kernel a few times, eagerly, and exit: "
                          "the program to put under rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
@@ -83,7 +83,7 @@ def main():
     ctx = esp.Context(0)
     lib = esp.load_library()
     CFG = args.config
-    LAYERS = args.layers
+    LAYERS = args.layers if args.layers > 0 else DEFAULT_LAYERS[CFG]
     M_LIST = tuple(wl.CONFIGS[CFG]["M"])
     MATS = MATS_OPT if CFG == 5 else MATS_LLAMA
     tdtype = wl.TORCH_DTYPE[wl.CONFIGS[CFG]["dtype"]]
@@ -126,7 +126,7 @@ def main():
             packed = ctx.dense_pack(W)
             if (li == 0 or CFG == 2) and not args.no_cpu_baseline and not args.counter_probe:
                 keep_dense_for_oracle[(li, name)] = (W.cpu(), res.perm.cpu().numpy().astype(np.int64), res.mask.cpu())
-            mats[name] = dict(N=N, K=K, comp=comp, perm=res.perm, packed=packed, W=W, stream=stream)
+            mats[name] = dict(N=N, K=K, comp=comp, perm=res.perm, packed=packed, W=W, stream=stream, score=res.score)
             del res
         del calibs
         layers.append(mats)
@@ -280,26 +280,40 @@ def main():
             Y = outs[(name, M)]
             ctx.stage_activations(X, layers[0][name]["perm"], N, ws)
 
-            def sp(i, M=M, name=name, Y=Y):
-                ctx.spmm_staged(M, layers[i % LAYERS][name]["comp"], ws, Y)
+            # launches rotate over every matrix of this shape in the step (all layer instances), so that the
+            # 256 MB last-level cache cannot hold the weights between uses; "hot" = one matrix over and over
+            pool = [(li, n2) for li in range(LAYERS) for n2, k2, _ in MATS if k2 == skey]
+            P = len(pool)
 
-            def dn(i, M=M, name=name, Y=Y, N=N, K=K):
-                ctx.dense_gemm_staged(M, layers[i % LAYERS][name]["packed"], N, K, ws, Y)
+            def sp(i, M=M, Y=Y, pool=pool, P=P):
+                li, n2 = pool[i % P]
+                ctx.spmm_staged(M, layers[li][n2]["comp"], ws, Y)
 
-            def stage(i, X=X, name=name, N=N):
-                ctx.stage_activations(X, layers[i % LAYERS][name]["perm"], N, ws)
+            def sp_hot(i, M=M, name=name, Y=Y):
+                ctx.spmm_staged(M, layers[0][name]["comp"], ws, Y)
 
-            def lt(i, X=X, name=name, Y=Y):
-                torch.matmul(X, layers[i % LAYERS][name]["W"].t(), out=Y)
+            def dn(i, M=M, Y=Y, N=N, K=K, pool=pool, P=P):
+                li, n2 = pool[i % P]
+                ctx.dense_gemm_staged(M, layers[li][n2]["packed"], N, K, ws, Y)
+
+            def stage(i, X=X, N=N, pool=pool, P=P):
+                li, n2 = pool[i % P]
+                ctx.stage_activations(X, layers[li][n2]["perm"], N, ws)
+
+            def lt(i, X=X, Y=Y, pool=pool, P=P):
+                li, n2 = pool[i % P]
+                torch.matmul(X, layers[li][n2]["W"].t(), out=Y)
 
             reps = 48 if M <= 128 else 12
             ts, td, tg, tl = kernel_time(sp, reps), kernel_time(dn, reps), kernel_time(stage, reps), kernel_time(lt, reps)
+            th = kernel_time(sp_hot, reps)
             bytes_alg = 1.125 * N * K + 2.0 * M * K + 2.0 * M * N
             flops = 2.0 * M * N * K
             mfma_bound = M >= 512
             row = dict(layer=skey, N=N, K=K, M=M, count_per_layer=count, bound="mfma" if mfma_bound else "hbm",
                        kernel=kernel_name(skey, M),
-                       spmm_kernel_us=round(ts * 1e6, 2), dense_kernel_us=round(td * 1e6, 2),
+                       spmm_kernel_us=round(ts * 1e6, 2), spmm_kernel_us_cache_resident=round(th * 1e6, 2),
+                       rotating_weight_mb=round(P * 1.125 * N * K / 1e6, 1), dense_kernel_us=round(td * 1e6, 2),
                        stage_kernel_us=round(tg * 1e6, 2), hipblaslt_dense_us=round(tl * 1e6, 2),
                        eff_tflops=round(flops / (ts + tg) / 1e12, 2),
                        eff_tflops_kernel=round(flops / ts / 1e12, 2),
@@ -379,6 +393,51 @@ def main():
                                    + f"), {t_cpu:.1f} s of CPU time")
         parity = dict(max_row_rel_err=worst, tol=tol, ok=bool(worst <= tol), products_checked=done)
 
+    # ------------------------------------------------------------------ extra: products that share an input, fused
+    # q/k/v read the same hidden state, so do gate/up: pruned as ONE stacked matrix they share one theta (the
+    # permutation belongs to the layer input, Section 3.3), one staging of X and one launch.  Same flops per step.
+    groups = [("qkv", ["q", "k", "v"])] + ([("gate_up", ["gate", "up"])] if CFG != 5 else [])
+    grouped = {n for _, g in groups for n in g}
+    fused_layers = []
+    for li in range(LAYERS):
+        fl_ = {}
+        for gname, members in groups:
+            Wcat = torch.cat([layers[li][n]["W"] for n in members], dim=0)
+            res = ctx.prune(None, Wcat, opts, score=layers[li][members[0]]["score"])
+            fl_[gname] = dict(N=Wcat.shape[0], K=Wcat.shape[1], comp=ctx.compress(Wcat, res.mask, res.perm, canonical=False),
+                              perm=res.perm, packed=ctx.dense_pack(Wcat), stream=layers[li][members[0]]["stream"])
+            del Wcat, res
+        for name, _, _ in MATS:
+            if name not in grouped:
+                fl_[name] = layers[li][name]
+        fused_layers.append(fl_)
+    torch.cuda.empty_cache()
+    f_outs = {(n, M): torch.empty((M, m["N"]), dtype=tdtype, device=dev) for n, m in fused_layers[0].items() for M in M_LIST}
+    for n, m in fused_layers[0].items():
+        for M in M_LIST:
+            ctx.tune(M, m["N"], m["K"], dcode, True)
+            ctx.tune(M, m["N"], m["K"], dcode, False)
+
+    def step_fused_sparse():
+        for fl_ in fused_layers:
+            for M in M_LIST:
+                for n, m in fl_.items():
+                    ctx.spmm(acts[(m["stream"], M)], m["comp"], m["perm"], out=f_outs[(n, M)])
+
+    def step_fused_dense():
+        for fl_ in fused_layers:
+            for M in M_LIST:
+                for n, m in fl_.items():
+                    ctx.dense_gemm(acts[(m["stream"], M)], m["packed"], m["N"], out=f_outs[(n, M)])
+
+    t_fs = timed(capture(step_fused_sparse), args.steps, args.warmup)
+    t_fd = timed(capture(step_fused_dense), args.steps, args.warmup)
+    fused = dict(what="q/k/v" + ("" if CFG == 5 else " and gate/up") + " pruned, compressed and multiplied as one stacked matrix each "
+                      "(one theta, one staging, one launch per group)",
+                 products_per_step=LAYERS * len(fused_layers[0]) * len(M_LIST), ms_per_step=round(t_fs * 1e3, 4),
+                 eff_tflops=round(flops_step / t_fs / 1e12, 3), dense_inrepo_ms_per_step=round(t_fd * 1e3, 4),
+                 speedup_vs_inrepo_dense=round(t_fd / t_fs, 3), speedup_vs_unfused_sparse=round(t_sparse / t_fs, 3))
+
     n_prod = LAYERS * len(MATS) * len(M_LIST)
     out = {
         "metric": "effective TFLOP/s (2 M N K / t) of the 2:4 SpMM at the workload's linear-layer shapes; "
@@ -407,6 +466,7 @@ def main():
                     "compress_ms_per_matrix": round(t_compress / (LAYERS * len(MATS)) * 1e3, 3),
                     "lbs_swaps_per_matrix": swaps_total // (LAYERS * len(MATS))},
         "tuned_variants_sparse_dense": tuned,
+        "fused_shared_input": fused,
         "per_shape": per_shape,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,

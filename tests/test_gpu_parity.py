@@ -271,6 +271,31 @@ def test_spmm_k_split_over_workgroups(esp, ctx, dtype):
     _spmm_case(esp, ctx, 64, 144, 2304, dtype, 50)
 
 
+def test_stacked_matrices_share_one_theta(esp, ctx):
+    """Matrices that read the same input (q/k/v, gate/up) pruned as one stacked matrix: one theta, one mask;
+    the product of the stack is the concatenation of the products of its slices (bitwise: rows are independent)
+    and matches the oracle on the stack."""
+    K, T, M = 256, 128, 20
+    Ws = [_rand((n, K), torch.float16, 60 + i, scale=K ** -0.5) for i, n in enumerate((48, 32, 80))]
+    Wcat = torch.cat(Ws, dim=0)
+    Xc = _rand((T, K), torch.float16, 63, col_scale=wl.channel_scales("lognormal", K, wl.stream_id("st", 1)))
+    X = _rand((M, K), torch.float16, 64)
+    alpha = wl.default_alpha(T)
+    res = ctx.prune(Xc.cuda(), Wcat.cuda(), esp.PruneOpts(block=64, alpha=alpha))
+    theta, mask, s, _ = orc.prune(_np(Xc), _np(Wcat), 2, 4, 64, alpha, 100)
+    assert (res.perm.cpu().numpy() == theta).all() and (res.mask.cpu().numpy() == mask).all()
+    comp = ctx.compress(Wcat.cuda(), res.mask, res.perm, canonical=False)
+    Y = ctx.spmm(X.cuda(), comp, res.perm)
+    assert orc.rowwise_rel_error(_np(Y), orc.spmm_ref(_np(X), _np(Wcat), theta, mask)).max() <= 2e-3
+    lo = 0
+    for W in Ws:
+        n = W.shape[0]
+        part = ctx.compress(W.cuda(), res.mask[lo:lo + n].contiguous(), res.perm, canonical=False)
+        Yp = ctx.spmm(X.cuda(), part, res.perm)
+        assert (_bits(Yp) == _bits(Y[:, lo:lo + n])).all()
+        lo += n
+
+
 def test_spmm_one_hot_reads_back_weights_through_theta(esp, ctx):
     N, K = 48, 256
     rng = np.random.default_rng(3)
