@@ -438,6 +438,28 @@ def main():
                  eff_tflops=round(flops_step / t_fs / 1e12, 3), dense_inrepo_ms_per_step=round(t_fd * 1e3, 4),
                  speedup_vs_inrepo_dense=round(t_fd / t_fs, 3), speedup_vs_unfused_sparse=round(t_sparse / t_fs, 3))
 
+    # ------------------------------------------------------------------ extra: eq. (4) output error for the ablation settings
+    # data-free stand-in for the paper's perplexity ablation (Table 4): relative output error on held-out synthetic
+    # activations and retained metric, first matrix of layer instance 0, for norm / + entropy / + GNS / + LBS
+    ablation = []
+    name0, skey0, stream0 = MATS[0]
+    N0, K0 = shapes[skey0]
+    W0 = layers[0][name0]["W"]
+    calib0 = wl.normal_matrix(T, K0, wl.stream_id("Xc", CFG, stream0, 0),
+                              col_scale=wl.channel_scales(act_law, K0, wl.stream_id("scale", CFG, stream0)), dtype=tdtype, device=dev)
+    Xh = wl.normal_matrix(256, K0, wl.stream_id("Xheld", CFG, stream0),
+                          col_scale=wl.channel_scales(act_law, K0, wl.stream_id("scale", CFG, stream0)), dtype=tdtype, device=dev)
+    Yd0 = ctx.dense_gemm(Xh, layers[0][name0]["packed"], N0)
+    for label, flags in (("norm", esp.USE_NORM), ("norm+entropy", esp.USE_NORM | esp.USE_ENTROPY),
+                         ("norm+entropy+GNS", esp.USE_NORM | esp.USE_ENTROPY | esp.USE_GNS), ("norm+entropy+GNS+LBS", esp.USE_ALL)):
+        o = esp.PruneOpts(n_keep=2, m_group=4, block=wl.CONFIGS[CFG]["block"], bins=100, alpha=alpha, flags=flags)
+        r = ctx.prune(calib0, W0, o, want_retained=True)
+        cmp_ = ctx.compress(W0, r.mask, r.perm, canonical=False)
+        num, den = ctx.output_error(Yd0, ctx.spmm(Xh, cmp_, r.perm))
+        ablation.append(dict(setting=label, rel_output_error=round(num / den, 6), retained_metric=r.retained))
+        del r, cmp_
+    del calib0, Xh, Yd0
+
     n_prod = LAYERS * len(MATS) * len(M_LIST)
     out = {
         "metric": "effective TFLOP/s (2 M N K / t) of the 2:4 SpMM at the workload's linear-layer shapes; "
@@ -467,6 +489,7 @@ def main():
                     "lbs_swaps_per_matrix": swaps_total // (LAYERS * len(MATS))},
         "tuned_variants_sparse_dense": tuned,
         "fused_shared_input": fused,
+        "ablation_eq4": {"matrix": f"{name0} of layer instance 0, 256 held-out tokens", "rows": ablation},
         "per_shape": per_shape,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,

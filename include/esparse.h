@@ -176,6 +176,16 @@ int esparse_tune(esparse_ctx* ctx, long long M, long long N, long long K, espars
 int esparse_tune_save(const esparse_ctx* ctx, const char* path);
 int esparse_tune_load(esparse_ctx* ctx, const char* path);
 
+/* ---- Section 3.3, eq. (4): output error of a pruned layer -------------------------------------
+ * Yref, Y (DEVICE, row-major [M, N], dtype): two outputs of the same activations, normally
+ * esparse_dense_gemm with the unpruned weights and esparse_spmm with the pruned ones.  Writes
+ * (HOST doubles) err_num = || Yref - Y ||_F^2 and err_den = || Yref ||_F^2, accumulated in float64 in
+ * a fixed order (deterministic); eq. (4)'s objective is err_num, its relative form err_num / err_den.
+ * Synchronises the context's stream; allocates a small scratch buffer.  M * N == 0 gives 0, 0.
+ * Errors: ESPARSE_EINVAL (null pointer, negative size, bad dtype), ESPARSE_ENOMEM, ESPARSE_EHIP. */
+int esparse_output_error(esparse_ctx* ctx, const void* Yref, const void* Y, long long M, long long N,
+                         esparse_dtype dtype, double* err_num, double* err_den);
+
 #ifdef __cplusplus
 }
 #endif

@@ -52,6 +52,7 @@ def load_library():
         "esparse_channel_stats": (i32, [vp, vp, ll, ll, i32, i32, vp, vp]),
         "esparse_prune": (i32, [vp, vp, ll, vp, ll, ll, i32, P(_Opts), vp, vp, vp, vp, vp]),
         "esparse_prune_with_scores": (i32, [vp, vp, vp, ll, ll, i32, P(_Opts), vp, vp, vp, vp]),
+        "esparse_output_error": (i32, [vp, vp, vp, ll, ll, i32, vp, vp]),
         "esparse_compressed_size": (i32, [ll, ll, i32, i32, i32, P(sz), P(sz), P(sz)]),
         "esparse_compress": (i32, [vp, vp, vp, vp, ll, ll, i32, i32, i32, vp, vp, vp]),
         "esparse_spmm_workspace": (i32, [ll, ll, ll, P(sz)]),
@@ -77,7 +78,7 @@ def load_library():
 
 
 EXPORTED = ["esparse_create", "esparse_destroy", "esparse_set_stream", "esparse_last_error",
-            "esparse_version", "esparse_channel_stats", "esparse_prune", "esparse_prune_with_scores",
+            "esparse_version", "esparse_channel_stats", "esparse_prune", "esparse_prune_with_scores", "esparse_output_error",
             "esparse_compressed_size", "esparse_compress", "esparse_spmm_workspace", "esparse_spmm",
             "esparse_stage_activations", "esparse_spmm_staged", "esparse_dense_gemm_staged",
             "esparse_spmm_num_variants", "esparse_spmm_variant_name", "esparse_dense_packed_size",
@@ -316,6 +317,17 @@ class Context:
         return Y
 
     # -- Section 4, step 2 --------------------------------------------------------------------
+    # -- Section 3.3 eq. 4 --------------------------------------------------------------------
+    def output_error(self, Yref: torch.Tensor, Y: torch.Tensor):
+        """(|| Yref - Y ||_F^2, || Yref ||_F^2) of two outputs of the same shape."""
+        assert Yref.shape == Y.shape and Yref.dtype == Y.dtype and Yref.is_contiguous() and Y.is_contiguous()
+        M, N = Yref.shape
+        num, den = C.c_double(0.0), C.c_double(0.0)
+        self._sync_stream()
+        self._check(self._lib.esparse_output_error(self._h, _ptr(Yref), _ptr(Y), M, N, _dtype_code(Y),
+                                                   C.cast(C.byref(num), C.c_void_p), C.cast(C.byref(den), C.c_void_p)))
+        return num.value, den.value
+
     def tune(self, M: int, N: int, K: int, dtype: int = F16, sparse: bool = True):
         best, ms = C.c_int(-1), C.c_float(0.0)
         self._sync_stream()

@@ -406,6 +406,21 @@ int esparse_tune(esparse_ctx* ctx, long long M, long long N, long long K, espars
   return ESPARSE_OK;
 }
 
+int esparse_output_error(esparse_ctx* ctx, const void* Yref, const void* Y, long long M, long long N, esparse_dtype dtype,
+                         double* err_num, double* err_den) {
+  if (!ctx) return ESPARSE_EINVAL;
+  int rc = check_dtype(ctx, dtype);
+  if (rc) return rc;
+  ESP_REQUIRE(ctx, err_num && err_den, ESPARSE_EINVAL, "err_num / err_den is null");
+  ESP_REQUIRE(ctx, M >= 0 && N >= 0 && M < (1ll << 31) && N < (1ll << 31), ESPARSE_EINVAL, "M or N out of range");
+  *err_num = 0.0;
+  *err_den = 0.0;
+  if (M == 0 || N == 0) return ESPARSE_OK;
+  ESP_REQUIRE(ctx, Yref && Y, ESPARSE_EINVAL, "Yref / Y is null");
+  ESP_HIP(ctx, hipSetDevice(ctx->device));
+  return esp_output_error_device(ctx, Yref, Y, M * N, dtype, err_num, err_den);
+}
+
 int esparse_tune_save(const esparse_ctx* ctx, const char* path) {
   if (!ctx || !path) return ESPARSE_EINVAL;
   FILE* f = fopen(path, "w");

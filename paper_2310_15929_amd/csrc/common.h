@@ -99,6 +99,10 @@ int esp_compress_device(esparse_ctx* ctx, const void* W, const uint8_t* mask, co
 int esp_dense_pack_device(esparse_ctx* ctx, const void* W, long long N, long long K, int dtype,
                           void* packed);
 // products
+// report (eq. 4)
+int esp_output_error_device(esparse_ctx* ctx, const void* Yref, const void* Y, long long count, int dtype, double* num_out,
+                            double* den_out);
+
 int esp_num_variants();
 const char* esp_variant_name(int v);
 bool esp_variant_applicable(int v, long long M, long long N, long long K, int sparse);

@@ -1,0 +1,71 @@
+// Output-error report of Section 3.3, eq. (4): || Y_ref - Y ||_F^2 and || Y_ref ||_F^2 of two
+// outputs of the same shape (normally the dense and the pruned product of the same activations).
+// Deterministic: every workgroup adds its elements in a fixed tree and writes one partial pair;
+// the host adds the partial pairs in ascending order.
+#include <hip/hip_runtime.h>
+
+#include <vector>
+
+#include "common.h"
+
+namespace {
+
+constexpr int REPORT_WG = 256;
+
+template <int DT>
+__global__ void __launch_bounds__(REPORT_WG) k_sq_diff(const uint16_t* __restrict__ Yref, const uint16_t* __restrict__ Y,
+                                                        long long count, long long per_block, double* __restrict__ partial) {
+  __shared__ double s_num[REPORT_WG];
+  __shared__ double s_den[REPORT_WG];
+  const long long lo = (long long)blockIdx.x * per_block;
+  const long long hi = lo + per_block < count ? lo + per_block : count;
+  double num = 0.0, den = 0.0;
+  for (long long e = lo + threadIdx.x; e < hi; e += REPORT_WG) {
+    const double a = (double)esp_to_float<DT>(Yref[e]);
+    const double d = a - (double)esp_to_float<DT>(Y[e]);
+    num = num + d * d;
+    den = den + a * a;
+  }
+  s_num[threadIdx.x] = num;
+  s_den[threadIdx.x] = den;
+  __syncthreads();
+  for (int w = REPORT_WG / 2; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) {
+      s_num[threadIdx.x] = s_num[threadIdx.x] + s_num[threadIdx.x + w];
+      s_den[threadIdx.x] = s_den[threadIdx.x] + s_den[threadIdx.x + w];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    partial[2 * blockIdx.x] = s_num[0];
+    partial[2 * blockIdx.x + 1] = s_den[0];
+  }
+}
+
+}  // namespace
+
+int esp_output_error_device(esparse_ctx* ctx, const void* Yref, const void* Y, long long count, int dtype, double* num_out,
+                            double* den_out) {
+  const long long per_block = 1 << 16;
+  const long long nblk = (count + per_block - 1) / per_block;
+  DevBuf d_part;
+  if (d_part.alloc((size_t)nblk * 16) != hipSuccess) return esp_fail(ctx, ESPARSE_ENOMEM, "scratch allocation failed");
+  const uint16_t* a = reinterpret_cast<const uint16_t*>(Yref);
+  const uint16_t* b = reinterpret_cast<const uint16_t*>(Y);
+  if (dtype == ESPARSE_F16)
+    hipLaunchKernelGGL(k_sq_diff<ESPARSE_F16>, dim3((unsigned)nblk), dim3(REPORT_WG), 0, ctx->stream, a, b, count, per_block, d_part.as<double>());
+  else
+    hipLaunchKernelGGL(k_sq_diff<ESPARSE_BF16>, dim3((unsigned)nblk), dim3(REPORT_WG), 0, ctx->stream, a, b, count, per_block, d_part.as<double>());
+  ESP_HIP(ctx, hipGetLastError());
+  std::vector<double> h((size_t)nblk * 2);
+  ESP_HIP(ctx, hipMemcpyAsync(h.data(), d_part.p, (size_t)nblk * 16, hipMemcpyDeviceToHost, ctx->stream));
+  ESP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  double num = 0.0, den = 0.0;
+  for (long long i = 0; i < nblk; i++) {
+    num = num + h[2 * i];
+    den = den + h[2 * i + 1];
+  }
+  *num_out = num;
+  *den_out = den;
+  return ESPARSE_OK;
+}

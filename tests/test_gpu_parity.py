@@ -359,3 +359,32 @@ def test_tune_picks_a_variant_and_persists(esp, ctx, tmp_path):
     c2 = esp.Context(0)
     c2.tune_load(p)
     assert esp.variant_name(best) in open(p).read()
+
+
+# ---------------------------------------------------------------- eq. 4 report
+def test_output_error_report_for_the_ablation_settings(esp, ctx):
+    """Relative output error of eq. (4) on held-out activations for the four settings of the paper's ablation
+    (norm; + entropy; + global shuffle; + local block shuffle), device against oracle."""
+    N, K, T, M = 96, 128, 200, 64
+    scales = wl.channel_scales("lognormal", K, wl.stream_id("oe", 1))
+    W = _rand((N, K), torch.float16, 70, scale=K ** -0.5)
+    Xc = _rand((T, K), torch.float16, 71, col_scale=scales)
+    X = _rand((M, K), torch.float16, 72, col_scale=scales)
+    alpha = wl.default_alpha(T)
+    packed = ctx.dense_pack(W.cuda())
+    Yd = ctx.dense_gemm(X.cuda(), packed, N)
+    for flags in (esp.USE_NORM, esp.USE_NORM | esp.USE_ENTROPY, esp.USE_NORM | esp.USE_ENTROPY | esp.USE_GNS, esp.USE_ALL):
+        res = ctx.prune(Xc.cuda(), W.cuda(), esp.PruneOpts(block=32, alpha=alpha, flags=flags))
+        comp = ctx.compress(W.cuda(), res.mask, res.perm, canonical=False)
+        Ys = ctx.spmm(X.cuda(), comp, res.perm)
+        num, den = ctx.output_error(Yd, Ys)
+        # the entry point itself, against float64 numpy on the same two outputs
+        a, b = _np(Yd).astype(np.float64), _np(Ys).astype(np.float64)
+        assert abs(num - ((a - b) ** 2).sum()) <= 1e-12 * num and abs(den - (a ** 2).sum()) <= 1e-12 * den
+        # the report, against the oracle's eq. (4) on exact products (the device outputs are rounded to 16 bits)
+        theta, mask, _, _ = orc.prune(_np(Xc), _np(W), 2, 4, 32, alpha, 100, use_entropy=bool(flags & esp.USE_ENTROPY),
+                                      use_norm=True, use_gns=bool(flags & esp.USE_GNS), use_lbs=bool(flags & esp.USE_LBS))
+        ref = orc.output_error(_np(X), _np(W), theta, mask)
+        assert abs(num / den - ref) <= 1e-2 * ref, (flags, num / den, ref)
+    n0, d0 = ctx.output_error(Yd[:0], Yd[:0])
+    assert (n0, d0) == (0.0, 0.0)

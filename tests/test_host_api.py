@@ -66,6 +66,8 @@ def test_argument_errors_need_no_gpu():
     assert lib.esparse_spmm(ctx._h, None, 0, None, None, 8, 16, 0, 2, 4, None, None, 0, -1) == 0   # M = 0
     assert lib.esparse_channel_stats(ctx._h, None, 4, 16, 0, 100, None, None) == -1
     assert lib.esparse_create(None, 0, None) == -1
+    assert lib.esparse_output_error(ctx._h, None, None, 4, 4, 0, None, None) == -1      # null result pointers
+    assert lib.esparse_output_error(None, None, None, 4, 4, 0, None, None) == -1        # null context
 
 
 def test_tune_table_text_roundtrip(tmp_path):
