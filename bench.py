@@ -460,6 +460,39 @@ def main():
         del r, cmp_
     del calib0, Xh, Yd0
 
+    # ------------------------------------------------------------------ extra: 4:8 against 2:4 at the decode sizes
+    # 4:8 has no matrix instruction: the decode kernel expands the bitmaps in registers and uses the dense one;
+    # same bytes per weight as 2:4, so where the product is bound by reading the weights it runs at the same rate
+    four_eight = []
+    seen48 = set()
+    for name, skey, stream in MATS:
+        if skey in seen48 or not any(M <= 64 for M in M_LIST):
+            continue
+        seen48.add(skey)
+        N, K = shapes[skey]
+        pool = [(li, n2) for li in range(LAYERS) for n2, k2, _ in MATS if k2 == skey]
+        comps48 = []
+        retained48 = None
+        for li, n2 in pool:
+            r = ctx.prune(None, layers[li][n2]["W"], esp.PruneOpts(n_keep=4, m_group=8, block=wl.CONFIGS[CFG]["block"], alpha=alpha),
+                          score=layers[li][n2]["score"], want_retained=retained48 is None)
+            if retained48 is None:
+                retained48 = r.retained
+                r24 = ctx.prune(None, layers[li][n2]["W"], opts, score=layers[li][n2]["score"], want_retained=True).retained
+            comps48.append(ctx.compress(layers[li][n2]["W"], r.mask, r.perm, 4, 8, canonical=False))
+            del r
+        for M in [m_ for m_ in M_LIST if m_ <= 64]:
+            ctx.tune(M, N, K, dcode, 2)
+            Y = outs[(name, M)]
+            ctx.stage_activations(acts[(stream, M)], layers[0][name]["perm"], N, ws)
+            P = len(pool)
+            t48 = kernel_time(lambda i, M=M, Y=Y: ctx.spmm_staged(M, comps48[i % P], ws, Y), 48)
+            t24 = [r_["spmm_kernel_us"] for r_ in per_shape if r_["layer"] == skey and r_["M"] == M][0]
+            four_eight.append(dict(layer=skey, N=N, K=K, M=M, spmm_4_8_kernel_us=round(t48 * 1e6, 2), spmm_2_4_kernel_us=t24,
+                                   retained_metric_4_8_over_2_4=round(retained48 / r24, 5)))
+        del comps48
+    torch.cuda.empty_cache()
+
     n_prod = LAYERS * len(MATS) * len(M_LIST)
     out = {
         "metric": "effective TFLOP/s (2 M N K / t) of the 2:4 SpMM at the workload's linear-layer shapes; "
@@ -489,6 +522,7 @@ def main():
                     "lbs_swaps_per_matrix": swaps_total // (LAYERS * len(MATS))},
         "tuned_variants_sparse_dense": tuned,
         "fused_shared_input": fused,
+        "four_eight_vs_two_four": four_eight,
         "ablation_eq4": {"matrix": f"{name0} of layer instance 0, 256 held-out tokens", "rows": ablation},
         "per_shape": per_shape,
         "roofline": roofline,

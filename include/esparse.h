@@ -104,7 +104,7 @@ int esparse_prune_with_scores(esparse_ctx* ctx, const double* score, const void*
  * Sizes (closed form; 2 bits of index per kept value -> 56.25 % of dense 16-bit for n/m = 1/2):
  *   values_bytes = N*K*n/m * 2,  meta_bytes = N*K/8,
  *   native_bytes = 1.125 * Np * Kp with Np = N rounded up to 16, Kp = K rounded up to 256
- *                  (0 for 4:8, which has no SpMM kernel yet).
+ *                  (2:4 and 4:8 alike: 1 byte of kept values + 1 bit of metadata per weight).
  * Any of the three outputs may be NULL. */
 int esparse_compressed_size(long long N, long long K, int n_keep, int m_group, esparse_dtype dtype,
                             size_t* values_bytes, size_t* meta_bytes, size_t* native_bytes);
@@ -116,10 +116,14 @@ int esparse_compressed_size(long long N, long long K, int n_keep, int m_group, e
  *   meta_out   2:4 -> uint32[N, ceil(K/32)]: field f (f-th kept value of the row) = its position in
  *              its group of 4, at bit 2*(f mod 16) of word f div 16;
  *              4:8 -> uint8[N, K/8]: occupancy bitmap of each group of 8
- *   native_out (2:4 only) the same data in the order the SpMM kernels stream it: unit = (row, 16
- *              re-ordered channels) = 8 kept values (16 B) + one uint16 of indices; values units
- *              ordered [row/16][chunk/4][chunk%4][row%16], then at byte offset Np*Kp the uint16
- *              units ordered [row/16][chunk/16][chunk%4][row%16][(chunk/4)%4]; zero padded.
+ *   native_out the same data in the order the SpMM kernels stream it, zero padded.
+ *              2:4: unit = (row, 16 re-ordered channels) = 8 kept values (16 B) + one uint16 of
+ *              indices; values units ordered [row/16][chunk/4][chunk%4][row%16], then at byte
+ *              offset Np*Kp the uint16 units ordered [row/16][chunk/16][chunk%4][row%16][(chunk/4)%4].
+ *              4:8: the group of row 16 rt + r covering re-ordered channels 64 ks + 32 h + 8 g .. + 8
+ *              belongs to lane 16 g + r: its 4 kept values are half h (8 B) of the 16-byte unit
+ *              (rt * Kp/64 + ks) * 64 + lane, its bitmap byte h of the uint16 unit at the place the
+ *              2:4 form keeps that lane's indices for step ks.
  * Errors: EBADMASK (a group keeping != n, or > n non-zeros with mask NULL), EBADPERM.
  * Synchronises (it reports those two errors). */
 int esparse_compress(esparse_ctx* ctx, const void* W, const uint8_t* mask, const int32_t* perm,
@@ -132,7 +136,12 @@ int esparse_compress(esparse_ctx* ctx, const void* W, const uint8_t* mask, const
  * esparse_compress.  workspace: DEVICE scratch of at least esparse_spmm_workspace bytes,
  * 256-byte aligned; it is overwritten.  variant: -1 = the one chosen by esparse_tune for this shape
  * (a built-in rule if never tuned), >= 0 = a specific kernel variant (EINVAL if out of range).
- * M = 0 is a no-op.  Only n:m = 2:4 (EUNSUPPORTED otherwise).  Does not synchronise. */
+ * M = 0 is a no-op.  n:m = 2:4 runs on the sparse matrix instruction.  n:m = 4:8 (Section 4 lists it as a
+ * format the hardware of the paper cannot multiply; there is no instruction for it here either): the
+ * decode kernels expand each bitmap to a dense operand in registers and use the dense instruction, which
+ * pays where the product is bound by reading the weights; inputs longer than 64 tokens are processed
+ * 64 at a time; only decode-kernel variants apply (EUNSUPPORTED for the others).  Other n:m:
+ * EUNSUPPORTED.  Does not synchronise. */
 int esparse_spmm_workspace(long long M, long long N, long long K, size_t* bytes);
 int esparse_spmm(esparse_ctx* ctx, const void* X, long long M, const void* native_w,
                  const int32_t* perm, long long N, long long K, esparse_dtype dtype, int n_keep,
@@ -167,7 +176,7 @@ int esparse_dense_gemm_staged(esparse_ctx* ctx, long long M, const void* packed_
                               size_t workspace_bytes, int variant);
 
 /* ---- Section 4, step 2: pick and remember the fastest variant for a shape --------------------
- * Times every applicable variant of esparse_spmm (sparse != 0) or esparse_dense_gemm on
+ * Times every applicable variant of esparse_spmm (sparse = 1: 2:4, sparse = 2: 4:8) or esparse_dense_gemm (sparse = 0) on
  * zero-filled scratch operands of shape (M, N, K) and stores the winner in the context; later
  * calls with variant = -1 use it.  best_variant (HOST, optional) receives its id.  The table can be
  * saved to / restored from a text file (HOST path).  Synchronises; allocates scratch. */

@@ -381,6 +381,36 @@ def native_tiling(values: np.ndarray, meta: np.ndarray, N: int, K: int):
     return nv.reshape(-1), nm.reshape(-1)
 
 
+def native_tiling_4_8(values: np.ndarray, meta: np.ndarray, N: int, K: int):
+    """Re-arrangement of the canonical 4:8 arrays into the order the 4:8 product streams.
+
+    A pure index map (documented in include/esparse.h), same size and unit numbering as the
+    2:4 one.  The group of row 16 rt + r that covers re-ordered channels 64 ks + 32 h + 8 g ..
+    + 8 belongs to lane 16 g + r: its 4 kept values (8 bytes) are the half h of the 16-byte
+    value unit (rt * nks + ks) * 64 + lane, its bitmap the byte h of the 16-bit metadata unit
+    ordered [rt][ks // 4][g][r][ks % 4].  Padding (rows to 16, K to 256) is zero.
+    Returns (native_values[Np*Kp/2] of the value dtype, native_meta[Np*Kp/8] uint8).
+    """
+    Np = -(-N // 16) * 16
+    Kp = -(-K // 256) * 256
+    nks = Kp // 64
+    v = np.zeros((Np, Kp // 8, 4), dtype=values.dtype)
+    v.reshape(Np, Kp // 2)[:N, :K // 2] = values
+    mb = np.zeros((Np, Kp // 8), dtype=np.uint8)
+    mb[:N, :K // 8] = np.asarray(meta, dtype=np.uint8).reshape(N, K // 8)
+    nv = np.zeros((Np // 16, nks, 64, 2, 4), dtype=values.dtype)
+    nm = np.zeros((Np // 16, nks // 4, 64, 4, 2), dtype=np.uint8)
+    for row in range(Np):
+        rt, r = divmod(row, 16)
+        for q in range(Kp // 8):
+            ks, rem = divmod(q, 8)
+            h, g = divmod(rem, 4)
+            lane = 16 * g + r
+            nv[rt, ks, lane, h, :] = v[row, q, :]
+            nm[rt, ks // 4, lane, ks % 4, h] = mb[row, q]
+    return nv.reshape(-1), nm.reshape(-1)
+
+
 # --------------------------------------------------------------------------------------
 # Section 4: the products
 # --------------------------------------------------------------------------------------

@@ -255,7 +255,7 @@ class Context:
         dev = W.device
         values = torch.empty((N, K * n_keep // m_group), dtype=W.dtype, device=dev) if canonical else None
         meta = torch.empty(mb, dtype=torch.uint8, device=dev) if canonical else None
-        nat = torch.empty(nb, dtype=torch.uint8, device=dev) if (native and m_group == 4) else None
+        nat = torch.empty(nb, dtype=torch.uint8, device=dev) if native else None
         self._sync_stream()
         self._check(self._lib.esparse_compress(self._h, _ptr(W), _ptr(mask), _ptr(perm), N, K, dt, n_keep, m_group,
                                                _ptr(values), _ptr(meta), _ptr(nat)))
@@ -328,10 +328,11 @@ class Context:
                                                    C.cast(C.byref(num), C.c_void_p), C.cast(C.byref(den), C.c_void_p)))
         return num.value, den.value
 
-    def tune(self, M: int, N: int, K: int, dtype: int = F16, sparse: bool = True):
+    def tune(self, M: int, N: int, K: int, dtype: int = F16, sparse=True):
+        """sparse: False / 0 = dense, True / 1 = 2:4, 2 = 4:8."""
         best, ms = C.c_int(-1), C.c_float(0.0)
         self._sync_stream()
-        self._check(self._lib.esparse_tune(self._h, M, N, K, dtype, 1 if sparse else 0, C.byref(best), C.byref(ms)))
+        self._check(self._lib.esparse_tune(self._h, M, N, K, dtype, int(sparse), C.byref(best), C.byref(ms)))
         return best.value, ms.value
 
     def tune_save(self, path: str):

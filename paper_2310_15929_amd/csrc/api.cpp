@@ -207,12 +207,8 @@ int esparse_compressed_size(long long N, long long K, int n, int m, esparse_dtyp
   if (values_bytes) *values_bytes = (size_t)N * (size_t)(K / m * n) * 2;
   if (meta_bytes) *meta_bytes = (m == 4) ? (size_t)N * (size_t)((K / 2 + 15) / 16) * 4 : (size_t)N * (size_t)(K / 8);
   if (native_bytes) {
-    if (m == 4) {
-      size_t Np = (size_t)esp_round_up(N, 16), Kp = (size_t)esp_round_up(K, 256);
-      *native_bytes = Np * Kp + Np * Kp / 8;
-    } else {
-      *native_bytes = 0;
-    }
+    size_t Np = (size_t)esp_round_up(N, 16), Kp = (size_t)esp_round_up(K, 256);
+    *native_bytes = Np * Kp + Np * Kp / 8;  // both forms: 1 byte of kept values + 1 bit of metadata per weight
   }
   return ESPARSE_OK;
 }
@@ -227,7 +223,6 @@ int esparse_compress(esparse_ctx* ctx, const void* W, const uint8_t* mask, const
   ESP_REQUIRE(ctx, W, ESPARSE_EINVAL, "W is null");
   ESP_REQUIRE(ctx, N >= 0 && N < (1ll << 31) && K >= 0 && K < (1ll << 31), ESPARSE_EINVAL, "N or K out of range");
   ESP_REQUIRE(ctx, K % m == 0, ESPARSE_EINVAL, "K = %lld is not a multiple of m = %d", K, m);
-  ESP_REQUIRE(ctx, !(native_out && m != 4), ESPARSE_EUNSUPPORTED, "native tiling exists for 2:4 only");
   ESP_REQUIRE(ctx, esp_aligned16(W) && esp_aligned16(mask) && esp_aligned16(perm) && esp_aligned16(values_out) &&
                        esp_aligned16(meta_out) && esp_aligned16(native_out),
               ESPARSE_EINVAL, "a pointer is not 16-byte aligned");
@@ -279,14 +274,17 @@ static int spmm_phases(esparse_ctx* ctx, const void* X, long long M, const void*
                        long long N, long long K, esparse_dtype dtype, int n, int m, void* Y, void* workspace,
                        size_t workspace_bytes, int variant, int phases) {
   if (!ctx) return ESPARSE_EINVAL;
-  ESP_REQUIRE(ctx, n == 2 && m == 4, ESPARSE_EUNSUPPORTED, "the sparse product exists for 2:4 only (got %d:%d)", n, m);
-  int rc = check_matmul(ctx, X, M, native_w, N, K, dtype, Y, workspace, workspace_bytes, variant, 1, phases);
+  ESP_REQUIRE(ctx, (n == 2 && m == 4) || (n == 4 && m == 8), ESPARSE_EUNSUPPORTED,
+              "the sparse product exists for 2:4 and 4:8 only (got %d:%d)", n, m);
+  const int mode = m == 4 ? 1 : 2;  // 1: sparse MFMA; 2: bitmaps expanded in registers, dense MFMA
+  int rc = check_matmul(ctx, X, M, native_w, N, K, dtype, Y, workspace, workspace_bytes, variant, mode, phases);
   if (rc) return rc;
+  ESP_REQUIRE(ctx, K % m == 0, ESPARSE_EINVAL, "K = %lld is not a multiple of %d", K, m);
   ESP_REQUIRE(ctx, esp_aligned16(perm), ESPARSE_EINVAL, "perm is not 16-byte aligned");
   if (M == 0) return ESPARSE_OK;
   ESP_HIP(ctx, hipSetDevice(ctx->device));
-  return esp_matmul_device(ctx, 1, X, M, native_w, perm, N, K, dtype, Y, workspace,
-                           pick_variant(ctx, 1, dtype, M, N, K, variant), phases);
+  return esp_matmul_device(ctx, mode, X, M, native_w, perm, N, K, dtype, Y, workspace,
+                           pick_variant(ctx, mode, dtype, M, N, K, variant), phases);
 }
 
 int esparse_spmm(esparse_ctx* ctx, const void* X, long long M, const void* native_w, const int32_t* perm,
@@ -358,7 +356,8 @@ int esparse_tune(esparse_ctx* ctx, long long M, long long N, long long K, espars
   if (rc) return rc;
   ESP_REQUIRE(ctx, M >= 1 && M < (1ll << 24) && N >= 1 && N < (1ll << 31) && K >= 4 && K < (1ll << 31) && K % 4 == 0,
               ESPARSE_EINVAL, "shape out of range");
-  sparse = sparse ? 1 : 0;
+  sparse = sparse == 2 ? 2 : (sparse ? 1 : 0);
+  ESP_REQUIRE(ctx, sparse != 2 || K % 8 == 0, ESPARSE_EINVAL, "K = %lld is not a multiple of 8", K);
   ESP_HIP(ctx, hipSetDevice(ctx->device));
   const size_t Np = (size_t)esp_round_up(N, 16), Kp = (size_t)esp_round_up(K, 256);
   DevBuf w, x, y, ws;

@@ -180,52 +180,71 @@ __global__ void __launch_bounds__(512) k_compress_2_4_rows(const uint16_t* __res
 }
 
 // ---- 4:8 ----------------------------------------------------------------------------------------
-// One thread per (row, group of 8): 4 kept values + one bitmap byte.
+// One thread per (row, group of 8) of the padded matrix: 4 kept values + one bitmap byte.
+// Native form (what the 4:8 product streams; same size and unit numbering as the 2:4 one): the group
+// of row 16 rt + r that covers channels 64 ks + 32 h + 8 g .. + 8 is the A operand of lane 16 g + r of
+// the dense 16x16x32 instruction for half-step h of step ks.  Its 4 kept values (8 bytes) sit at byte
+// 8 h of the 16-byte unit (rt nks + ks) 64 + lane; its bitmap is byte h of the 16-bit word at the place
+// where the 2:4 form keeps that lane's index half for step ks.  Padding rows and channels hold zeros.
 __global__ void __launch_bounds__(256) k_compress_4_8(const uint16_t* __restrict__ W, const uint8_t* __restrict__ mask,
-                                                       const int32_t* __restrict__ perm, long long N, long long K,
-                                                       uint16_t* __restrict__ values, uint8_t* __restrict__ meta,
+                                                       const int32_t* __restrict__ perm, long long N, long long K, long long Np,
+                                                       long long Kp, uint16_t* __restrict__ values, uint8_t* __restrict__ meta,
+                                                       unsigned char* __restrict__ nvalues, uint8_t* __restrict__ nmeta,
                                                        int* __restrict__ flags) {
-  const long long ng = K / 8;
+  const long long ng = K / 8, ngp = Kp / 8;
   long long e = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (e >= N * ng) return;
-  const long long row = e / ng, g = e % ng;
-  uint16_t w[8];
-  uint8_t mk[8];
-  int nz = 0;
-#pragma unroll
-  for (int i = 0; i < 8; i++) {
-    long long p = g * 8 + i;
-    long long c = perm ? perm[p] : p;
-    w[i] = W[row * K + c];
-    mk[i] = mask ? (mask[row * K + p] ? 1 : 0) : ((w[i] & 0x7fffu) ? 1 : 0);
-    nz += mk[i];
-  }
-  if (!mask) {
-    if (nz > 4) atomicOr(flags, 1);
-#pragma unroll
-    for (int i = 0; i < 8; i++)
-      if (nz < 4 && !mk[i]) {
-        mk[i] = 1;
-        nz++;
-      }
-  }
-  if (nz != 4) atomicOr(flags, 1);
+  if (e >= Np * ngp) return;
+  const long long row = e / ngp, g = e % ngp;
   uint16_t kept[4] = {0, 0, 0, 0};
   uint32_t bm = 0;
-  int nk = 0;
+  if (row < N && g < ng) {
+    uint16_t w[8];
+    uint8_t mk[8];
+    int nz = 0;
 #pragma unroll
-  for (int i = 0; i < 8; i++)
-    if (mk[i] && nk < 4) {
-      kept[nk++] = w[i];
-      bm |= 1u << i;
+    for (int i = 0; i < 8; i++) {
+      long long p = g * 8 + i;
+      long long c = perm ? perm[p] : p;
+      w[i] = W[row * K + c];
+      mk[i] = mask ? (mask[row * K + p] ? 1 : 0) : ((w[i] & 0x7fffu) ? 1 : 0);
+      nz += mk[i];
     }
-  if (values) {
+    if (!mask) {
+      if (nz > 4) atomicOr(flags, 1);
+#pragma unroll
+      for (int i = 0; i < 8; i++)
+        if (nz < 4 && !mk[i]) {
+          mk[i] = 1;
+          nz++;
+        }
+    }
+    if (nz != 4) atomicOr(flags, 1);
+    int nk = 0;
+#pragma unroll
+    for (int i = 0; i < 8; i++)
+      if (mk[i] && nk < 4) {
+        kept[nk++] = w[i];
+        bm |= 1u << i;
+      }
+    if (values) {
+      uint2 v;
+      v.x = kept[0] | ((uint32_t)kept[1] << 16);
+      v.y = kept[2] | ((uint32_t)kept[3] << 16);
+      *reinterpret_cast<uint2*>(values + row * (K / 2) + g * 4) = v;
+    }
+    if (meta) meta[row * ng + g] = (uint8_t)bm;
+  }
+  if (nvalues) {
+    const long long nks = Kp / 64;
+    const long long rt = row >> 4, ks = g >> 3;
+    const int r = (int)(row & 15), h = (int)((g >> 2) & 1), gg = (int)(g & 3);
+    const int lane = gg * 16 + r;
     uint2 v;
     v.x = kept[0] | ((uint32_t)kept[1] << 16);
     v.y = kept[2] | ((uint32_t)kept[3] << 16);
-    *reinterpret_cast<uint2*>(values + row * (K / 2) + g * 4) = v;
+    *reinterpret_cast<uint2*>(nvalues + ((rt * nks + ks) * 64 + lane) * 16 + 8 * h) = v;
+    nmeta[(((rt * (nks / 4) + ks / 4) * 64 + lane) * 4 + (ks & 3)) * 2 + h] = (uint8_t)bm;
   }
-  if (meta) meta[row * ng + g] = (uint8_t)bm;
 }
 
 int esp_compress_device(esparse_ctx* ctx, const void* Wv, const uint8_t* mask, const int32_t* perm, long long N,
@@ -268,9 +287,13 @@ int esp_compress_device(esparse_ctx* ctx, const void* Wv, const uint8_t* mask, c
                          reinterpret_cast<uint16_t*>(values_out), reinterpret_cast<uint32_t*>(meta_out), nvalues, nmeta, flags);
     }
   } else {
-    const long long groups = N * (K / 8);
-    hipLaunchKernelGGL(k_compress_4_8, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, W, mask, perm, N, K,
-                       reinterpret_cast<uint16_t*>(values_out), reinterpret_cast<uint8_t*>(meta_out), flags);
+    const long long Np = native_out ? esp_round_up(N, 16) : N;
+    const long long Kp = native_out ? esp_round_up(K, 256) : K;
+    const long long groups = Np * (Kp / 8);
+    unsigned char* nvalues = reinterpret_cast<unsigned char*>(native_out);
+    uint8_t* nmeta = native_out ? reinterpret_cast<uint8_t*>(native_out) + (size_t)Np * Kp : nullptr;
+    hipLaunchKernelGGL(k_compress_4_8, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, W, mask, perm, N, K, Np, Kp,
+                       reinterpret_cast<uint16_t*>(values_out), reinterpret_cast<uint8_t*>(meta_out), nvalues, nmeta, flags);
   }
   ESP_HIP(ctx, hipGetLastError());
   int h = 0;

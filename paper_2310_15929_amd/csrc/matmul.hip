@@ -87,6 +87,18 @@ __device__ __forceinline__ floatx4_t smfmac16(uint4 a, uint4 b0, uint4 b1, float
   }
 }
 
+// byte permute: byte i of the result is byte sel[i] of {hi, lo} (0-3: lo, 4-7: hi) or 0x00 for sel[i] = 0x0c
+__device__ __forceinline__ uint32_t byte_perm(uint32_t hi, uint32_t lo, uint32_t sel) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_amdgcn_perm(hi, lo, sel);
+#else
+  (void)hi;
+  (void)lo;
+  (void)sel;
+  return 0;
+#endif
+}
+
 template <int DT>
 __device__ __forceinline__ floatx4_t mfma16(uint4 a, uint4 b, floatx4_t c) {
   if (DT == ESPARSE_F16) {
@@ -357,7 +369,27 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(const uint4* __restrict__
                                                         const uint4* __restrict__ Xf, uint16_t* __restrict__ Y, long long M,
                                                         long long N, long long Mp, long long Np, long long Kp) {
   extern __shared__ floatx4_t s_red[];  // [NW][RT * MT][64]
+  // SPARSE == 2 (4:8): byte-permute selectors that spread a group's 4 kept values over its 8 positions,
+  // one 16-byte entry per bitmap: output half e takes value number popcount(bitmap below bit e) if
+  // bit e is set and 0 otherwise (selector byte 0x0c yields 0x00)
+  __shared__ uint4 s_lut[SPARSE == 2 ? 256 : 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (SPARSE == 2) {
+    if (tid < 256) {
+      uint32_t sel[4] = {0x0c0c0c0cu, 0x0c0c0c0cu, 0x0c0c0c0cu, 0x0c0c0c0cu};
+#pragma unroll
+      for (int e = 0; e < 8; e++)
+        if ((tid >> e) & 1) {
+          const uint32_t r = (uint32_t)__builtin_popcount(tid & ((1 << e) - 1));
+          if (r < 4) {
+            const int sh = 16 * (e & 1);
+            sel[e >> 1] = (sel[e >> 1] & ~(0xffffu << sh)) | (((2u * r) | ((2u * r + 1u) << 8)) << sh);
+          }
+        }
+      s_lut[tid] = uint4{sel[0], sel[1], sel[2], sel[3]};
+    }
+    __syncthreads();
+  }
   const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
   const long long rt0 = (long long)blockIdx.x * RT;
   long long rts[RT];
@@ -380,7 +412,7 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(const uint4* __restrict__
     for (int u = 0; u < 2; u++) {
 #pragma unroll
       for (int i = 0; i < RT; i++) {
-        if (SPARSE) {
+        if (SPARSE) {  // 2:4: kept values + index half; 4:8: kept values of two groups + their two bitmaps
           a[u][i] = A[(rts[i] * nks + kk[u]) * 64 + lane];
           idx[u][i] = (int)meta16[((rts[i] * (nks / 4) + kk[u] / 4) * 64 + lane) * 4 + (kk[u] & 3)];
         } else {
@@ -395,6 +427,19 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(const uint4* __restrict__
         b1[u][j] = Xf[(tt * (2 * nks) + 2 * kk[u] + 1) * 64 + lane];
       }
     }
+    if (SPARSE == 2) {
+#pragma unroll
+      for (int u = 0; u < 2; u++)
+#pragma unroll
+        for (int i = 0; i < RT; i++) {
+          const uint4 v = a[u][i];
+          const uint4 s0 = s_lut[idx[u][i] & 0xff], s1 = s_lut[(idx[u][i] >> 8) & 0xff];
+          a[u][i] = uint4{byte_perm(v.y, v.x, s0.x), byte_perm(v.y, v.x, s0.y),
+                          byte_perm(v.y, v.x, s0.z), byte_perm(v.y, v.x, s0.w)};
+          a2[u][i] = uint4{byte_perm(v.w, v.z, s1.x), byte_perm(v.w, v.z, s1.y),
+                           byte_perm(v.w, v.z, s1.z), byte_perm(v.w, v.z, s1.w)};
+        }
+    }
 #pragma unroll
     for (int u = 0; u < 2; u++) {
       if (u == 1 && !second) break;
@@ -402,7 +447,7 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(const uint4* __restrict__
       for (int i = 0; i < RT; i++)
 #pragma unroll
         for (int j = 0; j < MT; j++) {
-          if (SPARSE) {
+          if (SPARSE == 1) {
             acc[i][j] = smfmac16<DT, 0>(a[u][i], b0[u][j], b1[u][j], acc[i][j], idx[u][i]);
           } else {
             acc[i][j] = mfma16<DT>(a[u][i], b0[u][j], acc[i][j]);
@@ -741,9 +786,15 @@ const char* esp_variant_name(int v) { return kVariants[v].name; }
 bool esp_variant_applicable(int v, long long M, long long N, long long K, int sparse) {
   (void)N;
   (void)K;
-  (void)sparse;
   if (v < 0 || v >= kNumVariants) return false;
   const Variant& var = kVariants[v];
+  if (sparse == 2) {
+    // 4:8: decode kernels only; longer inputs go through them 64 tokens at a time
+    if (var.kind != KIND_KSPLIT) return false;
+    const long long mc = M < 64 ? M : 64;
+    const long long mt = mc <= 16 ? 1 : (mc <= 32 ? 2 : 4);
+    return (long long)var.nw * var.rt * mt * 1024 <= 160 * 1024;
+  }
   if (var.split_mode == 1 && M > 128) return false;  // partial buffers are sized for M <= 128 only
   if (var.kind == KIND_KSPLIT) {
     if (M > 64) return false;
@@ -756,7 +807,7 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
 
 int esp_default_variant(long long M, long long N, long long K, int sparse) {
   (void)K;
-  if (M <= 32) {
+  if (M <= 32 || sparse == 2) {
     const long long nrt = esp_round_up(N, 16) / 16;
     return nrt <= 320 ? 4 : 5;  // ksplit_w16_r1 / ksplit_w16_r2
   }
@@ -920,17 +971,24 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
 
   if (v.kind == KIND_KSPLIT) {
     const uint16_t* meta16 = reinterpret_cast<const uint16_t*>(meta_bytes);
-#define ESP_KSPLIT(DTv, SPv)                                                                  \
-  do {                                                                                        \
-    if (ntt == 1) launch_ksplit<DTv, SPv, 1>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);      \
-    else if (ntt == 2) launch_ksplit<DTv, SPv, 2>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp); \
-    else launch_ksplit<DTv, SPv, 4>(v, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp);               \
+#define ESP_KSPLIT(DTv, SPv)                                                                                   \
+  do {                                                                                                         \
+    for (long long t0 = 0; t0 < M; t0 += 64) { /* more than 64 tokens (4:8 only): 64 at a time */             \
+      const long long mc = (M - t0) < 64 ? (M - t0) : 64, mcp = esp_round_up(mc, 16);                          \
+      const uint4* xf = Xf + (t0 / 16) * (2 * nks) * 64;                                                       \
+      uint16_t* y = Y + t0 * N;                                                                                \
+      if (mcp == 16) launch_ksplit<DTv, SPv, 1>(v, st, A, meta16, xf, y, mc, N, mcp, Np, Kp);                  \
+      else if (mcp == 32) launch_ksplit<DTv, SPv, 2>(v, st, A, meta16, xf, y, mc, N, mcp, Np, Kp);             \
+      else launch_ksplit<DTv, SPv, 4>(v, st, A, meta16, xf, y, mc, N, mcp, Np, Kp);                            \
+    }                                                                                                          \
   } while (0)
     if (dtype == ESPARSE_F16) {
-      if (sparse) ESP_KSPLIT(ESPARSE_F16, 1);
+      if (sparse == 2) ESP_KSPLIT(ESPARSE_F16, 2);
+      else if (sparse) ESP_KSPLIT(ESPARSE_F16, 1);
       else ESP_KSPLIT(ESPARSE_F16, 0);
     } else {
-      if (sparse) ESP_KSPLIT(ESPARSE_BF16, 1);
+      if (sparse == 2) ESP_KSPLIT(ESPARSE_BF16, 2);
+      else if (sparse) ESP_KSPLIT(ESPARSE_BF16, 1);
       else ESP_KSPLIT(ESPARSE_BF16, 0);
     }
 #undef ESP_KSPLIT

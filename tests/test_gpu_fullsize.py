@@ -207,7 +207,7 @@ def test_config5_block_size_sweep_and_4_8(esp, ctx):
             assert res.retained >= base.retained
             mask_rows = orc.nm_mask_vectorised(Wf[rows], s, theta, n, m)
             assert (res.mask[rows_t].cpu().numpy() == mask_rows).all()
-            comp = ctx.compress(W, res.mask, res.perm, n, m, native=(m == 4))
+            comp = ctx.compress(W, res.mask, res.perm, n, m)
             values, meta = orc.compress_vectorised(_bits(W[rows_t]).reshape(rows.size, K), theta, mask_rows, n, m)
             assert (_bits(comp.values[rows_t]).reshape(values.shape) == values).all()
             got = comp.meta.view(N, -1)[rows_t].cpu().numpy()
@@ -216,6 +216,17 @@ def test_config5_block_size_sweep_and_4_8(esp, ctx):
             vb, mb, _ = esp.compressed_size(N, K, n, m)
             assert (vb, mb) == orc.compressed_bytes(N, K, n, m) and mb * 8 == N * K      # 1 bit of metadata per weight
             retained[(n, m, B)] = res.retained
+            if B == 64:
+                # the product at the decode sizes of the configuration, sampled tokens x sampled output features
+                feat = np.sort(rng.choice(N, 512, replace=False))
+                mask_feat = orc.nm_mask_vectorised(Wf[feat], s, theta, n, m)
+                for M in (1, 64):
+                    X = wl.activations(cfg, layer, M, device="cuda")
+                    Y = ctx.spmm(X, comp, res.perm)
+                    tok = np.sort(rng.choice(M, min(M, 4), replace=False))
+                    Yref = orc.spmm_ref(_np(X)[tok], Wf[feat], theta, mask_feat)
+                    err = orc.rowwise_rel_error(_np(Y)[tok][:, feat], Yref)
+                    assert err.max() <= 2e-3, (n, m, M, err.max())
             _log(f"{n}:{m} B={B}: {int(res.swaps.sum())} swaps, retained {res.retained:.8g}", t0)
     print("retained metric by (n, m, B):", retained, flush=True)
 

@@ -194,7 +194,10 @@ def test_compress_4_8_and_derived_mask_and_errors(esp, ctx):
     values, meta = orc.compress_vectorised(_bits(W).reshape(N, K), theta, mask, 4, 8)
     assert (_bits(comp.values).reshape(values.shape) == values).all()
     assert (comp.meta.cpu().numpy().reshape(meta.shape) == meta).all()
-    assert comp.native is None
+    nv, nm = orc.native_tiling_4_8(values, meta, N, K)
+    nat = comp.native.cpu().numpy()
+    assert nat.size == esp.compressed_size(N, K, 4, 8)[2] == nv.nbytes + nm.nbytes
+    assert (nat[:nv.nbytes].view(np.uint16) == nv).all() and (nat[nv.nbytes:] == nm).all()
     # mask = NULL: the mask is read off the zeros of an already pruned weight
     for n, m in ((2, 4), (4, 8)):
         mk = orc.nm_mask_vectorised(_np(W), s, theta, n, m)
@@ -388,3 +391,49 @@ def test_output_error_report_for_the_ablation_settings(esp, ctx):
         assert abs(num / den - ref) <= 1e-2 * ref, (flags, num / den, ref)
     n0, d0 = ctx.output_error(Yd[:0], Yd[:0])
     assert (n0, d0) == (0.0, 0.0)
+
+
+# ---------------------------------------------------------------- 4:8 product (bitmaps expanded in registers)
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("M,N,K", [(1, 72, 576), (8, 40, 256), (33, 72, 576), (64, 144, 2304), (150, 48, 512)])
+def test_spmm_4_8(esp, ctx, M, N, K, dtype):
+    rng = np.random.default_rng(M * N + K)
+    scales = wl.channel_scales("lognormal", K, wl.stream_id("x48", M))
+    W = _rand((N, K), dtype, 80, scale=K ** -0.5)
+    X = _rand((M, K), dtype, 81, col_scale=scales)
+    s = np.abs(rng.standard_normal(K)) + 0.1
+    theta = rng.permutation(K)
+    mask = orc.nm_mask_vectorised(_np(W), s, theta, 4, 8)
+    th = torch.tensor(theta, dtype=torch.int32).cuda()
+    comp = ctx.compress(W.cuda(), torch.tensor(mask).cuda(), th, 4, 8)
+    values, meta = orc.compress_vectorised(_bits(W).reshape(N, K), theta, mask, 4, 8)
+    nv, nm = orc.native_tiling_4_8(values, meta, N, K)
+    nat = comp.native.cpu().numpy()
+    assert (nat[:nv.nbytes].view(np.uint16) == nv).all() and (nat[nv.nbytes:] == nm).all()
+    Yref = orc.spmm_ref(_np(X), _np(W), theta, mask)
+    ran = 0
+    for v in [-1] + list(range(esp.num_variants())):
+        print(f"4:8 spmm M={M} N={N} K={K} {dtype} variant={v}", flush=True)
+        try:
+            Y = ctx.spmm(X.cuda(), comp, th, variant=v)
+        except esp.EsparseError as e:
+            assert e.code == -2 and v >= 0          # not a decode kernel, or its partial tiles do not fit the LDS at this M
+            continue
+        torch.cuda.synchronize()
+        err = orc.rowwise_rel_error(_np(Y), Yref)
+        assert err.max() <= TOL[dtype], (v, err.max())
+        ran += 1
+    assert ran >= 3
+
+
+def test_spmm_4_8_one_hot_reads_back_weights(esp, ctx):
+    N, K = 32, 256
+    rng = np.random.default_rng(48)
+    W = _rand((N, K), torch.float16, 82)
+    s = np.abs(rng.standard_normal(K)) + 0.1
+    theta = rng.permutation(K)
+    mask = orc.nm_mask_vectorised(_np(W), s, theta, 4, 8)
+    th = torch.tensor(theta, dtype=torch.int32).cuda()
+    comp = ctx.compress(W.cuda(), torch.tensor(mask).cuda(), th, 4, 8, canonical=False)
+    Y = ctx.spmm(torch.eye(K, dtype=torch.float16).cuda(), comp, th)         # [K, N]: row c = masked W[:, c]
+    assert (_np(Y) == (_np(W) * orc.mask_to_original_order(mask, theta)).T).all()

@@ -32,7 +32,8 @@ def test_size_queries_closed_form():
         Np, Kp = -(-N // 16) * 16, -(-K // 256) * 256
         assert nb == Np * Kp * 9 // 8
         vb8, mb8, nb8 = esp.compressed_size(N, K - K % 8, 4, 8)
-        assert vb8 == N * (K - K % 8) and mb8 == N * (K - K % 8) // 8 and nb8 == 0
+        Kp8 = -(-(K - K % 8) // 256) * 256
+        assert vb8 == N * (K - K % 8) and mb8 == N * (K - K % 8) // 8 and nb8 == Np * Kp8 * 9 // 8
     vb, mb, _ = esp.compressed_size(4096, 4096, 2, 4)
     assert (vb + mb) / (2 * 4096 * 4096) == 0.5625
     assert esp.dense_packed_size(24, 320) == 32 * 512 * 2
@@ -60,7 +61,8 @@ def test_argument_errors_need_no_gpu():
     assert code(lambda: ctx.prune(Xc, W, esp.PruneOpts(block=8, flags=esp.USE_GNS))) == -1
     assert code(lambda: ctx.prune(Xc, W, esp.PruneOpts(block=8, max_swaps=-1))) == -1
     lib = esp.load_library()
-    assert lib.esparse_spmm(ctx._h, None, 4, None, None, 8, 16, 0, 4, 8, None, None, 0, -1) == -2
+    assert lib.esparse_spmm(ctx._h, None, 4, None, None, 8, 16, 0, 1, 4, None, None, 0, -1) == -2   # no 1:4 product
+    assert lib.esparse_spmm(ctx._h, None, 4, None, None, 8, 16, 0, 4, 8, None, None, 0, -1) == -1   # 4:8: null pointers
     assert lib.esparse_spmm(ctx._h, None, 4, None, None, 8, 16, 0, 2, 4, None, None, 0, -1) == -1
     assert b"null" in lib.esparse_last_error(ctx._h)
     assert lib.esparse_spmm(ctx._h, None, 0, None, None, 8, 16, 0, 2, 4, None, None, 0, -1) == 0   # M = 0

@@ -338,6 +338,43 @@ def test_native_tiling_is_bijection_and_matches_instruction_layout():
     assert np.allclose(Y, orc.spmm_ref(X, W, theta, mk), rtol=1e-12, atol=1e-12)
 
 
+def test_native_tiling_4_8_is_bijection_and_matches_dense_instruction_layout():
+    """The 4:8 native form, expanded the way the kernel does it (value number = popcount of the bitmap below the
+    position) and multiplied with the measured operand layout of the dense 16x16x32 instruction (A lane l: row
+    l % 16, channels 8 (l // 16) .. + 8), gives the plain masked product."""
+    N, K, M = 24, 320, 3
+    W = _f16(RNG.standard_normal((N, K)))
+    s = np.abs(RNG.standard_normal(K)) + 0.1
+    theta = RNG.permutation(K)
+    mk = orc.nm_mask(W, s, theta, 4, 8)
+    values, meta = orc.compress(W, theta, mk, 4, 8)
+    tags = (np.arange(values.size, dtype=np.uint16) + 1).view(np.float16).reshape(values.shape)
+    nv_t, _ = orc.native_tiling_4_8(tags, meta, N, K)
+    got = np.sort(nv_t.view(np.uint16)[nv_t.view(np.uint16) != 0])
+    assert (got == np.arange(1, values.size + 1)).all()             # each value exactly once
+    nv, nm = orc.native_tiling_4_8(values, meta, N, K)
+    Np, Kp = 32, 512
+    assert nv.nbytes + nm.nbytes == 1.125 * Np * Kp
+    nks = Kp // 64
+    vals = nv.reshape(Np // 16, nks, 64, 2, 4).astype(np.float64)
+    maps = nm.reshape(Np // 16, nks // 4, 64, 4, 2)
+    Xp = np.zeros((M, Kp))
+    X = _f16(RNG.standard_normal((M, K)))
+    Xp[:, :K] = X.astype(np.float64)[:, theta]
+    Y = np.zeros((M, Np))
+    for rt in range(Np // 16):
+        for ks in range(nks):
+            for lane in range(64):
+                r, g = lane % 16, lane // 16
+                for h in range(2):
+                    bm = int(maps[rt, ks // 4, lane, ks % 4, h])
+                    for e in range(8):
+                        if (bm >> e) & 1:
+                            rank = bin(bm & ((1 << e) - 1)).count("1")
+                            Y[:, 16 * rt + r] += vals[rt, ks, lane, h, rank] * Xp[:, 64 * ks + 32 * h + 8 * g + e]
+    assert np.allclose(Y[:, :N], orc.spmm_ref(X, W, theta, mk), rtol=1e-12, atol=1e-12)
+
+
 # ---------------------------------------------------------------- products
 def test_spmm_ref_definition_on_tiny_inputs():
     N, K, M = 6, 16, 4
