@@ -175,13 +175,24 @@ def _top_n_sum_rows(xi_cols: np.ndarray, n: int) -> np.ndarray:
     return t
 
 
+ROW_SUM_LANES = 16
+
+
 def group_value(xi_cols: np.ndarray, n: int) -> float:
-    """v(g) = sum over rows j = 0..N-1 (in that order, float64) of the row's retained
-    metric in the group: the contribution of one group of m channels to eq. (5)."""
+    """v(g) = sum over the output rows of the row's retained metric in the group: the
+    contribution of one group of m channels to eq. (5).
+
+    Reading (the paper does not fix the order of this sum; float64 addition is not
+    associative, so one must be fixed): 16 interleaved sub-sums - sub-sum l adds the rows
+    j = l, l + 16, l + 32, ... in ascending order - which are then added in ascending l.
+    """
     t = _top_n_sum_rows(np.asarray(xi_cols, dtype=np.float64), n)
-    acc = 0.0
+    lanes = [0.0] * ROW_SUM_LANES
     for j in range(t.shape[0]):
-        acc = acc + float(t[j])
+        lanes[j % ROW_SUM_LANES] = lanes[j % ROW_SUM_LANES] + float(t[j])
+    acc = lanes[0]
+    for l in range(1, ROW_SUM_LANES):
+        acc = acc + lanes[l]
     return acc
 
 
@@ -472,10 +483,21 @@ def prune(Xc: np.ndarray, W: np.ndarray, n: int, m: int, B: int, alpha: float, b
 # --------------------------------------------------------------------------------------
 
 def _seq_sum_rows(t: np.ndarray) -> np.ndarray:
-    """Sum over axis 0 in the order j = 0, 1, ..., N-1 (float64), for every column."""
-    acc = np.zeros(t.shape[1:], dtype=np.float64)
-    for j in range(t.shape[0]):
-        acc = acc + t[j]
+    """Sum over axis 0 in the order of `group_value` (16 interleaved sub-sums added in
+    ascending order), for every column.  Rows are padded with +0.0, which changes no sum of
+    non-negative terms."""
+    L = ROW_SUM_LANES
+    N = t.shape[0]
+    pad = (-N) % L
+    if pad:
+        t = np.concatenate([t, np.zeros((pad,) + t.shape[1:], dtype=np.float64)], axis=0)
+    r = t.reshape((t.shape[0] // L, L) + t.shape[1:])
+    lanes = np.zeros(r.shape[1:], dtype=np.float64)
+    for q in range(r.shape[0]):
+        lanes = lanes + r[q]
+    acc = lanes[0]
+    for l in range(1, L):
+        acc = acc + lanes[l]
     return acc
 
 

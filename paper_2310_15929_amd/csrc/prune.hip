@@ -310,31 +310,51 @@ __device__ __forceinline__ double top_n_sum(double* v) {
   return t;
 }
 
+// Order of every sum over output rows (eq. 5): ROW_LANES = 16 interleaved sub-sums - sub-sum l adds the
+// rows j = l, l + 16, l + 32, ... in ascending order - which are then added in ascending l.  A fixed
+// order that 16 lanes can work on at once; the lanes of one sum are 16 neighbouring lanes of a wave.
+#define ROW_LANES 16
+
+__device__ __forceinline__ double lanes_total(double part) {
+  // lane 0 of each group of 16 neighbouring lanes gets ((part_0 + part_1) + part_2) + ... + part_15
+  double acc = __shfl(part, 0, ROW_LANES);
+#pragma unroll
+  for (int l = 1; l < ROW_LANES; l++) acc = acc + __shfl(part, l, ROW_LANES);
+  return acc;
+}
+
 // V[blk][g][i][x] = retained metric of group g of block blk with its i-th member replaced by panel
-// column x of the block (x == the member itself gives v(g)); rows summed in order by one thread.
-// grid (entries / 256, blocks), block 256.  `groups` = list of 2 group numbers per block to refresh
-// (or NULL = all groups).  Entries whose x sits in group g (other than the member itself) are skipped.
+// column x of the block (x == the member itself gives v(g)).  grid (entries / 64, blocks), block 1024 =
+// 64 entries x 16 row lanes.  `groups` = list of 2 group numbers per block to refresh (or NULL = all
+// groups).  Entries whose x sits in group g (other than the member itself) are skipped.
+// The block's metric values go through LDS in chunks of rows_chunk rows (a multiple of 16; rows are
+// padded by one value so that the 16 row lanes of an entry read different banks); the panel values of
+// the next chunk are loaded into registers before the current chunk is evaluated.
 template <int DT, int NKEEP, int MG>
-__global__ void __launch_bounds__(256) k_lbs_eval(const uint16_t* __restrict__ P, const double* __restrict__ sp /*[K] score in panel order*/,
-                                                   const int* __restrict__ lp /*[nblk][B] position -> panel column*/,
-                                                   const int* __restrict__ groups /*[nblk][2] or null*/,
-                                                   const int* __restrict__ done /*[nblk]*/, long long N, long long K, int B,
-                                                   int rows_chunk, double* __restrict__ V /*[nblk][G][MG][B]*/) {
+__global__ void __launch_bounds__(1024) k_lbs_eval(const uint16_t* __restrict__ P, const double* __restrict__ sp /*[K] score in panel order*/,
+                                                    const int* __restrict__ lp /*[nblk][B] position -> panel column*/,
+                                                    const int* __restrict__ groups /*[nblk][2] or null*/,
+                                                    const int* __restrict__ done /*[nblk]*/, long long N, long long K, int B,
+                                                    int rows_chunk, double* __restrict__ V /*[nblk][G][MG][B]*/) {
   extern __shared__ unsigned char smem_raw[];
-  double* s_xi = reinterpret_cast<double*>(smem_raw);  // [rows_chunk][B]
-  __shared__ int s_lp[256];
+  double* s_xi = reinterpret_cast<double*>(smem_raw);  // [rows_chunk][B + 1]
+  __shared__ int s_lp[1024];
   const int blk = blockIdx.y;
   if (done[blk]) return;
   const int G = B / MG;
   const int tid = threadIdx.x;
-  const int eid = blockIdx.x * 256 + tid;  // entry within this block's refresh list
+  const int rl = tid & (ROW_LANES - 1);                  // row lane
+  const int eid = blockIdx.x * 64 + (tid >> 4);          // entry within this block's refresh list
   const int per_group = MG * B;
   const int ngroups = groups ? 2 : G;
-  for (int i = tid; i < B; i += 256) s_lp[i] = lp[blk * B + i];
+  const int stride = B + 1;
+  for (int i = tid; i < B; i += 1024) s_lp[i] = lp[blk * B + i];
   __syncthreads();
   bool active = eid < ngroups * per_group;
   int g = 0, i = 0, x = 0;
   int cols[MG];
+#pragma unroll
+  for (int k = 0; k < MG; k++) cols[k] = 0;
   if (active) {
     int gsel = eid / per_group;
     g = groups ? groups[blk * 2 + gsel] : gsel;
@@ -354,25 +374,166 @@ __global__ void __launch_bounds__(256) k_lbs_eval(const uint16_t* __restrict__ P
   }
   const uint16_t* Pb = P + (long long)blk * B;
   const double* spb = sp + (long long)blk * B;
-  double acc = 0.0;
+  // this thread's share of a chunk: values tid, tid + 1024, ... of the rows_chunk x B values (the same
+  // places in every chunk)
+  constexpr int EPT = 4;
+  const int elems = rows_chunk * B;  // <= EPT * 1024: the host picks rows_chunk <= 4096 / B (B <= 256)
+  uint16_t nextv[EPT];
+  int rq[EPT], cq[EPT];
+  double sq[EPT];
+#pragma unroll
+  for (int q = 0; q < EPT; q++) {
+    const int e = tid + 1024 * q;
+    rq[q] = e < elems ? e / B : rows_chunk;  // rows_chunk = "no such value"
+    cq[q] = e % B;
+    sq[q] = spb[cq[q]];
+  }
+  auto fetch = [&](long long r0) {
+    const int nr = (int)((N - r0) < rows_chunk ? (N - r0) : rows_chunk);
+#pragma unroll
+    for (int q = 0; q < EPT; q++) nextv[q] = (rq[q] < nr) ? Pb[(r0 + rq[q]) * K + cq[q]] : (uint16_t)0;
+  };
+  double acc = 0.0;  // this lane's sub-sum
+  fetch(0);
   for (long long r0 = 0; r0 < N; r0 += rows_chunk) {
     const int nr = (int)((N - r0) < rows_chunk ? (N - r0) : rows_chunk);
     __syncthreads();
-    for (int e = tid; e < nr * B; e += 256) {
-      int rr = e / B, cc = e % B;
-      s_xi[e] = (double)esp_to_float<DT>(Pb[(r0 + rr) * K + cc]) * spb[cc];
-    }
+#pragma unroll
+    for (int q = 0; q < EPT; q++)
+      if (rq[q] < nr) s_xi[rq[q] * stride + cq[q]] = (double)esp_to_float<DT>(nextv[q]) * sq[q];
     __syncthreads();
+    if (r0 + rows_chunk < N) fetch(r0 + rows_chunk);
     if (active) {
-      for (int rr = 0; rr < nr; rr++) {
+      // rows r0 + rl, r0 + rl + 16, ...: r0 is a multiple of 16, so they are this lane's rows
+#pragma unroll 4
+      for (int rr = rl; rr < nr; rr += ROW_LANES) {
         double v[MG];
 #pragma unroll
-        for (int k = 0; k < MG; k++) v[k] = s_xi[rr * B + cols[k]];
+        for (int k = 0; k < MG; k++) v[k] = s_xi[rr * stride + cols[k]];
         acc = acc + top_n_sum<NKEEP, MG>(v);
       }
     }
   }
-  if (active) V[(((long long)blk * G + g) * MG + i) * B + x] = acc;
+  const double total = lanes_total(active ? acc : 0.0);
+  if (active && rl == 0) V[(((long long)blk * G + g) * MG + i) * B + x] = total;
+}
+
+// The same table for 2:4, several times faster.  The B candidates x of one (group g, member i)
+// combination share the group's three other members, so the two largest of those three are found
+// once per row (m1 >= m2) and a candidate's retained metric in that row is
+// max(m1, xi_x) + max(m2, min(m1, xi_x)): the two largest of the four values, the same two doubles
+// the general network adds.  A workgroup (1024 threads = up to 64 candidates x 16 row lanes) stages the
+// block's metric values once per chunk and evaluates NC units with them; a unit is a combination and
+// a slice of XL = min(B, 64) candidates.  grid (ceil(units / NC), blocks); B % 64 == 0 or B < 64.
+template <int DT, int NC>
+__global__ void __launch_bounds__(1024) k_lbs_eval_2_4(const uint16_t* __restrict__ P, const double* __restrict__ sp,
+                                                        const int* __restrict__ lp, const int* __restrict__ groups,
+                                                        const int* __restrict__ done, long long N, long long K, int B, int rows_chunk,
+                                                        double* __restrict__ V) {
+  constexpr int MG = 4;
+  extern __shared__ unsigned char smem_raw[];
+  double* s_xi = reinterpret_cast<double*>(smem_raw);  // [rows_chunk][B + 1]
+  __shared__ int s_lp[256];
+  const int blk = blockIdx.y;
+  if (done[blk]) return;
+  const int G = B / MG;
+  const int tid = threadIdx.x;
+  const int rl = tid & (ROW_LANES - 1), xl = tid >> 4;
+  const int XL = B < 64 ? B : 64, xslices = B / XL;
+  const int ngroups = groups ? 2 : G;
+  const int nunits = ngroups * MG * xslices;
+  const int stride = B + 1;
+  double* s_pair = s_xi + (size_t)rows_chunk * stride;  // [NC][rows_chunk][2]: the 16 row lanes read 256 contiguous bytes
+  for (int i = tid; i < B; i += 1024) s_lp[i] = lp[blk * B + i];
+  __syncthreads();
+  // per unit: group, member, candidate of this thread, and whether the entry exists
+  int ug[NC], ui[NC], ux[NC];
+  bool uact[NC];
+#pragma unroll
+  for (int c = 0; c < NC; c++) {
+    const int u = blockIdx.x * NC + c;
+    const int cmb = u / xslices;
+    ux[c] = (u % xslices) * XL + xl;
+    ui[c] = cmb % MG;
+    const int gsel = cmb / MG;
+    ug[c] = -1;
+    if (u < nunits) ug[c] = groups ? groups[blk * 2 + gsel] : gsel;
+    uact[c] = ug[c] >= 0 && xl < XL;
+    if (!uact[c]) ux[c] = 0;
+    if (uact[c]) {
+#pragma unroll
+      for (int k = 0; k < MG; k++)
+        if (k != ui[c] && s_lp[ug[c] * MG + k] == ux[c]) uact[c] = false;  // x is another member of the group
+    }
+  }
+  const uint16_t* Pb = P + (long long)blk * B;
+  const double* spb = sp + (long long)blk * B;
+  constexpr int EPT = 4;
+  const int elems = rows_chunk * B;  // <= EPT * 1024
+  uint16_t nextv[EPT];
+  int rq[EPT], cq[EPT];
+  double sq[EPT];
+#pragma unroll
+  for (int q = 0; q < EPT; q++) {
+    const int e = tid + 1024 * q;
+    rq[q] = e < elems ? e / B : rows_chunk;
+    cq[q] = e % B;
+    sq[q] = spb[cq[q]];
+  }
+  auto fetch = [&](long long r0) {
+    const int nr = (int)((N - r0) < rows_chunk ? (N - r0) : rows_chunk);
+#pragma unroll
+    for (int q = 0; q < EPT; q++) nextv[q] = (rq[q] < nr) ? Pb[(r0 + rq[q]) * K + cq[q]] : (uint16_t)0;
+  };
+  double acc[NC];
+#pragma unroll
+  for (int c = 0; c < NC; c++) acc[c] = 0.0;
+  fetch(0);
+  for (long long r0 = 0; r0 < N; r0 += rows_chunk) {
+    const int nr = (int)((N - r0) < rows_chunk ? (N - r0) : rows_chunk);
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < EPT; q++)
+      if (rq[q] < nr) s_xi[rq[q] * stride + cq[q]] = (double)esp_to_float<DT>(nextv[q]) * sq[q];
+    __syncthreads();
+    if (r0 + rows_chunk < N) fetch(r0 + rows_chunk);
+    for (int t = tid; t < nr * NC; t += 1024) {
+      const int row = t / NC, c = t % NC;
+      const int u = blockIdx.x * NC + c;
+      const int cmb = u / xslices, mi = cmb % MG, gsel = cmb / MG;
+      double m1 = 0.0, m2 = 0.0;
+      if (u < nunits) {
+        const int gg = groups ? groups[blk * 2 + gsel] : gsel;
+        if (gg >= 0) {
+          double o[3];
+          int c3 = 0;
+#pragma unroll
+          for (int k = 0; k < MG; k++)
+            if (k != mi) o[c3++] = s_xi[row * stride + s_lp[gg * MG + k]];
+          const double hi = fmax(o[0], o[1]), lo = fmin(o[0], o[1]);
+          m1 = fmax(hi, o[2]);
+          m2 = fmax(lo, fmin(hi, o[2]));
+        }
+      }
+      s_pair[2 * (c * rows_chunk + row)] = m1;
+      s_pair[2 * (c * rows_chunk + row) + 1] = m2;
+    }
+    __syncthreads();
+    // rows r0 + rl, r0 + rl + 16, ...: r0 is a multiple of 16, so they are this lane's rows
+    for (int rr = rl; rr < nr; rr += ROW_LANES) {
+#pragma unroll
+      for (int c = 0; c < NC; c++) {  // entries that do not exist compute along (column 0) and are dropped at the end
+        const double xv = s_xi[rr * stride + ux[c]];
+        const double2 mm = *reinterpret_cast<const double2*>(s_pair + 2 * (c * rows_chunk + rr));
+        acc[c] = acc[c] + (fmax(mm.x, xv) + fmax(mm.y, fmin(mm.x, xv)));
+      }
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < NC; c++) {
+    const double total = lanes_total(uact[c] ? acc[c] : 0.0);
+    if (uact[c] && rl == 0) V[(((long long)blk * G + ug[c]) * MG + ui[c]) * B + ux[c]] = total;
+  }
 }
 
 // One workgroup per block: best exchange (largest delta, ties -> smallest (i, j)), applied if delta > 0.
@@ -498,23 +659,28 @@ template <int DT, int NKEEP, int MG>
 __global__ void __launch_bounds__(64) k_group_values(const uint16_t* __restrict__ W, const double* __restrict__ s,
                                                       const int32_t* __restrict__ theta, long long N, long long K,
                                                       double* __restrict__ out) {
-  long long g = (long long)blockIdx.x * 64 + threadIdx.x;
-  if (g >= K / MG) return;
+  // 4 groups per workgroup, 16 row lanes per group
+  const int rl = threadIdx.x & (ROW_LANES - 1);
+  const long long g = (long long)blockIdx.x * 4 + (threadIdx.x >> 4);
+  const bool active = g < K / MG;
   int c[MG];
   double sc[MG];
 #pragma unroll
   for (int k = 0; k < MG; k++) {
-    c[k] = theta[g * MG + k];
-    sc[k] = s[c[k]];
+    c[k] = active ? theta[g * MG + k] : 0;
+    sc[k] = active ? s[c[k]] : 0.0;
   }
   double acc = 0.0;
-  for (long long j = 0; j < N; j++) {
-    double v[MG];
+  if (active) {
+    for (long long j = rl; j < N; j += ROW_LANES) {
+      double v[MG];
 #pragma unroll
-    for (int k = 0; k < MG; k++) v[k] = fabs((double)esp_to_float<DT>(W[j * K + c[k]])) * sc[k];
-    acc = acc + top_n_sum<NKEEP, MG>(v);
+      for (int k = 0; k < MG; k++) v[k] = fabs((double)esp_to_float<DT>(W[j * K + c[k]])) * sc[k];
+      acc = acc + top_n_sum<NKEEP, MG>(v);
+    }
   }
-  out[g] = acc;
+  const double total = lanes_total(acc);
+  if (active && rl == 0) out[g] = total;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -601,19 +767,39 @@ int esp_prune_device(esparse_ctx* ctx, const double* score, const void* Wv, long
                        d_swaps.as<long long>(), (int)nblk, B);
     int nact = (int)nblk;
     ESP_HIP(ctx, hipMemcpyAsync(d_nact.p, &nact, 4, hipMemcpyHostToDevice, st));
-    const int rows_chunk = std::max(1, 4096 / B);
-    const size_t smem = (size_t)rows_chunk * B * 8;
+    // rows per LDS chunk: a multiple of the 16 row lanes, about 4096 metric values (at most 16 per thread)
+    const int rows_chunk = std::max(16, (4096 / B) / 16 * 16);
+    const size_t smem = (size_t)rows_chunk * (B + 1) * 8;
     bool first = true;
     long long iter = 0;
     while (nact > 0) {
       const int entries = (first ? G : 2) * m * B;
-      dim3 grid((unsigned)((entries + 255) / 256), (unsigned)nblk);
       const int* grp = first ? nullptr : d_groups.as<int>();
-#define LAUNCH_EVAL(DT, NK, MGv, ...)                                                                                  \
-  hipLaunchKernelGGL((k_lbs_eval<DT, NK, MGv>), grid, dim3(256), smem, st, d_P.as<uint16_t>(), d_sp.as<double>(), d_lp.as<int>(), \
+      if (n == 2 && m == 4 && (B % 64 == 0 || B < 64)) {
+        // 2:4: 8 units per workgroup while every group is evaluated, 2 in the refresh rounds (more workgroups)
+        const int units = (first ? G : 2) * m * (B < 64 ? 1 : B / 64);
+        const int nc = first ? 8 : 2;
+        dim3 grid((unsigned)((units + nc - 1) / nc), (unsigned)nblk);
+        const size_t smem2 = (size_t)rows_chunk * (B + 1) * 8 + (size_t)rows_chunk * nc * 16;
+#define LAUNCH_EVAL24(DTv, NCv)                                                                                             \
+  hipLaunchKernelGGL((k_lbs_eval_2_4<DTv, NCv>), grid, dim3(1024), smem2, st, d_P.as<uint16_t>(), d_sp.as<double>(), d_lp.as<int>(), \
                      grp, d_done.as<int>(), N, K, B, rows_chunk, d_V.as<double>())
-      DISPATCH_DT_NM(dtype, n, LAUNCH_EVAL, 0);
+        if (dtype == ESPARSE_F16) {
+          if (first) LAUNCH_EVAL24(ESPARSE_F16, 8);
+          else LAUNCH_EVAL24(ESPARSE_F16, 2);
+        } else {
+          if (first) LAUNCH_EVAL24(ESPARSE_BF16, 8);
+          else LAUNCH_EVAL24(ESPARSE_BF16, 2);
+        }
+#undef LAUNCH_EVAL24
+      } else {
+        dim3 grid((unsigned)((entries + 63) / 64), (unsigned)nblk);
+#define LAUNCH_EVAL(DT, NK, MGv, ...)                                                                                  \
+  hipLaunchKernelGGL((k_lbs_eval<DT, NK, MGv>), grid, dim3(1024), smem, st, d_P.as<uint16_t>(), d_sp.as<double>(), d_lp.as<int>(), \
+                     grp, d_done.as<int>(), N, K, B, rows_chunk, d_V.as<double>())
+        DISPATCH_DT_NM(dtype, n, LAUNCH_EVAL, 0);
 #undef LAUNCH_EVAL
+      }
       ESP_HIP(ctx, hipGetLastError());
       if (m == 4)
         hipLaunchKernelGGL(k_lbs_select<4>, dim3((unsigned)nblk), dim3(256), 0, st, d_V.as<double>(), d_lp.as<int>(), d_groups.as<int>(),
@@ -652,7 +838,7 @@ int esp_prune_device(esparse_ctx* ctx, const double* score, const void* Wv, long
     DevBuf d_gv;
     const long long ng = K / m;
     if (d_gv.alloc(ng * 8) != hipSuccess) return esp_fail(ctx, ESPARSE_ENOMEM, "scratch allocation failed");
-    dim3 grid((unsigned)((ng + 63) / 64));
+    dim3 grid((unsigned)((ng + 3) / 4));
 #define LAUNCH_GV(DT, NK, MGv, ...) \
   hipLaunchKernelGGL((k_group_values<DT, NK, MGv>), grid, dim3(64), 0, st, W, d_s.as<double>(), perm_out, N, K, d_gv.as<double>())
     DISPATCH_DT_NM(dtype, n, LAUNCH_GV, 0);
