@@ -37,6 +37,9 @@ MEASURED_TRAFFIC = {
     (2, 1, 4096, 4096): 19974609, (2, 8, 4096, 4096): 20030503, (2, 32, 4096, 4096): 21278653,
     (2, 1, 11008, 4096): 51866143, (2, 8, 11008, 4096): 52021023, (2, 32, 11008, 4096): 54076166,
     (2, 1, 4096, 11008): 53591110, (2, 8, 4096, 11008): 53647089, (2, 32, 4096, 11008): 56664533,
+    # group launches (config, M, N, K, members)
+    (2, 1, 4096, 4096, 3): 59895462, (2, 8, 4096, 4096, 3): 60006317, (2, 32, 4096, 4096, 3): 63743589,
+    (2, 1, 11008, 4096, 2): 104096772, (2, 8, 11008, 4096, 2): 104506660, (2, 32, 11008, 4096, 2): 107312110,
     (3, 512, 5120, 5120): 82745824, (3, 2048, 5120, 5120): 314272462, (3, 512, 13824, 5120): 144935671,
     (3, 2048, 13824, 5120): 504618024, (3, 512, 5120, 13824): 220277027, (3, 2048, 5120, 13824): 842458894,
 }
@@ -144,7 +147,7 @@ def main():
     outs = {(name, M): torch.empty((M, shapes[skey][0]), dtype=tdtype, device=dev)
             for name, skey, _ in MATS for M in M_LIST}
     ws_bytes = max(esp.spmm_workspace(M, shapes[skey][0], shapes[skey][1]) for _, skey, _ in MATS for M in M_LIST)
-    ws = ctx.workspace(ws_bytes)
+    ws = ctx.workspace(4 * ws_bytes)        # room for the group calls (up to 4 staged inputs)
 
     # every shape gets the variant the library's own tuner finds fastest (sparse and dense alike)
     tuned = {}
@@ -157,19 +160,36 @@ def main():
             tuned[f"{skey}/M={M}"] = [esp.variant_name(vs), esp.variant_name(vd)]
 
     # ------------------------------------------------------------------ steps
+    # the linears of a layer that have one shape and read one input (q/k/v; gate/up) go through the library's
+    # group call: the same products, bit for bit, with one staging launch and one multiply launch per group where
+    # a decode kernel serves the shape.  Every matrix keeps its own permutation, mask and shape.
+    GROUPS = []
+    for name, skey, stream in MATS:
+        if GROUPS and GROUPS[-1][1] == skey and GROUPS[-1][2] == stream:
+            GROUPS[-1][0].append(name)
+        else:
+            GROUPS.append(([name], skey, stream))
+
     def step_sparse():
+        for mats in layers:
+            for M in M_LIST:
+                for names, _, stream in GROUPS:
+                    ctx.spmm_group([acts[(stream, M)]] * len(names), [mats[n]["comp"] for n in names],
+                                   [mats[n]["perm"] for n in names], outs=[outs[(n, M)] for n in names])
+
+    def step_dense():
+        for mats in layers:
+            for M in M_LIST:
+                for names, skey, stream in GROUPS:
+                    ctx.dense_gemm_group([acts[(stream, M)]] * len(names), [mats[n]["packed"] for n in names], shapes[skey][0],
+                                         outs=[outs[(n, M)] for n in names])
+
+    def step_sparse_single():
         for mats in layers:
             for M in M_LIST:
                 for name, _, stream in MATS:
                     m = mats[name]
                     ctx.spmm(acts[(stream, M)], m["comp"], m["perm"], out=outs[(name, M)])
-
-    def step_dense():
-        for mats in layers:
-            for M in M_LIST:
-                for name, _, stream in MATS:
-                    m = mats[name]
-                    ctx.dense_gemm(acts[(stream, M)], m["packed"], m["N"], out=outs[(name, M)])
 
     def step_hipblaslt():
         for mats in layers:
@@ -228,6 +248,19 @@ def main():
                 for _ in range(3):
                     ctx.dense_gemm_staged(M, m["packed"], N, K, ws, outs[(name, M)])
                 torch.cuda.synchronize()
+        for names, skey, stream in GROUPS:
+            if len(names) < 2:
+                continue
+            N, K = shapes[skey]
+            for M in [m_ for m_ in M_LIST if m_ <= 64]:
+                cnt = len(names)
+                print(f"counter probe: group of {cnt}, M={M} N={N} K={K}: 1 x group stage, 3 x group sparse product "
+                      f"(algorithmic bytes {int(cnt * (1.125 * N * K + 2 * M * N) + 2 * M * K)})", flush=True)
+                ctx.stage_activations_group([acts[(stream, M)]] * cnt, [layers[0][n]["perm"] for n in names],
+                                            layers[0][names[0]]["comp"], ws)
+                for _ in range(3):
+                    ctx.spmm_group_staged(M, [layers[0][n]["comp"] for n in names], ws, [outs[(n, M)] for n in names])
+                torch.cuda.synchronize()
         return
 
     flops_step = sum(2.0 * M * shapes[skey][0] * shapes[skey][1] for _, skey, _ in MATS for M in M_LIST) * LAYERS
@@ -237,6 +270,7 @@ def main():
     t_dense = timed(g_dense, args.steps, args.warmup)
     g_ref = capture(step_hipblaslt)
     t_ref = timed(g_ref, args.steps, args.warmup)
+    t_single = timed(capture(step_sparse_single), args.steps, args.warmup)
 
     # ------------------------------------------------------------------ per-kernel durations (HIP events on the launch stream)
     def kernel_time(launch, reps):
@@ -324,14 +358,44 @@ def main():
                        speedup_vs_dense_incl_stage=round((td + tg) / (ts + tg), 3),
                        alg_bytes=int(bytes_alg), flops=flops)
             per_shape.append(row)
-    # dominant kernel = the multiply kernel of the (shape, M) class with the largest total time per step
-    dom = max(per_shape, key=lambda r: r["spmm_kernel_us"] * r["count_per_layer"])
+    # the grouped launches of the step (q/k/v, gate/up at decode sizes): one multiply kernel for the whole group
+    per_group = []
+    for names, skey, stream in GROUPS:
+        if len(names) < 2:
+            continue
+        N, K = shapes[skey]
+        for M in [m_ for m_ in M_LIST if m_ <= 64]:
+            cnt = len(names)
+            X = acts[(stream, M)]
+            ctx.stage_activations_group([X] * cnt, [layers[0][n]["perm"] for n in names], layers[0][names[0]]["comp"], ws)
+            ys = [outs[(n, M)] for n in names]
+
+            def gp(i, M=M, names=names, ys=ys):
+                ctx.spmm_group_staged(M, [layers[i % LAYERS][n]["comp"] for n in names], ws, ys)
+
+            def gs(i, X=X, names=names, cnt=cnt):
+                ctx.stage_activations_group([X] * cnt, [layers[i % LAYERS][n]["perm"] for n in names],
+                                            layers[0][names[0]]["comp"], ws)
+
+            tgp, tgs = kernel_time(gp, 48), kernel_time(gs, 48)
+            bytes_alg = cnt * (1.125 * N * K + 2.0 * M * N) + 2.0 * M * K
+            per_group.append(dict(layer=skey, members=cnt, N=N, K=K, M=M, count_per_layer=1, bound="hbm",
+                                  kernel=kernel_name(skey, M) + f" x{cnt} in one launch",
+                                  spmm_kernel_us=round(tgp * 1e6, 2), stage_kernel_us=round(tgs * 1e6, 2),
+                                  rotating_weight_mb=round(LAYERS * cnt * 1.125 * N * K / 1e6, 1),
+                                  kernel_gbs=round(bytes_alg / tgp / 1e9, 1), frac_hbm_peak=round(bytes_alg / tgp / 1e9 / HBM_PEAK_GBS, 3),
+                                  alg_bytes=int(bytes_alg), flops=2.0 * cnt * M * N * K))
+    # dominant kernel = the multiply kernel with the largest total time per step among the launches the step makes:
+    # group launches where they exist, single products otherwise
+    grouped_keys = {(g_["layer"], g_["M"]) for g_ in per_group}
+    launches = per_group + [r for r in per_shape if (r["layer"], r["M"]) not in grouped_keys]
+    dom = max(launches, key=lambda r: r["spmm_kernel_us"] * r["count_per_layer"])
     if dom["bound"] == "hbm":
         ach = dom["alg_bytes"] / (dom["spmm_kernel_us"] * 1e-6) / 1e9
         roofline = dict(bound="hbm", kernel=dom["kernel"] + " (2:4 sparse product, staged activations)",
                         shape=f"M={dom['M']} N={dom['N']} K={dom['K']}", achieved=round(ach, 1), peak=HBM_PEAK_GBS,
                         unit="GB/s", frac=round(ach / HBM_PEAK_GBS, 4), alg_bytes_per_launch=dom["alg_bytes"],
-                        avg_launch_us=dom["spmm_kernel_us"], traffic=MEASURED_TRAFFIC.get((CFG, dom["M"], dom["N"], dom["K"])))
+                        avg_launch_us=dom["spmm_kernel_us"], traffic=MEASURED_TRAFFIC.get((CFG, dom["M"], dom["N"], dom["K"]) + ((dom["members"],) if "members" in dom else ())))
     else:
         ach = dom["flops"] / (dom["spmm_kernel_us"] * 1e-6) / 1e12
         roofline = dict(bound="mfma", kernel=dom["kernel"] + " (2:4 sparse product, staged activations)",
@@ -339,8 +403,8 @@ def main():
                         peak=SPARSE_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=round(ach / SPARSE_MFMA_PEAK_TFLOPS, 4),
                         flops_per_launch=dom["flops"], avg_launch_us=dom["spmm_kernel_us"],
                         note="dense-equivalent flops 2 M N K against twice the dense 16-bit MFMA peak",
-                        traffic=MEASURED_TRAFFIC.get((CFG, dom["M"], dom["N"], dom["K"])))
-    for r in per_shape:
+                        traffic=MEASURED_TRAFFIC.get((CFG, dom["M"], dom["N"], dom["K"]) + ((dom["members"],) if "members" in dom else ())))
+    for r in per_shape + per_group:
         del r["flops"]
 
     # ------------------------------------------------------------------ CPU oracle on a bounded sample + parity of that sample
@@ -511,6 +575,8 @@ def main():
         "config": {"workload": WORKLOAD_TEXT[CFG] + ", 2:4 along K, entropy+norm metric, GNS + LBS(64); "
                                f"{LAYERS} layer instances per step ({n_prod} products), one HIP graph per step",
                    "calib_tokens": T, "alpha": alpha},
+        "launches": "grouped: q/k/v and gate/up each go through one esparse_spmm_group call (own theta, mask and shape per matrix)",
+        "ms_per_step_one_call_per_product": round(t_single * 1e3, 4),
         "speedup_vs_inrepo_dense": round(t_dense / t_sparse, 3),
         "dense_inrepo_ms_per_step": round(t_dense * 1e3, 4),
         "hipblaslt_dense_ms_per_step": round(t_ref * 1e3, 4),
@@ -524,6 +590,7 @@ def main():
         "fused_shared_input": fused,
         "four_eight_vs_two_four": four_eight,
         "ablation_eq4": {"matrix": f"{name0} of layer instance 0, 256 held-out tokens", "rows": ablation},
+        "per_group_launch": per_group,
         "per_shape": per_shape,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,

@@ -175,6 +175,39 @@ int esparse_dense_gemm_staged(esparse_ctx* ctx, long long M, const void* packed_
                               long long K, esparse_dtype dtype, void* Y, void* workspace,
                               size_t workspace_bytes, int variant);
 
+/* ---- Section 4 / Table 5 (decoder): several products of one shape in one call ---------------------
+ * At decode sizes one product of a 4096 x 4096 matrix is a few microseconds of kernel, mostly launch and
+ * ramp-up; the linear layers that read the same hidden state (q/k/v, gate/up) have the same shape.  This
+ * call runs count (1..4) products Y[i] = X[i][:, perm[i]] . W'_i^T, all with the same M, N, K, dtype
+ * and n:m, through one staging launch and one multiply launch when a decode kernel serves the shape
+ * (M <= 64, or 4:8), and one after the other otherwise.  X, native_w, perm, Y: HOST arrays of count
+ * DEVICE pointers (perm may be NULL = identity for all, or hold NULL entries); members may share X.
+ * workspace: DEVICE, 256-byte aligned, at least esparse_spmm_group_workspace bytes.  Results are
+ * bitwise those of esparse_spmm with the same variant.  Errors as esparse_spmm; count outside 1..4:
+ * EINVAL.  Does not synchronise. */
+int esparse_spmm_group_workspace(int count, long long M, long long N, long long K, size_t* bytes);
+int esparse_spmm_group(esparse_ctx* ctx, int count, const void* const* X, long long M,
+                       const void* const* native_w, const int32_t* const* perm, long long N, long long K,
+                       esparse_dtype dtype, int n_keep, int m_group, void* const* Y, void* workspace,
+                       size_t workspace_bytes, int variant);
+
+/* The two halves of esparse_spmm_group (for callers that time the multiply alone); they exist where a
+ * decode kernel serves the shape (EUNSUPPORTED otherwise).  n_keep / m_group and variant must be the
+ * ones of the multiply that follows. */
+int esparse_stage_activations_group(esparse_ctx* ctx, int count, const void* const* X, long long M,
+                                    const int32_t* const* perm, long long N, long long K,
+                                    esparse_dtype dtype, int n_keep, int m_group, void* workspace,
+                                    size_t workspace_bytes, int variant);
+int esparse_spmm_group_staged(esparse_ctx* ctx, int count, long long M, const void* const* native_w,
+                              long long N, long long K, esparse_dtype dtype, int n_keep, int m_group,
+                              void* const* Y, void* workspace, size_t workspace_bytes, int variant);
+
+/* The dense counterpart (speedup denominator of the grouped call): count products
+ * Y[i] = X[i] . W_i^T with packed_w[i] from esparse_dense_pack.  Same conventions and workspace size. */
+int esparse_dense_gemm_group(esparse_ctx* ctx, int count, const void* const* X, long long M,
+                             const void* const* packed_w, long long N, long long K, esparse_dtype dtype,
+                             void* const* Y, void* workspace, size_t workspace_bytes, int variant);
+
 /* ---- Section 4, step 2: pick and remember the fastest variant for a shape --------------------
  * Times every applicable variant of esparse_spmm (sparse = 1: 2:4, sparse = 2: 4:8) or esparse_dense_gemm (sparse = 0) on
  * zero-filled scratch operands of shape (M, N, K) and stores the winner in the context; later

@@ -53,6 +53,11 @@ def load_library():
         "esparse_prune": (i32, [vp, vp, ll, vp, ll, ll, i32, P(_Opts), vp, vp, vp, vp, vp]),
         "esparse_prune_with_scores": (i32, [vp, vp, vp, ll, ll, i32, P(_Opts), vp, vp, vp, vp]),
         "esparse_output_error": (i32, [vp, vp, vp, ll, ll, i32, vp, vp]),
+        "esparse_spmm_group_workspace": (i32, [i32, ll, ll, ll, P(sz)]),
+        "esparse_spmm_group": (i32, [vp, i32, P(vp), ll, P(vp), P(vp), ll, ll, i32, i32, i32, P(vp), vp, sz, i32]),
+        "esparse_dense_gemm_group": (i32, [vp, i32, P(vp), ll, P(vp), ll, ll, i32, P(vp), vp, sz, i32]),
+        "esparse_stage_activations_group": (i32, [vp, i32, P(vp), ll, P(vp), ll, ll, i32, i32, i32, vp, sz, i32]),
+        "esparse_spmm_group_staged": (i32, [vp, i32, ll, P(vp), ll, ll, i32, i32, i32, P(vp), vp, sz, i32]),
         "esparse_compressed_size": (i32, [ll, ll, i32, i32, i32, P(sz), P(sz), P(sz)]),
         "esparse_compress": (i32, [vp, vp, vp, vp, ll, ll, i32, i32, i32, vp, vp, vp]),
         "esparse_spmm_workspace": (i32, [ll, ll, ll, P(sz)]),
@@ -79,6 +84,8 @@ def load_library():
 
 EXPORTED = ["esparse_create", "esparse_destroy", "esparse_set_stream", "esparse_last_error",
             "esparse_version", "esparse_channel_stats", "esparse_prune", "esparse_prune_with_scores", "esparse_output_error",
+            "esparse_spmm_group_workspace", "esparse_spmm_group", "esparse_dense_gemm_group",
+            "esparse_stage_activations_group", "esparse_spmm_group_staged",
             "esparse_compressed_size", "esparse_compress", "esparse_spmm_workspace", "esparse_spmm",
             "esparse_stage_activations", "esparse_spmm_staged", "esparse_dense_gemm_staged",
             "esparse_spmm_num_variants", "esparse_spmm_variant_name", "esparse_dense_packed_size",
@@ -273,6 +280,69 @@ class Context:
         self._check(self._lib.esparse_spmm(self._h, _ptr(X), M, _ptr(comp.native), _ptr(perm), comp.N, K, comp.dtype,
                                            comp.n_keep, comp.m_group, _ptr(Y), _ptr(ws), nbytes, variant))
         return Y
+
+    def spmm_group(self, Xs, comps, perms, *, variant: int = -1, outs=None):
+        """Products of one shape (same M, N, K, dtype, n:m) through one staging and one multiply launch
+        where a decode kernel serves the shape; returns the list of outputs."""
+        count = len(comps)
+        assert len(Xs) == count and (perms is None or len(perms) == count)
+        M, K = Xs[0].shape
+        c0 = comps[0]
+        for X, c in zip(Xs, comps):
+            assert tuple(X.shape) == (M, K) and (c.N, c.K, c.dtype, c.n_keep, c.m_group) == (c0.N, K, c0.dtype, c0.n_keep, c0.m_group)
+            assert _dtype_code(X) == c0.dtype
+        if outs is None:
+            outs = [torch.empty((M, c0.N), dtype=Xs[0].dtype, device=Xs[0].device) for _ in range(count)]
+        nbytes = C.c_size_t(0)
+        rc = self._lib.esparse_spmm_group_workspace(count, M, c0.N, K, C.byref(nbytes))
+        if rc:
+            raise EsparseError(rc, "esparse_spmm_group_workspace: bad arguments")
+        ws = self.workspace(nbytes.value)
+        arr = C.c_void_p * count
+        xs = arr(*[_ptr(x) for x in Xs])
+        wsn = arr(*[_ptr(c.native) for c in comps])
+        ps = arr(*[_ptr(p) for p in perms]) if perms is not None else None
+        ys = arr(*[_ptr(y) for y in outs])
+        self._sync_stream()
+        self._check(self._lib.esparse_spmm_group(self._h, count, xs, M, wsn, ps, c0.N, K, c0.dtype, c0.n_keep, c0.m_group, ys,
+                                                 _ptr(ws), nbytes.value, variant))
+        return outs
+
+    def stage_activations_group(self, Xs, perms, comp0: Compressed, ws: torch.Tensor, *, variant: int = -1):
+        count = len(Xs)
+        M, K = Xs[0].shape
+        arr = C.c_void_p * count
+        ps = arr(*[_ptr(p) for p in perms]) if perms is not None else None
+        self._sync_stream()
+        self._check(self._lib.esparse_stage_activations_group(self._h, count, arr(*[_ptr(x) for x in Xs]), M, ps, comp0.N, K,
+                                                              comp0.dtype, comp0.n_keep, comp0.m_group, _ptr(ws), ws.numel(), variant))
+
+    def spmm_group_staged(self, M: int, comps, ws: torch.Tensor, outs, *, variant: int = -1):
+        count = len(comps)
+        c0 = comps[0]
+        arr = C.c_void_p * count
+        self._sync_stream()
+        self._check(self._lib.esparse_spmm_group_staged(self._h, count, M, arr(*[_ptr(c.native) for c in comps]), c0.N, c0.K,
+                                                        c0.dtype, c0.n_keep, c0.m_group, arr(*[_ptr(y) for y in outs]), _ptr(ws),
+                                                        ws.numel(), variant))
+        return outs
+
+    def dense_gemm_group(self, Xs, packed, N: int, *, variant: int = -1, outs=None):
+        count = len(packed)
+        M, K = Xs[0].shape
+        if outs is None:
+            outs = [torch.empty((M, N), dtype=Xs[0].dtype, device=Xs[0].device) for _ in range(count)]
+        nbytes = C.c_size_t(0)
+        rc = self._lib.esparse_spmm_group_workspace(count, M, N, K, C.byref(nbytes))
+        if rc:
+            raise EsparseError(rc, "esparse_spmm_group_workspace: bad arguments")
+        ws = self.workspace(nbytes.value)
+        arr = C.c_void_p * count
+        self._sync_stream()
+        self._check(self._lib.esparse_dense_gemm_group(self._h, count, arr(*[_ptr(x) for x in Xs]), M, arr(*[_ptr(w) for w in packed]),
+                                                       N, K, _dtype_code(Xs[0]), arr(*[_ptr(y) for y in outs]), _ptr(ws), nbytes.value,
+                                                       variant))
+        return outs
 
     def stage_activations(self, X: torch.Tensor, perm: Optional[torch.Tensor], N: int,
                           ws: Optional[torch.Tensor] = None) -> torch.Tensor:

@@ -306,6 +306,78 @@ int esparse_spmm_staged(esparse_ctx* ctx, long long M, const void* native_w, lon
                      ESP_PHASE_MULTIPLY);
 }
 
+int esparse_spmm_group_workspace(int count, long long M, long long N, long long K, size_t* bytes) {
+  if (!bytes || count < 1 || count > 4 || M < 0 || N < 1 || K < 4) return ESPARSE_EINVAL;
+  *bytes = esp_group_workspace_bytes(count, M, N, K);
+  return ESPARSE_OK;
+}
+
+static int spmm_group_phases(esparse_ctx* ctx, int count, const void* const* X, long long M, const void* const* native_w,
+                             const int32_t* const* perm, long long N, long long K, esparse_dtype dtype, int n, int m,
+                             void* const* Y, void* workspace, size_t workspace_bytes, int variant, int phases) {
+  if (!ctx) return ESPARSE_EINVAL;
+  ESP_REQUIRE(ctx, count >= 1 && count <= 4, ESPARSE_EINVAL, "count = %d outside 1..4", count);
+  ESP_REQUIRE(ctx, (n == 2 && m == 4) || (n == 4 && m == 8), ESPARSE_EUNSUPPORTED,
+              "the sparse product exists for 2:4 and 4:8 only (got %d:%d)", n, m);
+  ESP_REQUIRE(ctx, ((phases & ESP_PHASE_STAGE) ? X != nullptr : true) && ((phases & ESP_PHASE_MULTIPLY) ? (native_w && Y) : true),
+              ESPARSE_EINVAL, "X / native_w / Y array is null");
+  const int mode = m == 4 ? 1 : 2;
+  for (int i = 0; i < count; i++) {
+    int rc = check_matmul(ctx, X ? X[i] : nullptr, M, native_w ? native_w[i] : nullptr, N, K, dtype, Y ? Y[i] : nullptr, workspace,
+                          workspace_bytes, variant, mode, phases);
+    if (rc) return rc;
+    ESP_REQUIRE(ctx, !perm || esp_aligned16(perm[i]), ESPARSE_EINVAL, "perm[%d] is not 16-byte aligned", i);
+  }
+  ESP_REQUIRE(ctx, K % m == 0, ESPARSE_EINVAL, "K = %lld is not a multiple of %d", K, m);
+  if (M == 0) return ESPARSE_OK;
+  ESP_REQUIRE(ctx, workspace_bytes >= esp_group_workspace_bytes(count, M, N, K), ESPARSE_EWORKSPACE,
+              "workspace has %zu bytes, %zu needed", workspace_bytes, esp_group_workspace_bytes(count, M, N, K));
+  const int v = pick_variant(ctx, mode, dtype, M, N, K, variant);
+  ESP_REQUIRE(ctx, phases == (ESP_PHASE_STAGE | ESP_PHASE_MULTIPLY) || esp_variant_is_decode_kernel(v), ESPARSE_EUNSUPPORTED,
+              "the two halves of a group call exist for the decode kernels only");
+  ESP_HIP(ctx, hipSetDevice(ctx->device));
+  return esp_matmul_group_device(ctx, mode, count, X, M, native_w, perm, N, K, dtype, Y, workspace, v, phases);
+}
+
+int esparse_spmm_group(esparse_ctx* ctx, int count, const void* const* X, long long M, const void* const* native_w,
+                       const int32_t* const* perm, long long N, long long K, esparse_dtype dtype, int n, int m,
+                       void* const* Y, void* workspace, size_t workspace_bytes, int variant) {
+  return spmm_group_phases(ctx, count, X, M, native_w, perm, N, K, dtype, n, m, Y, workspace, workspace_bytes, variant,
+                           ESP_PHASE_STAGE | ESP_PHASE_MULTIPLY);
+}
+
+int esparse_stage_activations_group(esparse_ctx* ctx, int count, const void* const* X, long long M,
+                                    const int32_t* const* perm, long long N, long long K, esparse_dtype dtype, int n, int m,
+                                    void* workspace, size_t workspace_bytes, int variant) {
+  return spmm_group_phases(ctx, count, X, M, nullptr, perm, N, K, dtype, n, m, nullptr, workspace, workspace_bytes, variant,
+                           ESP_PHASE_STAGE);
+}
+
+int esparse_spmm_group_staged(esparse_ctx* ctx, int count, long long M, const void* const* native_w, long long N, long long K,
+                              esparse_dtype dtype, int n, int m, void* const* Y, void* workspace, size_t workspace_bytes,
+                              int variant) {
+  return spmm_group_phases(ctx, count, nullptr, M, native_w, nullptr, N, K, dtype, n, m, Y, workspace, workspace_bytes, variant,
+                           ESP_PHASE_MULTIPLY);
+}
+
+int esparse_dense_gemm_group(esparse_ctx* ctx, int count, const void* const* X, long long M, const void* const* packed_w,
+                             long long N, long long K, esparse_dtype dtype, void* const* Y, void* workspace,
+                             size_t workspace_bytes, int variant) {
+  if (!ctx) return ESPARSE_EINVAL;
+  ESP_REQUIRE(ctx, count >= 1 && count <= 4, ESPARSE_EINVAL, "count = %d outside 1..4", count);
+  ESP_REQUIRE(ctx, X && packed_w && Y, ESPARSE_EINVAL, "X / packed_w / Y array is null");
+  for (int i = 0; i < count; i++) {
+    int rc = check_matmul(ctx, X[i], M, packed_w[i], N, K, dtype, Y[i], workspace, workspace_bytes, variant, 0, 3);
+    if (rc) return rc;
+  }
+  if (M == 0) return ESPARSE_OK;
+  ESP_REQUIRE(ctx, workspace_bytes >= esp_group_workspace_bytes(count, M, N, K), ESPARSE_EWORKSPACE,
+              "workspace has %zu bytes, %zu needed", workspace_bytes, esp_group_workspace_bytes(count, M, N, K));
+  ESP_HIP(ctx, hipSetDevice(ctx->device));
+  return esp_matmul_group_device(ctx, 0, count, X, M, packed_w, nullptr, N, K, dtype, Y, workspace,
+                                 pick_variant(ctx, 0, dtype, M, N, K, variant), ESP_PHASE_STAGE | ESP_PHASE_MULTIPLY);
+}
+
 int esparse_dense_packed_size(long long N, long long K, size_t* bytes) {
   if (!bytes || N < 0 || K < 0) return ESPARSE_EINVAL;
   *bytes = (size_t)esp_round_up(N, 16) * (size_t)esp_round_up(K, 256) * 2;

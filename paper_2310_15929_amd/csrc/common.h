@@ -114,6 +114,12 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
                       const int32_t* perm, long long N, long long K, int dtype, void* Y,
                       void* workspace, int variant, int phases);
 
+size_t esp_group_workspace_bytes(int count, long long M, long long N, long long K);
+int esp_matmul_group_device(esparse_ctx* ctx, int sparse, int count, const void* const* X, long long M,
+                            const void* const* w, const int32_t* const* perm, long long N, long long K,
+                            int dtype, void* const* Y, void* workspace, int variant, int phases);
+bool esp_variant_is_decode_kernel(int v);
+
 // exact accumulation helpers (host)
 // value = sum_b bins[b] * 2^(unit0 + 16*b), rounded once to nearest-even double
 double esp_exact_bins_to_double(const unsigned long long* bins, int nb, int unit0);

@@ -29,6 +29,7 @@
 
 #define WS_HEADER_BYTES 65536
 #define MAX_SPLIT 16
+#define ESP_MAX_GROUP 4  // products of one shape that may share a launch
 
 // ------------------------------------------------------------------------------------------------
 // device-only intrinsics (hipcc also parses kernels in its host pass, where these do not exist)
@@ -112,8 +113,24 @@ __device__ __forceinline__ floatx4_t mfma16(uint4 a, uint4 b, floatx4_t c) {
 // activation staging: X[M,K] (original channel order) -> fragment-major X' through theta
 // one thread per 16-byte unit
 // ------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_gather_x(const uint16_t* __restrict__ X, const int32_t* __restrict__ perm, long long M,
-                                                   long long K, long long Kp, long long units, uint4* __restrict__ Xf) {
+// Up to ESP_MAX_GROUP products of one shape go through one launch (blockIdx.y picks the member): at
+// decode sizes a product of a 4096 x 4096 matrix is a 5 us kernel, mostly launch and ramp-up.
+struct GatherArgs {
+  const uint16_t* X[ESP_MAX_GROUP];
+  const int32_t* perm[ESP_MAX_GROUP];
+  uint4* Xf[ESP_MAX_GROUP];
+};
+struct KsplitArgs {
+  const uint4* A[ESP_MAX_GROUP];
+  const uint16_t* meta16[ESP_MAX_GROUP];
+  const uint4* Xf[ESP_MAX_GROUP];
+  uint16_t* Y[ESP_MAX_GROUP];
+};
+
+__global__ void __launch_bounds__(256) k_gather_x(GatherArgs args, long long M, long long K, long long Kp, long long units) {
+  const uint16_t* __restrict__ X = args.X[blockIdx.y];
+  const int32_t* __restrict__ perm = args.perm[blockIdx.y];
+  uint4* __restrict__ Xf = args.Xf[blockIdx.y];
   long long u = (long long)blockIdx.x * 256 + threadIdx.x;
   if (u >= units) return;
   const int lane = (int)(u & 63);
@@ -365,9 +382,12 @@ __global__ void __launch_bounds__(256) k_mm_wave_tile(const uint4* __restrict__ 
 // grid = ceil(row tiles / RT), block = 64 * NW.
 // ------------------------------------------------------------------------------------------------
 template <int DT, int SPARSE, int MT, int RT, int NW>
-__global__ void __launch_bounds__(NW * 64) k_mm_ksplit(const uint4* __restrict__ A, const uint16_t* __restrict__ meta16,
-                                                        const uint4* __restrict__ Xf, uint16_t* __restrict__ Y, long long M,
-                                                        long long N, long long Mp, long long Np, long long Kp) {
+__global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long long M, long long N, long long Mp, long long Np,
+                                                        long long Kp) {
+  const uint4* __restrict__ A = args.A[blockIdx.y];
+  const uint16_t* __restrict__ meta16 = args.meta16[blockIdx.y];
+  const uint4* __restrict__ Xf = args.Xf[blockIdx.y];
+  uint16_t* __restrict__ Y = args.Y[blockIdx.y];
   extern __shared__ floatx4_t s_red[];  // [NW][RT * MT][64]
   // SPARSE == 2 (4:8): byte-permute selectors that spread a group's 4 kept values over its 8 positions,
   // one 16-byte entry per bitmap: output half e takes value number popcount(bitmap below bit e) if
@@ -844,13 +864,12 @@ static void launch_wave_tile(const Variant& v, dim3 grid, hipStream_t st, const 
 }
 
 template <int DT, int SPARSE, int MT>
-static void launch_ksplit(const Variant& v, hipStream_t st, const uint4* A, const uint16_t* meta16, const uint4* Xf, uint16_t* Y,
-                          long long M, long long N, long long Mp, long long Np, long long Kp) {
+static void launch_ksplit(const Variant& v, hipStream_t st, const KsplitArgs& args, int count, long long M, long long N, long long Mp,
+                          long long Np, long long Kp) {
   const long long nrt = Np / 16;
-  dim3 grid((unsigned)((nrt + v.rt - 1) / v.rt));
+  dim3 grid((unsigned)((nrt + v.rt - 1) / v.rt), (unsigned)count);
   const size_t smem = (size_t)v.nw * v.rt * MT * 64 * 16;
-#define LAUNCH(R, W) \
-  hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W>), grid, dim3(W * 64), smem, st, A, meta16, Xf, Y, M, N, Mp, Np, Kp)
+#define LAUNCH(R, W) hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp)
   if (v.nw == 16 && v.rt == 1) LAUNCH(1, 16);
   else if (v.nw == 16 && v.rt == 2) LAUNCH(2, 16);
   else if (v.nw == 16 && v.rt == 3) LAUNCH(3, 16);
@@ -946,8 +965,45 @@ static int stage_activations(esparse_ctx* ctx, const void* X, const int32_t* per
     return ESPARSE_OK;
   }
   const long long units = Mp * Kp / 8;
-  hipLaunchKernelGGL(k_gather_x, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, ctx->stream, Xh, perm, M, K, Kp, units, Xf);
+  GatherArgs ga = {};
+  ga.X[0] = Xh;
+  ga.perm[0] = perm;
+  ga.Xf[0] = Xf;
+  hipLaunchKernelGGL(k_gather_x, dim3((unsigned)((units + 255) / 256), 1), dim3(256), 0, ctx->stream, ga, M, K, Kp, units);
   ESP_HIP(ctx, hipGetLastError());
+  return ESPARSE_OK;
+}
+
+// the decode kernels on `count` products of one shape: members share M, N, K; ka holds their operands
+static int launch_ksplit_any(esparse_ctx* ctx, const Variant& v, int sparse, int dtype, KsplitArgs ka, int count, long long M,
+                             long long N, long long Np, long long Kp) {
+  hipStream_t st = ctx->stream;
+  const long long nks = Kp / 64;
+  for (long long t0 = 0; t0 < M; t0 += 64) {  // more than 64 tokens (4:8 only): 64 at a time
+    const long long mc = (M - t0) < 64 ? (M - t0) : 64, mcp = esp_round_up(mc, 16);
+    KsplitArgs kc = ka;
+    for (int i = 0; i < count; i++) {
+      kc.Xf[i] = ka.Xf[i] + (t0 / 16) * (2 * nks) * 64;
+      kc.Y[i] = ka.Y[i] + t0 * N;
+    }
+#define ESP_KSPLIT(DTv, SPv)                                                          \
+  do {                                                                                \
+    if (mcp == 16) launch_ksplit<DTv, SPv, 1>(v, st, kc, count, mc, N, mcp, Np, Kp);  \
+    else if (mcp == 32) launch_ksplit<DTv, SPv, 2>(v, st, kc, count, mc, N, mcp, Np, Kp); \
+    else launch_ksplit<DTv, SPv, 4>(v, st, kc, count, mc, N, mcp, Np, Kp);            \
+  } while (0)
+    if (dtype == ESPARSE_F16) {
+      if (sparse == 2) ESP_KSPLIT(ESPARSE_F16, 2);
+      else if (sparse) ESP_KSPLIT(ESPARSE_F16, 1);
+      else ESP_KSPLIT(ESPARSE_F16, 0);
+    } else {
+      if (sparse == 2) ESP_KSPLIT(ESPARSE_BF16, 2);
+      else if (sparse) ESP_KSPLIT(ESPARSE_BF16, 1);
+      else ESP_KSPLIT(ESPARSE_BF16, 0);
+    }
+#undef ESP_KSPLIT
+    ESP_HIP(ctx, hipGetLastError());
+  }
   return ESPARSE_OK;
 }
 
@@ -970,30 +1026,12 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
   if (!(phases & ESP_PHASE_MULTIPLY)) return ESPARSE_OK;
 
   if (v.kind == KIND_KSPLIT) {
-    const uint16_t* meta16 = reinterpret_cast<const uint16_t*>(meta_bytes);
-#define ESP_KSPLIT(DTv, SPv)                                                                                   \
-  do {                                                                                                         \
-    for (long long t0 = 0; t0 < M; t0 += 64) { /* more than 64 tokens (4:8 only): 64 at a time */             \
-      const long long mc = (M - t0) < 64 ? (M - t0) : 64, mcp = esp_round_up(mc, 16);                          \
-      const uint4* xf = Xf + (t0 / 16) * (2 * nks) * 64;                                                       \
-      uint16_t* y = Y + t0 * N;                                                                                \
-      if (mcp == 16) launch_ksplit<DTv, SPv, 1>(v, st, A, meta16, xf, y, mc, N, mcp, Np, Kp);                  \
-      else if (mcp == 32) launch_ksplit<DTv, SPv, 2>(v, st, A, meta16, xf, y, mc, N, mcp, Np, Kp);             \
-      else launch_ksplit<DTv, SPv, 4>(v, st, A, meta16, xf, y, mc, N, mcp, Np, Kp);                            \
-    }                                                                                                          \
-  } while (0)
-    if (dtype == ESPARSE_F16) {
-      if (sparse == 2) ESP_KSPLIT(ESPARSE_F16, 2);
-      else if (sparse) ESP_KSPLIT(ESPARSE_F16, 1);
-      else ESP_KSPLIT(ESPARSE_F16, 0);
-    } else {
-      if (sparse == 2) ESP_KSPLIT(ESPARSE_BF16, 2);
-      else if (sparse) ESP_KSPLIT(ESPARSE_BF16, 1);
-      else ESP_KSPLIT(ESPARSE_BF16, 0);
-    }
-#undef ESP_KSPLIT
-    ESP_HIP(ctx, hipGetLastError());
-    return ESPARSE_OK;
+    KsplitArgs ka = {};
+    ka.A[0] = A;
+    ka.meta16[0] = reinterpret_cast<const uint16_t*>(meta_bytes);
+    ka.Xf[0] = Xf;
+    ka.Y[0] = Y;
+    return launch_ksplit_any(ctx, v, sparse, dtype, ka, 1, M, N, Np, Kp);
   }
 
   if (v.kind == KIND_TILE) {
@@ -1037,3 +1075,56 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
   }
   return ESPARSE_OK;
 }
+
+// ------------------------------------------------------------------------------------------------
+// several products of one shape
+// ------------------------------------------------------------------------------------------------
+size_t esp_group_workspace_bytes(int count, long long M, long long N, long long K) {
+  const size_t Mp = (size_t)esp_round_up(M, 16), Kp = (size_t)esp_round_up(K, 256);
+  const size_t xbytes = (Mp * Kp * 2 + 255) / 256 * 256;
+  return std::max(esp_workspace_bytes(M, N, K), (size_t)WS_HEADER_BYTES + (size_t)count * xbytes);
+}
+
+int esp_matmul_group_device(esparse_ctx* ctx, int sparse, int count, const void* const* X, long long M, const void* const* w,
+                            const int32_t* const* perm, long long N, long long K, int dtype, void* const* Y, void* workspace,
+                            int variant, int phases) {
+  const Variant& v = kVariants[variant];
+  if (v.kind != KIND_KSPLIT) {
+    // no grouped form of the other kernels: one product after the other through the same workspace
+    // (callers that split the phases get EUNSUPPORTED before they reach this point)
+    for (int i = 0; i < count; i++) {
+      int rc = esp_matmul_device(ctx, sparse, X[i], M, w[i], perm ? perm[i] : nullptr, N, K, dtype, Y[i], workspace, variant,
+                                 ESP_PHASE_STAGE | ESP_PHASE_MULTIPLY);
+      if (rc) return rc;
+    }
+    return ESPARSE_OK;
+  }
+  const long long Mp = esp_round_up(M, 16), Np = esp_round_up(N, 16), Kp = esp_round_up(K, 256);
+  unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+  const size_t xbytes = ((size_t)Mp * Kp * 2 + 255) / 256 * 256;
+  GatherArgs ga = {};
+  KsplitArgs ka = {};
+  for (int i = 0; i < count; i++) {
+    uint4* Xf = reinterpret_cast<uint4*>(ws + WS_HEADER_BYTES + (size_t)i * xbytes);
+    if (phases & ESP_PHASE_STAGE) {
+      ga.X[i] = reinterpret_cast<const uint16_t*>(X[i]);
+      ga.perm[i] = perm ? perm[i] : nullptr;
+      ga.Xf[i] = Xf;
+    }
+    if (phases & ESP_PHASE_MULTIPLY) {
+      ka.A[i] = reinterpret_cast<const uint4*>(w[i]);
+      ka.meta16[i] = sparse ? reinterpret_cast<const uint16_t*>(reinterpret_cast<const unsigned char*>(w[i]) + (size_t)Np * Kp) : nullptr;
+      ka.Xf[i] = Xf;
+      ka.Y[i] = reinterpret_cast<uint16_t*>(Y[i]);
+    }
+  }
+  if (phases & ESP_PHASE_STAGE) {
+    const long long units = Mp * Kp / 8;
+    hipLaunchKernelGGL(k_gather_x, dim3((unsigned)((units + 255) / 256), (unsigned)count), dim3(256), 0, ctx->stream, ga, M, K, Kp, units);
+    ESP_HIP(ctx, hipGetLastError());
+  }
+  if (!(phases & ESP_PHASE_MULTIPLY)) return ESPARSE_OK;
+  return launch_ksplit_any(ctx, v, sparse, dtype, ka, count, M, N, Np, Kp);
+}
+
+bool esp_variant_is_decode_kernel(int v) { return v >= 0 && v < kNumVariants && kVariants[v].kind == KIND_KSPLIT; }

@@ -437,3 +437,49 @@ def test_spmm_4_8_one_hot_reads_back_weights(esp, ctx):
     comp = ctx.compress(W.cuda(), torch.tensor(mask).cuda(), th, 4, 8, canonical=False)
     Y = ctx.spmm(torch.eye(K, dtype=torch.float16).cuda(), comp, th)         # [K, N]: row c = masked W[:, c]
     assert (_np(Y) == (_np(W) * orc.mask_to_original_order(mask, theta)).T).all()
+
+
+# ---------------------------------------------------------------- several products of one shape in one call
+@pytest.mark.parametrize("n,m", [(2, 4), (4, 8)])
+@pytest.mark.parametrize("M", [1, 20, 64, 100])
+def test_spmm_group_equals_single_products(esp, ctx, M, n, m):
+    N, K = 80, 512
+    rng = np.random.default_rng(M + n)
+    X = _rand((M, K), torch.float16, 90).cuda()
+    X2 = _rand((M, K), torch.float16, 91).cuda()
+    comps, perms, refs = [], [], []
+    for i in range(3):
+        W = _rand((N, K), torch.float16, 92 + i, scale=K ** -0.5)
+        s = np.abs(rng.standard_normal(K)) + 0.1
+        theta = rng.permutation(K)
+        mask = orc.nm_mask_vectorised(_np(W), s, theta, n, m)
+        th = torch.tensor(theta, dtype=torch.int32).cuda()
+        comps.append(ctx.compress(W.cuda(), torch.tensor(mask).cuda(), th, n, m, canonical=False))
+        perms.append(th)
+        refs.append(orc.spmm_ref(_np(X2 if i == 2 else X), _np(W), theta, mask))
+    Xs = [X, X, X2]                                   # two members share their input, like q/k/v
+    print(f"group M={M} {n}:{m}", flush=True)
+    Ys = ctx.spmm_group(Xs, comps, perms)
+    torch.cuda.synchronize()
+    for i in range(3):
+        assert orc.rowwise_rel_error(_np(Ys[i]), refs[i]).max() <= 2e-3
+        single = ctx.spmm(Xs[i], comps[i], perms[i])
+        assert (_bits(single) == _bits(Ys[i])).all()
+    if n == 2:
+        Ws = [_rand((N, K), torch.float16, 92 + i, scale=K ** -0.5).cuda() for i in range(3)]
+        packed = [ctx.dense_pack(W) for W in Ws]
+        Yd = ctx.dense_gemm_group(Xs, packed, N)
+        for i in range(3):
+            assert (_bits(Yd[i]) == _bits(ctx.dense_gemm(Xs[i], packed[i], N))).all()
+            assert orc.rowwise_rel_error(_np(Yd[i]), orc.dense_ref(_np(Xs[i]), _np(Ws[i]))).max() <= 2e-3
+    if M <= 32 or m == 8:
+        # the two halves as separate calls (they exist where a decode kernel is the default: M <= 32, or 4:8)
+        ws = ctx.workspace(4 * esp.spmm_workspace(M, N, K))
+        ctx.stage_activations_group(Xs, perms, comps[0], ws)
+        outs = [torch.empty_like(y) for y in Ys]
+        ctx.spmm_group_staged(M, comps, ws, outs)
+        for i in range(3):
+            assert (_bits(outs[i]) == _bits(Ys[i])).all()
+    # identity permutation for all members, one member only
+    Y1 = ctx.spmm_group([X], comps[:1], None)
+    assert (_bits(Y1[0]) == _bits(ctx.spmm(X, comps[0], None))).all()

@@ -69,6 +69,14 @@ def test_argument_errors_need_no_gpu():
     assert lib.esparse_channel_stats(ctx._h, None, 4, 16, 0, 100, None, None) == -1
     assert lib.esparse_create(None, 0, None) == -1
     assert lib.esparse_output_error(ctx._h, None, None, 4, 4, 0, None, None) == -1      # null result pointers
+    assert lib.esparse_spmm_group(ctx._h, 0, None, 4, None, None, 8, 16, 0, 2, 4, None, None, 0, -1) == -1   # count
+    assert lib.esparse_spmm_group(ctx._h, 5, None, 4, None, None, 8, 16, 0, 2, 4, None, None, 0, -1) == -1
+    assert lib.esparse_spmm_group(ctx._h, 2, None, 4, None, None, 8, 16, 0, 2, 4, None, None, 0, -1) == -1   # null arrays
+    assert lib.esparse_spmm_group(ctx._h, 2, None, 4, None, None, 8, 16, 0, 3, 4, None, None, 0, -1) == -2   # no 3:4
+    import ctypes as C
+    nb = C.c_size_t(0)
+    assert lib.esparse_spmm_group_workspace(3, 8, 512, 512, C.byref(nb)) == 0 and nb.value >= 65536 + 3 * 16 * 512 * 2
+    assert lib.esparse_spmm_group_workspace(0, 8, 512, 512, C.byref(nb)) == -1
     assert lib.esparse_output_error(None, None, None, 4, 4, 0, None, None) == -1        # null context
 
 
