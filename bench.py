@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the E-Sparse hot path on one MI355X.
 
-Default workload: configuration 2 of the build's workload list, the linear layers of a LLaMA-7B-shaped
+Default workload: configuration 2 of workloads.py, the linear layers of a LLaMA-7B-shaped
 decoder layer in fp16 (q/k/v/o 4096x4096, gate/up 11008x4096, down 4096x11008) at decode sizes
 M in {1, 8, 32}, pruned 2:4 with the entropy + norm metric, global naive shuffle and local block
 shuffle (blocks of 64), compressed, and multiplied with the sparse-MFMA kernels.  --config 3/4/5
@@ -14,7 +14,7 @@ as one HIP graph.  value = dense-equivalent flops (2 M N K per product) per seco
 steps.  The same steps run with the in-repo dense MFMA kernels give the speedup; hipBLASLt (through
 torch.matmul) is quoted as a reference point only.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line.
 """
 import argparse
 import ctypes as C
