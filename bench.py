@@ -456,6 +456,28 @@ def main():
                                    + (f", {feat_cap} sampled output features of the large ones" if sampled else "")
                                    + f"), {t_cpu:.1f} s of CPU time")
         parity = dict(max_row_rel_err=worst, tol=tol, ok=bool(worst <= tol), products_checked=done)
+        # the offline stage at config 1 (512 x 512, T = 256), the oracle on a bounded sample of it: statistics, GNS
+        # and mask complete, the LBS search on 1 of the 8 blocks
+        W1, Xc1 = wl.weights(1, "linear"), wl.calibration(1, "linear")
+        a1 = wl.default_alpha(Xc1.shape[0])
+        t0 = time.perf_counter()
+        s1 = orc.channel_score(Xc1.numpy(), a1, 100)
+        th0 = orc.global_naive_shuffle(W1.numpy(), s1, 4)
+        t1 = time.perf_counter()
+        th1, _ = orc.local_block_shuffle_vectorised(W1.numpy(), s1, th0, 2, 4, 64, blocks=[0])
+        t2 = time.perf_counter()
+        orc.nm_mask_vectorised(W1.numpy(), s1, th1, 2, 4)
+        t3 = time.perf_counter()
+        o1 = esp.PruneOpts(block=64, alpha=a1)
+        ctx.prune(Xc1.to(dev), W1.to(dev), o1)          # warm-up
+        torch.cuda.synchronize()
+        t4 = time.perf_counter()
+        r1 = ctx.prune(Xc1.to(dev), W1.to(dev), o1)
+        torch.cuda.synchronize()
+        t5 = time.perf_counter()
+        cpu_baseline["offline_config1"] = dict(oracle_stats_gns_s=round(t1 - t0, 3), oracle_lbs_one_block_of_8_s=round(t2 - t1, 3),
+                                               oracle_mask_s=round(t3 - t2, 4), device_prune_all_blocks_ms=round((t5 - t4) * 1e3, 2),
+                                               same_order_in_that_block=bool((r1.perm.cpu().numpy()[:64] == th1[:64]).all()))
 
     # ------------------------------------------------------------------ extra: products that share an input, fused
     # q/k/v read the same hidden state, so do gate/up: pruned as ONE stacked matrix they share one theta (the
