@@ -67,6 +67,13 @@ __device__ __forceinline__ void global_to_lds_4(const uint32_t* gsrc, uint32_t* 
   (void)lds_wave_base;
 #endif
 }
+// streaming load: the line is not kept in the caches once read (weights are read once per product)
+typedef unsigned int esp_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream_16(const uint4* p) {
+  const esp_u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const esp_u32x4*>(p));
+  return uint4{v.x, v.y, v.z, v.w};
+}
+__device__ __forceinline__ uint32_t load_stream_4(const uint32_t* p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ void sched_fence() {
 #if defined(__HIP_DEVICE_COMPILE__)
   __builtin_amdgcn_sched_barrier(0);
@@ -264,6 +271,29 @@ __global__ void __launch_bounds__(256) k_reduce_splits(const float* __restrict__
   floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
   for (int s = 0; s < nsplit; s++) {
     const floatx4_t v = *reinterpret_cast<const floatx4_t*>(partial + ((long long)s * Mp + t) * Np + n);
+    acc += v;
+  }
+  store_y4<DT>(Y, M, N, t, n, acc);
+}
+
+// partial[piece][t][n] -> Y for the stream kernels: the steps of all row blocks (rows_per_block rows, nks steps
+// each) form one sequence cut into spans of `span` steps, one per workgroup; row block rb is covered by the
+// spans first(rb) .. last(rb), whose partial tiles are pieces 0 .. last - first, added in ascending order.
+// A row block inside a single span was stored to Y by its workgroup and is skipped here.
+template <int DT>
+__global__ void __launch_bounds__(256) k_reduce_pieces(const float* __restrict__ partial, long long M, long long N, long long Mp,
+                                                        long long Np, uint16_t* __restrict__ Y, long long nks, long long span,
+                                                        long long rows_per_block) {
+  const long long n4 = Np / 4;
+  long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= M * n4) return;
+  const long long t = e / n4, n = (e % n4) * 4;
+  const long long rb = n / rows_per_block;
+  const long long first = (rb * nks) / span, last = ((rb + 1) * nks - 1) / span;
+  if (first == last) return;
+  floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+  for (long long s = 0; s <= last - first; s++) {
+    const floatx4_t v = *reinterpret_cast<const floatx4_t*>(partial + (s * Mp + t) * Np + n);
     acc += v;
   }
   store_y4<DT>(Y, M, N, t, n, acc);
@@ -769,9 +799,226 @@ __global__ void __launch_bounds__(128 * NWC) k_mm_tile(const uint4* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------------
+// variant "stream" (M <= 128, bound by reading the weights): a workgroup of NW waves owns NW RT row
+// tiles and all MT token tiles over a range of K; wave w owns row tiles (NW rb + w) RT .. + RT.
+// Weights go HBM -> registers, one 64-channel step at a time, NB - 1 steps ahead (registers, not LDS,
+// hold the bytes in flight: that is what lets a CU keep enough of them under way); the step's slice of
+// the staged activations (MT * 2 KiB) is shared by the waves through a ring of NB LDS buffers filled
+// by DMA.  Both kinds of load keep their program order, so one counted wait per step covers them.
+// Work is cut without regard to row blocks: the steps of all row blocks, nks each, form one sequence
+// that is cut into equal spans, one per workgroup, as many as the chip runs at once - no second, partly
+// filled round of workgroups.  A span that covers a whole row block stores Y; otherwise it writes an
+// fp32 partial tile, and k_reduce_pieces adds the pieces of a row block in ascending order.
+//
+// Two things keep the compiler's own waits out of the loop (it adds a full vmcnt(0) wherever it needs
+// any wait on a register load while a DMA into LDS is pending): the loop body runs at least once and
+// has no branches, so the loads stay in the order written here and the explicit counted wait already
+// covers every register the multiplies read; steps past the end of the K range (the trip count is
+// rounded up to whole rings) load the last real step again and multiply it by zeros.
+// ------------------------------------------------------------------------------------------------
+template <int SPARSE, int RT>
+struct StreamRegs {
+  uint4 a[RT];
+  uint4 a2[SPARSE ? 1 : RT];
+  int idx[RT];
+};
+
+template <int SPARSE, int MT, int RT, int NW>
+struct StreamState {
+  static constexpr int BC = (2 * MT + NW - 1) / NW;          // DMA copies of activations per lane and step
+  static constexpr int GSZ = 2 * RT + BC;                    // vector-memory operations per step and wave
+  const uint4* a_row[RT];     // per row tile: base of its weights
+  const uint32_t* m_row[RT];  // ... and of its index words (one word = the 16-bit index halves of two steps)
+  const uint4* x_src[BC];     // wave-uniform bases of this wave's DMA copies (token tile q / 2, half q % 2)
+  unsigned x_dst[BC];         // ... and where they land in a ring buffer, in units
+  unsigned lane, wave;
+};
+
+template <int SPARSE, int MT, int RT, int NW>
+__device__ __forceinline__ void stream_issue(const StreamState<SPARSE, MT, RT, NW>& st, StreamRegs<SPARSE, RT>& r, uint4* sb,
+                                             unsigned ks) {
+  using State = StreamState<SPARSE, MT, RT, NW>;
+#pragma unroll
+  for (int i = 0; i < RT; i++) {
+    if (SPARSE) {
+      r.a[i] = load_stream_16(st.a_row[i] + ((size_t)ks * 64 + st.lane));
+      r.idx[i] = (int)st.m_row[i][((size_t)(ks >> 2) * 64 + st.lane) * 2 + ((ks >> 1) & 1u)];
+    } else {
+      r.a[i] = load_stream_16(st.a_row[i] + ((size_t)(2 * ks) * 64 + st.lane));
+      r.a2[i] = load_stream_16(st.a_row[i] + ((size_t)(2 * ks + 1) * 64 + st.lane));
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < State::BC; p++) global_to_lds_16(st.x_src[p] + ((size_t)(2 * ks) * 64 + st.lane), sb + st.x_dst[p]);
+}
+
+// PAR = parity of the step: which half of the index word belongs to it; live = false: multiply by zeros
+template <int DT, int SPARSE, int MT, int RT, int NW, int PAR>
+__device__ __forceinline__ void stream_multiply(const StreamState<SPARSE, MT, RT, NW>& st, const StreamRegs<SPARSE, RT>& r,
+                                                const uint4* sb, floatx4_t (&acc)[RT][MT], bool live) {
+  const uint32_t keep = live ? 0xffffffffu : 0u;
+  uint4 a[RT], a2[SPARSE ? 1 : RT];
+#pragma unroll
+  for (int i = 0; i < RT; i++) {
+    a[i] = uint4{r.a[i].x & keep, r.a[i].y & keep, r.a[i].z & keep, r.a[i].w & keep};
+    if (!SPARSE) a2[i] = uint4{r.a2[i].x & keep, r.a2[i].y & keep, r.a2[i].z & keep, r.a2[i].w & keep};
+  }
+  // the activations of token tile j + 1 are read while tile j is multiplied
+  uint4 b0[2], b1[2];
+  b0[0] = sb[st.lane];
+  b1[0] = sb[64 + st.lane];
+#pragma unroll
+  for (int j = 0; j < MT; j++) {
+    if (j + 1 < MT) {
+      b0[(j + 1) & 1] = sb[(2 * j + 2) * 64 + st.lane];
+      b1[(j + 1) & 1] = sb[(2 * j + 3) * 64 + st.lane];
+    }
+#pragma unroll
+    for (int i = 0; i < RT; i++) {
+      if (SPARSE) {
+        acc[i][j] = smfmac16<DT, PAR>(a[i], b0[j & 1], b1[j & 1], acc[i][j], r.idx[i]);
+      } else {
+        acc[i][j] = mfma16<DT>(a[i], b0[j & 1], acc[i][j]);
+        acc[i][j] = mfma16<DT>(a2[i], b1[j & 1], acc[i][j]);
+      }
+    }
+  }
+  // issue order: reads of tile 0, then per tile the reads of the next one ahead of its multiplies
+  constexpr int MM = (SPARSE ? 1 : 2) * RT;
+  sched_group<0x100, 2>();
+#pragma unroll
+  for (int j = 0; j + 1 < MT; j++) {
+    sched_group<0x100, 2>();
+    sched_group<0x008, MM>();
+  }
+  sched_group<0x008, MM>();
+}
+
+// one step: wait for the loads of step ks (NB - 2 newer groups may be outstanding), meet the other waves (their
+// DMA of this step has landed too, and they are done with the buffer the next DMA overwrites), issue the loads
+// of step ks + NB - 1, multiply step ks
+template <int DT, int SPARSE, int MT, int RT, int NW, int NB, int PAR>
+__device__ __forceinline__ void stream_step(const StreamState<SPARSE, MT, RT, NW>& st, const StreamRegs<SPARSE, RT>& cur,
+                                            StreamRegs<SPARSE, RT>& pre, const uint4* sb_cur, uint4* sb_pre, floatx4_t (&acc)[RT][MT],
+                                            unsigned ks, unsigned k1) {
+  constexpr int OUT = (NB - 2) * StreamState<SPARSE, MT, RT, NW>::GSZ;
+  static_assert(OUT <= 63, "vmcnt is a 6-bit counter");
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_s_waitcnt((OUT & 15) | ((OUT >> 4) << 14) | 0x0F70);  // vmcnt(OUT)
+  __builtin_amdgcn_s_barrier();
+#endif
+  const unsigned kp = ks + (NB - 1);
+  stream_issue<SPARSE, MT, RT, NW>(st, pre, sb_pre, kp < k1 ? kp : k1 - 1);
+  sched_fence();  // the loads of one step stay together: the counted wait relies on their order
+  stream_multiply<DT, SPARSE, MT, RT, NW, PAR>(st, cur, sb_cur, acc, ks < k1);
+  sched_fence();
+}
+
+template <int DT, int SPARSE, int MT, int RT, int NW, int NB>
+__device__ __attribute__((always_inline)) void stream_pipeline(uint4* __restrict__ sb, const uint4* __restrict__ A,
+                                                               const uint16_t* __restrict__ meta16, const uint4* __restrict__ Xf,
+                                                               uint16_t* __restrict__ Y, float* __restrict__ partial, long long M,
+                                                               long long N, long long Mp, long long Np, long long Kp, long long span) {
+  static_assert(NB % 2 == 0, "the parity of a step is that of its ring slot");
+  using State = StreamState<SPARSE, MT, RT, NW>;
+  constexpr int BUF = MT * 128;  // units per ring buffer: [MT token tiles][2 half steps][64 lanes]
+  State st;
+  const int tid = threadIdx.x;
+  st.lane = (unsigned)(tid & 63);
+  st.wave = (unsigned)wave_uniform(tid >> 6);
+  const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
+  const long long nrb = (nrt + NW * RT - 1) / (NW * RT);
+  const long long s_begin = (long long)blockIdx.x * span;
+  const long long s_end = s_begin + span < nrb * nks ? s_begin + span : nrb * nks;
+#pragma unroll
+  for (int p = 0; p < State::BC; p++) {
+    const long long q = ((long long)NW * p + st.wave) % (2 * MT);  // chunk of 64 units (more waves than chunks: copied twice)
+    long long tt = q / 2;
+    tt = tt < ntt ? tt : ntt - 1;
+    st.x_src[p] = Xf + (tt * (2 * nks) + (q & 1)) * 64;
+    st.x_dst[p] = (unsigned)q * 64;
+  }
+  // the segments of this span: one per row block it touches (spans, nks and hence k0, k1 are multiples of four steps)
+  for (long long s = s_begin; s < s_end;) {
+    const long long rb = s / nks;
+    const unsigned k0 = (unsigned)(s - rb * nks);
+    const unsigned k1 = (unsigned)((s_end - rb * nks) < nks ? (s_end - rb * nks) : nks);
+    s += k1 - k0;
+#pragma unroll
+    for (int i = 0; i < RT; i++) {
+      long long rt = (rb * NW + st.wave) * RT + i;
+      rt = rt < nrt ? rt : nrt - 1;  // clamp: duplicate work, discarded in the epilogue
+      st.a_row[i] = A + (SPARSE ? rt * nks : rt * (2 * nks)) * 64;
+      st.m_row[i] = reinterpret_cast<const uint32_t*>(meta16) + rt * (nks / 4) * 128;
+    }
+    floatx4_t acc[RT][MT];
+#pragma unroll
+    for (int i = 0; i < RT; i++)
+#pragma unroll
+      for (int j = 0; j < MT; j++) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+    __syncthreads();  // the previous segment's reads of the ring are done
+    // k0 is even, so the parity of a step is that of its ring slot
+    StreamRegs<SPARSE, RT> r[NB];
+#pragma unroll
+    for (int q = 0; q < NB - 1; q++) {
+      stream_issue<SPARSE, MT, RT, NW>(st, r[q], sb + q * BUF, k0 + q < k1 ? k0 + q : k1 - 1);
+      sched_fence();
+    }
+    const unsigned trips = (k1 - k0 + NB - 1) / NB;
+    unsigned ks = k0, t = 0;
+    do {  // at least one trip
+#pragma unroll
+      for (int q = 0; q < NB; q++) {
+        if (q & 1)
+          stream_step<DT, SPARSE, MT, RT, NW, NB, 1>(st, r[q], r[(q + NB - 1) % NB], sb + q * BUF, sb + ((q + NB - 1) % NB) * BUF,
+                                                     acc, ks + q, k1);
+        else
+          stream_step<DT, SPARSE, MT, RT, NW, NB, 0>(st, r[q], r[(q + NB - 1) % NB], sb + q * BUF, sb + ((q + NB - 1) % NB) * BUF,
+                                                     acc, ks + q, k1);
+      }
+      ks += NB;
+    } while (++t < trips);
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no DMA into the ring is left in flight
+#endif
+    // the store addresses are formed here, from a lane number the compiler cannot trace back: formed ahead of the
+    // segment loop they would occupy registers all through the multiply loop
+    unsigned lane_e = st.lane;
+    asm volatile("" : "+v"(lane_e));
+    const int c = (int)(lane_e & 15), g = (int)(lane_e >> 4);
+    const bool whole = k0 == 0 && k1 == (unsigned)nks;
+    const long long piece = (long long)blockIdx.x - (rb * nks) / span;
+#pragma unroll
+    for (int i = 0; i < RT; i++) {
+      const long long rt = (rb * NW + st.wave) * RT + i;
+      if (rt >= nrt) continue;
+#pragma unroll
+      for (int j = 0; j < MT; j++) {
+        if (j >= ntt) continue;
+        const long long tk = (long long)j * 16 + c, n = rt * 16 + g * 4;
+        if (whole)
+          store_y4<DT>(Y, M, N, tk, n, acc[i][j]);
+        else
+          *reinterpret_cast<floatx4_t*>(partial + (piece * Mp + tk) * Np + n) = acc[i][j];
+      }
+    }
+  }
+}
+
+template <int DT, int SPARSE, int MT, int RT, int NW, int NB>
+__global__ void __launch_bounds__(NW * 64) k_mm_stream(const uint4* __restrict__ A, const uint16_t* __restrict__ meta16,
+                                                        const uint4* __restrict__ Xf, uint16_t* __restrict__ Y,
+                                                        float* __restrict__ partial, long long M, long long N, long long Mp,
+                                                        long long Np, long long Kp, long long span) {
+  extern __shared__ uint4 s_stream[];  // NB ring buffers of MT * 128 units
+  stream_pipeline<DT, SPARSE, MT, RT, NW, NB>(s_stream, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span);
+}
+
+// ------------------------------------------------------------------------------------------------
 // variant table and host launcher
 // ------------------------------------------------------------------------------------------------
-enum { KIND_WAVE = 0, KIND_KSPLIT = 1, KIND_TILE = 2 };
+enum { KIND_WAVE = 0, KIND_KSPLIT = 1, KIND_TILE = 2, KIND_STREAM = 3 };
 struct Variant {
   const char* name;
   int kind;
@@ -797,6 +1044,11 @@ static const Variant kVariants[] = {
     {"tile_w8_r128_t128", KIND_TILE, 4, 2, 0, 4},         // 128 rows (dense 64) x 128 tokens per workgroup, 8 waves
     {"tile_w8_r128_t128_splitk", KIND_TILE, 4, 2, 1, 4},  // ... with K split over workgroups (M <= 128)
     {"tile_w8_r128_t64_splitk", KIND_TILE, 4, 1, 1, 4},   // 128 rows (dense 64) x 64 tokens, K split (M <= 128)
+    // stream kind: nw waves x rt row tiles per workgroup, all tokens (M <= 128), K split; tt = ring slots
+    {"stream_w8_r1_d3", KIND_STREAM, 1, 4, 1, 8},
+    {"stream_w8_r1_d7", KIND_STREAM, 1, 8, 1, 8},
+    {"stream_w8_r2_d3", KIND_STREAM, 2, 4, 1, 8},
+    {"stream_w8_r2_d5", KIND_STREAM, 2, 6, 1, 8},
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -822,6 +1074,7 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
     if ((long long)var.nw * var.rt * mt * 1024 > 160 * 1024) return false;
   }
   if (var.kind == KIND_TILE && M < 64) return false;
+  if (var.kind == KIND_STREAM && M > 128) return false;
   return true;
 }
 
@@ -831,8 +1084,8 @@ int esp_default_variant(long long M, long long N, long long K, int sparse) {
     const long long nrt = esp_round_up(N, 16) / 16;
     return nrt <= 320 ? 4 : 5;  // ksplit_w16_r1 / ksplit_w16_r2
   }
-  if (M <= 64) return 16;   // tile_w8_r128_t64_splitk
-  if (M <= 128) return 15;  // tile_w8_r128_t128_splitk
+  if (M <= 64) return 19;   // stream_w8_r2_d3
+  if (M <= 128) return 17;  // stream_w8_r1_d3
   // 8-wave tile kernels: the largest macro tile that still gives half of the 256 CUs a tile
   const long long rows = sparse ? 256 : 128;
   const long long nrb = (N + rows - 1) / rows;
@@ -918,6 +1171,68 @@ static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const
       hipLaunchKernelGGL(k_reduce_splits<ESPARSE_F16>, dim3((unsigned)((e + 255) / 256)), dim3(256), 0, st, partial, nsplit, M, N, Mp, Np, Y);
     else
       hipLaunchKernelGGL(k_reduce_splits<ESPARSE_BF16>, dim3((unsigned)((e + 255) / 256)), dim3(256), 0, st, partial, nsplit, M, N, Mp, Np, Y);
+    ESP_HIP(ctx, hipGetLastError());
+  }
+  return ESPARSE_OK;
+}
+
+template <int DT, int SPARSE, int MT, int RT, int NW, int NB>
+static hipError_t launch_stream_kernel(dim3 grid, hipStream_t st, const uint4* A, const uint16_t* meta16, const uint4* Xf, uint16_t* Y,
+                                       float* partial, long long M, long long N, long long Mp, long long Np, long long Kp,
+                                       long long span) {
+  constexpr size_t smem = (size_t)NB * MT * 128 * 16;
+  static bool raised = false;  // once per process: allow the kernel more than the default 64 KiB of dynamic LDS
+  if (smem > 64 * 1024 && !raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_mm_stream<DT, SPARSE, MT, RT, NW, NB>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  hipLaunchKernelGGL((k_mm_stream<DT, SPARSE, MT, RT, NW, NB>), grid, dim3(NW * 64), smem, st, A, meta16, Xf, Y, partial, M, N, Mp, Np,
+                     Kp, span);
+  return hipGetLastError();
+}
+
+// span of the stream kernels: steps per workgroup when `slots` workgroups share nrb row blocks of nks steps.
+// A multiple of four steps, at least 8, and long enough that a row block has at most MAX_SPLIT pieces.
+static long long stream_span(long long nrb, long long nks, long long slots) {
+  long long span = (nrb * nks + slots - 1) / slots;
+  span = std::max<long long>(span, 8);
+  span = std::max<long long>(span, (nks + MAX_SPLIT - 3) / (MAX_SPLIT - 2));  // pieces <= (nks - 1) / span + 2
+  return (span + 3) / 4 * 4;
+}
+
+template <int DT, int SPARSE>
+static int launch_stream(esparse_ctx* ctx, const Variant& v, hipStream_t st, const uint4* A, const uint16_t* meta16, const uint4* Xf,
+                         uint16_t* Y, float* partial, long long M, long long N, long long Mp, long long Np, long long Kp) {
+  const long long nrt = Np / 16, nks = Kp / 64;
+  const long long rows = (long long)v.nw * v.rt;  // row tiles per workgroup
+  const long long nrb = (nrt + rows - 1) / rows;
+  const int mt = Mp <= 16 ? 1 : (Mp <= 32 ? 2 : (Mp <= 64 ? 4 : 8));
+  // one workgroup per CU: measured faster than two with half the span each
+  const long long span = stream_span(nrb, nks, 256);
+  dim3 grid((unsigned)((nrb * nks + span - 1) / span));
+  hipError_t e = hipErrorInvalidValue;
+#define ESP_STREAM(RTv, NWv, NBv)                                                                                           \
+  if (v.rt == RTv && v.nw == NWv && v.tt == NBv)                                                                            \
+  e = (mt == 1)   ? launch_stream_kernel<DT, SPARSE, 1, RTv, NWv, NBv>(grid, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span) \
+      : (mt == 2) ? launch_stream_kernel<DT, SPARSE, 2, RTv, NWv, NBv>(grid, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span) \
+      : (mt == 4) ? launch_stream_kernel<DT, SPARSE, 4, RTv, NWv, NBv>(grid, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span) \
+                  : launch_stream_kernel<DT, SPARSE, 8, RTv, NWv, NBv>(grid, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span)
+  ESP_STREAM(1, 8, 4);
+  ESP_STREAM(1, 8, 8);
+  ESP_STREAM(2, 8, 4);
+  ESP_STREAM(2, 8, 6);
+#undef ESP_STREAM
+  ESP_HIP(ctx, e);
+  if (span % nks != 0) {  // some row block is cut
+    const long long e4 = M * (Np / 4);
+    if (DT == ESPARSE_F16)
+      hipLaunchKernelGGL(k_reduce_pieces<ESPARSE_F16>, dim3((unsigned)((e4 + 255) / 256)), dim3(256), 0, st, partial, M, N, Mp, Np, Y, nks,
+                         span, rows * 16);
+    else
+      hipLaunchKernelGGL(k_reduce_pieces<ESPARSE_BF16>, dim3((unsigned)((e4 + 255) / 256)), dim3(256), 0, st, partial, M, N, Mp, Np, Y, nks,
+                         span, rows * 16);
     ESP_HIP(ctx, hipGetLastError());
   }
   return ESPARSE_OK;
@@ -1041,6 +1356,15 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
                     : launch_tile<ESPARSE_F16, 0>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp);
     return sparse ? launch_tile<ESPARSE_BF16, 1>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp)
                   : launch_tile<ESPARSE_BF16, 0>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp);
+  }
+
+  if (v.kind == KIND_STREAM) {
+    const uint16_t* meta16 = reinterpret_cast<const uint16_t*>(meta_bytes);
+    if (dtype == ESPARSE_F16)
+      return sparse ? launch_stream<ESPARSE_F16, 1>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp)
+                    : launch_stream<ESPARSE_F16, 0>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp);
+    return sparse ? launch_stream<ESPARSE_BF16, 1>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp)
+                  : launch_stream<ESPARSE_BF16, 0>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp);
   }
 
   // ---- wave-tile kinds

@@ -262,6 +262,13 @@ def test_spmm_small_ragged(esp, ctx, M, dtype):
     _spmm_case(esp, ctx, M, 72, 576, dtype, 41)
 
 
+def test_spmm_stream_spans(esp, ctx):
+    """Stream kernels cut the steps of all row blocks into equal spans: a span inside one row block (partial
+    pieces), a span across a row block boundary, and spans holding several whole row blocks (stored directly)."""
+    _spmm_case(esp, ctx, 70, 400, 768, torch.float16, 44)        # 12 steps per row block, spans of 8
+    _spmm_case(esp, ctx, 40, 65536 + 48, 256, torch.bfloat16, 45)  # 4 steps per row block, spans of 8 or more
+
+
 def test_spmm_identity_perm_and_multi_tile(esp, ctx):
     _spmm_case(esp, ctx, 16, 512, 2048, torch.float16, 42, use_perm=False)
     _spmm_case(esp, ctx, 200, 272, 1280, torch.float16, 43)
