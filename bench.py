@@ -299,7 +299,7 @@ def main():
 
     def kernel_name(skey, M):
         v = tuned[f"{skey}/M={M}"][0]
-        return {"ksplit": "k_mm_ksplit", "wave": "k_mm_wave_tile", "tile": "k_mm_tile"}[v.split("_")[0]] + f" [{v}]"
+        return {"ksplit": "k_mm_ksplit", "wave": "k_mm_wave_tile", "tile": "k_mm_tile", "stream": "k_mm_stream"}[v.split("_")[0]] + f" [{v}]"
 
     per_shape = []
     seen = set()
@@ -364,7 +364,7 @@ def main():
         if len(names) < 2:
             continue
         N, K = shapes[skey]
-        for M in [m_ for m_ in M_LIST if m_ <= 64]:
+        for M in [m_ for m_ in M_LIST if tuned[f"{skey}/M={m_}"][0].startswith("ksplit")]:   # one launch for the group
             cnt = len(names)
             X = acts[(stream, M)]
             ctx.stage_activations_group([X] * cnt, [layers[0][n]["perm"] for n in names], layers[0][names[0]]["comp"], ws)
