@@ -34,14 +34,14 @@ HBM_PEAK_GBS = 8000.0
 # `bench.py --counter-probe` and scaled by the same counters' reading for a copy kernel of known size;
 # key (config, M, N, K), value = fetched + written bytes.  The summaries are kept under profiles/.
 MEASURED_TRAFFIC = {
-    (2, 1, 4096, 4096): 19974609, (2, 8, 4096, 4096): 20030503, (2, 32, 4096, 4096): 21278653,
-    (2, 1, 11008, 4096): 51866143, (2, 8, 11008, 4096): 52021023, (2, 32, 11008, 4096): 54076166,
-    (2, 1, 4096, 11008): 53591110, (2, 8, 4096, 11008): 53647089, (2, 32, 4096, 11008): 56664533,
+    (2, 1, 4096, 4096): 19971392, (2, 8, 4096, 4096): 20041705, (2, 32, 4096, 4096): 21276542,
+    (2, 1, 11008, 4096): 51838598, (2, 8, 11008, 4096): 52090577, (2, 32, 11008, 4096): 53581464,
+    (2, 1, 4096, 11008): 53587876, (2, 8, 4096, 11008): 53643855, (2, 32, 4096, 11008): 56672554,
     # group launches (config, M, N, K, members)
-    (2, 1, 4096, 4096, 3): 59895462, (2, 8, 4096, 4096, 3): 60006317, (2, 32, 4096, 4096, 3): 63743589,
-    (2, 1, 11008, 4096, 2): 104096772, (2, 8, 11008, 4096, 2): 104506660, (2, 32, 11008, 4096, 2): 107312110,
-    (3, 512, 5120, 5120): 82745824, (3, 2048, 5120, 5120): 314272462, (3, 512, 13824, 5120): 144935671,
-    (3, 2048, 13824, 5120): 504618024, (3, 512, 5120, 13824): 220277027, (3, 2048, 5120, 13824): 842458894,
+    (2, 1, 4096, 4096, 3): 59835508, (2, 8, 4096, 4096, 3): 60004468, (2, 32, 4096, 4096, 3): 63763073,
+    (2, 1, 11008, 4096, 2): 104041019, (2, 8, 11008, 4096, 2): 104562939, (2, 32, 11008, 4096, 2): 107110709,
+    (3, 512, 5120, 5120): 76809032, (3, 2048, 5120, 5120): 225381167, (3, 512, 13824, 5120): 144959199,
+    (3, 2048, 13824, 5120): 510778932, (3, 512, 5120, 13824): 198251888, (3, 2048, 5120, 13824): 572712129,
 }
 SPARSE_MFMA_PEAK_TFLOPS = 5000.0   # dense-equivalent flops of the 2:4 MFMA path: twice the dense 16-bit peak of 2.5 PFLOP/s
 DEFAULT_LAYERS = {2: 6, 3: 3, 4: 2, 5: 2}   # enough instances that every shape rotates over > 256 MB of weights
@@ -169,6 +169,14 @@ def main():
             GROUPS[-1][0].append(name)
         else:
             GROUPS.append(([name], skey, stream))
+    # a launch of several products fills the chip differently from a single one: its variant is tuned separately
+    for names, skey, _ in GROUPS:
+        if len(names) > 1:
+            N, K = shapes[skey]
+            for M in M_LIST:
+                vs, _ = ctx.tune_group(len(names), M, N, K, dcode, True)
+                vd, _ = ctx.tune_group(len(names), M, N, K, dcode, False)
+                tuned[f"{skey}/M={M}/x{len(names)}"] = [esp.variant_name(vs), esp.variant_name(vd)]
 
     def step_sparse():
         for mats in layers:
@@ -252,7 +260,7 @@ def main():
             if len(names) < 2:
                 continue
             N, K = shapes[skey]
-            for M in [m_ for m_ in M_LIST if m_ <= 64]:
+            for M in [m_ for m_ in M_LIST if tuned[f"{skey}/M={m_}/x{len(names)}"][0].startswith("ksplit")]:
                 cnt = len(names)
                 print(f"counter probe: group of {cnt}, M={M} N={N} K={K}: 1 x group stage, 3 x group sparse product "
                       f"(algorithmic bytes {int(cnt * (1.125 * N * K + 2 * M * N) + 2 * M * K)})", flush=True)
@@ -297,8 +305,8 @@ def main():
             torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / (3 * reps)
 
-    def kernel_name(skey, M):
-        v = tuned[f"{skey}/M={M}"][0]
+    def kernel_name(skey, M, cnt=1):
+        v = tuned[f"{skey}/M={M}" + (f"/x{cnt}" if cnt > 1 else "")][0]
         return {"ksplit": "k_mm_ksplit", "wave": "k_mm_wave_tile", "tile": "k_mm_tile", "stream": "k_mm_stream"}[v.split("_")[0]] + f" [{v}]"
 
     per_shape = []
@@ -364,7 +372,7 @@ def main():
         if len(names) < 2:
             continue
         N, K = shapes[skey]
-        for M in [m_ for m_ in M_LIST if tuned[f"{skey}/M={m_}"][0].startswith("ksplit")]:   # one launch for the group
+        for M in [m_ for m_ in M_LIST if tuned[f"{skey}/M={m_}/x{len(names)}"][0].startswith("ksplit")]:   # one launch for the group
             cnt = len(names)
             X = acts[(stream, M)]
             ctx.stage_activations_group([X] * cnt, [layers[0][n]["perm"] for n in names], layers[0][names[0]]["comp"], ws)
@@ -380,7 +388,7 @@ def main():
             tgp, tgs = kernel_time(gp, 48), kernel_time(gs, 48)
             bytes_alg = cnt * (1.125 * N * K + 2.0 * M * N) + 2.0 * M * K
             per_group.append(dict(layer=skey, members=cnt, N=N, K=K, M=M, count_per_layer=1, bound="hbm",
-                                  kernel=kernel_name(skey, M) + f" x{cnt} in one launch",
+                                  kernel=kernel_name(skey, M, cnt) + f" x{cnt} in one launch",
                                   spmm_kernel_us=round(tgp * 1e6, 2), stage_kernel_us=round(tgs * 1e6, 2),
                                   rotating_weight_mb=round(LAYERS * cnt * 1.125 * N * K / 1e6, 1),
                                   kernel_gbs=round(bytes_alg / tgp / 1e9, 1), frac_hbm_peak=round(bytes_alg / tgp / 1e9 / HBM_PEAK_GBS, 3),

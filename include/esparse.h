@@ -217,6 +217,12 @@ int esparse_dense_gemm_group(esparse_ctx* ctx, int count, const void* const* X, 
  * saved to / restored from a text file (HOST path).  Synchronises; allocates scratch. */
 int esparse_tune(esparse_ctx* ctx, long long M, long long N, long long K, esparse_dtype dtype,
                  int sparse, int* best_variant, float* best_ms);
+/* The same search for launches of `count` products of one shape (esparse_spmm_group, esparse_dense_gemm_group; count in
+ * 1..4): a group fills the chip differently from a single product, so its fastest variant can differ.  Group calls with
+ * variant = -1 use the choice tuned for their count, else the one tuned for the single product, else the default.
+ * In the text file a line may end in the count. */
+int esparse_tune_group(esparse_ctx* ctx, int count, long long M, long long N, long long K, esparse_dtype dtype,
+                       int sparse, int* best_variant, float* best_ms);
 int esparse_tune_save(const esparse_ctx* ctx, const char* path);
 int esparse_tune_load(esparse_ctx* ctx, const char* path);
 

@@ -71,6 +71,7 @@ def load_library():
         "esparse_dense_pack": (i32, [vp, vp, ll, ll, i32, vp]),
         "esparse_dense_gemm": (i32, [vp, vp, ll, vp, ll, ll, i32, vp, vp, sz, i32]),
         "esparse_tune": (i32, [vp, ll, ll, ll, i32, i32, P(i32), P(C.c_float)]),
+        "esparse_tune_group": (i32, [vp, i32, ll, ll, ll, i32, i32, P(i32), P(C.c_float)]),
         "esparse_tune_save": (i32, [vp, C.c_char_p]),
         "esparse_tune_load": (i32, [vp, C.c_char_p]),
     }
@@ -89,7 +90,7 @@ EXPORTED = ["esparse_create", "esparse_destroy", "esparse_set_stream", "esparse_
             "esparse_compressed_size", "esparse_compress", "esparse_spmm_workspace", "esparse_spmm",
             "esparse_stage_activations", "esparse_spmm_staged", "esparse_dense_gemm_staged",
             "esparse_spmm_num_variants", "esparse_spmm_variant_name", "esparse_dense_packed_size",
-            "esparse_dense_pack", "esparse_dense_gemm", "esparse_tune", "esparse_tune_save",
+            "esparse_dense_pack", "esparse_dense_gemm", "esparse_tune", "esparse_tune_group", "esparse_tune_save",
             "esparse_tune_load"]
 
 
@@ -403,6 +404,13 @@ class Context:
         best, ms = C.c_int(-1), C.c_float(0.0)
         self._sync_stream()
         self._check(self._lib.esparse_tune(self._h, M, N, K, dtype, int(sparse), C.byref(best), C.byref(ms)))
+        return best.value, ms.value
+
+    def tune_group(self, count: int, M: int, N: int, K: int, dtype: int = F16, sparse=True):
+        """The same search for launches of `count` products of one shape (spmm_group, dense_gemm_group)."""
+        best, ms = C.c_int(-1), C.c_float(0.0)
+        self._sync_stream()
+        self._check(self._lib.esparse_tune_group(self._h, count, M, N, K, dtype, int(sparse), C.byref(best), C.byref(ms)))
         return best.value, ms.value
 
     def tune_save(self, path: str):

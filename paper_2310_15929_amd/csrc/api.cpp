@@ -255,10 +255,13 @@ static int check_matmul(esparse_ctx* ctx, const void* X, long long M, const void
   return ESPARSE_OK;
 }
 
-static int pick_variant(esparse_ctx* ctx, int sparse, int dtype, long long M, long long N, long long K, int variant) {
+// count = products in the launch: a group call looks for a choice tuned for its size first, then for the single product
+static int pick_variant(esparse_ctx* ctx, int sparse, int dtype, long long M, long long N, long long K, int variant, int count = 1) {
   if (variant >= 0) return variant;
-  auto it = ctx->tuned.find(std::make_tuple(sparse, dtype, M, N, K));
-  if (it != ctx->tuned.end() && esp_variant_applicable(it->second, M, N, K, sparse)) return it->second;
+  for (int c : {count, 1}) {
+    auto it = ctx->tuned.find(std::make_tuple(c, sparse, dtype, M, N, K));
+    if (it != ctx->tuned.end() && esp_variant_applicable(it->second, M, N, K, sparse)) return it->second;
+  }
   return esp_default_variant(M, N, K, sparse);
 }
 
@@ -333,7 +336,7 @@ static int spmm_group_phases(esparse_ctx* ctx, int count, const void* const* X, 
   if (M == 0) return ESPARSE_OK;
   ESP_REQUIRE(ctx, workspace_bytes >= esp_group_workspace_bytes(count, M, N, K), ESPARSE_EWORKSPACE,
               "workspace has %zu bytes, %zu needed", workspace_bytes, esp_group_workspace_bytes(count, M, N, K));
-  const int v = pick_variant(ctx, mode, dtype, M, N, K, variant);
+  const int v = pick_variant(ctx, mode, dtype, M, N, K, variant, count);
   ESP_REQUIRE(ctx, phases == (ESP_PHASE_STAGE | ESP_PHASE_MULTIPLY) || esp_variant_is_decode_kernel(v), ESPARSE_EUNSUPPORTED,
               "the two halves of a group call exist for the decode kernels only");
   ESP_HIP(ctx, hipSetDevice(ctx->device));
@@ -376,7 +379,7 @@ int esparse_dense_gemm_group(esparse_ctx* ctx, int count, const void* const* X, 
               "workspace has %zu bytes, %zu needed", workspace_bytes, esp_group_workspace_bytes(count, M, N, K));
   ESP_HIP(ctx, hipSetDevice(ctx->device));
   return esp_matmul_group_device(ctx, 0, count, X, M, packed_w, nullptr, N, K, dtype, Y, workspace,
-                                 pick_variant(ctx, 0, dtype, M, N, K, variant), ESP_PHASE_STAGE | ESP_PHASE_MULTIPLY);
+                                 pick_variant(ctx, 0, dtype, M, N, K, variant, count), ESP_PHASE_STAGE | ESP_PHASE_MULTIPLY);
 }
 
 int esparse_dense_packed_size(long long N, long long K, size_t* bytes) {
@@ -422,11 +425,12 @@ int esparse_dense_gemm_staged(esparse_ctx* ctx, long long M, const void* packed_
                       ESP_PHASE_MULTIPLY);
 }
 
-int esparse_tune(esparse_ctx* ctx, long long M, long long N, long long K, esparse_dtype dtype, int sparse,
-                 int* best_variant, float* best_ms) {
+static int tune_impl(esparse_ctx* ctx, int count, long long M, long long N, long long K, esparse_dtype dtype, int sparse,
+                     int* best_variant, float* best_ms) {
   if (!ctx) return ESPARSE_EINVAL;
   int rc = check_dtype(ctx, dtype);
   if (rc) return rc;
+  ESP_REQUIRE(ctx, count >= 1 && count <= 4, ESPARSE_EINVAL, "count = %d outside 1..4", count);
   ESP_REQUIRE(ctx, M >= 1 && M < (1ll << 24) && N >= 1 && N < (1ll << 31) && K >= 4 && K < (1ll << 31) && K % 4 == 0,
               ESPARSE_EINVAL, "shape out of range");
   sparse = sparse == 2 ? 2 : (sparse ? 1 : 0);
@@ -437,9 +441,10 @@ int esparse_tune(esparse_ctx* ctx, long long M, long long N, long long K, espars
   // the timed launches rotate over copies of the weight operand, more of them than the caches hold (256 MiB
   // last-level cache): in a model every matrix is read once per step, so the cold time is the one that counts
   const size_t wbytes = ((sparse ? Np * Kp + Np * Kp / 8 : Np * Kp * 2) + 255) / 256 * 256;
-  const int ncopies = (int)std::max<size_t>(2, std::min<size_t>(64, ((size_t)640 << 20) / wbytes + 1));
+  const int ncopies = (int)std::max<size_t>(2 * count, std::min<size_t>(64, ((size_t)640 << 20) / wbytes + count));
+  const size_t ybytes = ((size_t)M * N * 2 + 255) / 256 * 256;
   if (w.alloc(wbytes * ncopies) != hipSuccess || x.alloc((size_t)M * K * 2) != hipSuccess ||
-      y.alloc((size_t)M * N * 2) != hipSuccess || ws.alloc(esp_workspace_bytes(M, N, K)) != hipSuccess)
+      y.alloc(ybytes * count) != hipSuccess || ws.alloc(esp_group_workspace_bytes(count, M, N, K)) != hipSuccess)
     return esp_fail(ctx, ESPARSE_ENOMEM, "scratch allocation for tuning failed");
   ESP_HIP(ctx, hipMemsetAsync(w.p, 0, wbytes * ncopies, ctx->stream));
   ESP_HIP(ctx, hipMemsetAsync(x.p, 0, (size_t)M * K * 2, ctx->stream));
@@ -452,15 +457,26 @@ int esparse_tune(esparse_ctx* ctx, long long M, long long N, long long K, espars
   for (int v = 0; v < esp_num_variants(); v++) {
     if (!esp_variant_applicable(v, M, N, K, sparse)) continue;
     const unsigned char* wbase = reinterpret_cast<const unsigned char*>(w.p);
+    unsigned char* ybase = reinterpret_cast<unsigned char*>(y.p);
+    // launch i reads the weight copies i count, i count + 1, ... (mod ncopies)
+    auto launch = [&](int i) {
+      const void* Xs[4];
+      const void* Ws[4];
+      void* Ys[4];
+      for (int j = 0; j < count; j++) {
+        Xs[j] = x.p;
+        Ws[j] = wbase + (size_t)((i * count + j) % ncopies) * wbytes;
+        Ys[j] = ybase + (size_t)j * ybytes;
+      }
+      if (count == 1) return esp_matmul_device(ctx, sparse, Xs[0], M, Ws[0], nullptr, N, K, dtype, Ys[0], ws.p, v, 3);
+      return esp_matmul_group_device(ctx, sparse, count, Xs, M, Ws, nullptr, N, K, dtype, Ys, ws.p, v, 3);
+    };
     for (int i = 0; i < 3; i++)
-      if ((rc = esp_matmul_device(ctx, sparse, x.p, M, wbase + (size_t)(i % ncopies) * wbytes, nullptr, N, K, dtype, y.p, ws.p, v, 3)))
-        break;
+      if ((rc = launch(i))) break;
     if (rc) break;
     (void)hipEventRecord(e0, ctx->stream);
     for (int i = 0; i < reps; i++)
-      if ((rc = esp_matmul_device(ctx, sparse, x.p, M, wbase + (size_t)((i + 3) % ncopies) * wbytes, nullptr, N, K, dtype, y.p, ws.p, v,
-                                  3)))
-        break;
+      if ((rc = launch(i + 3))) break;
     (void)hipEventRecord(e1, ctx->stream);
     if (rc) break;
     if (hipEventSynchronize(e1) != hipSuccess) {
@@ -479,10 +495,20 @@ int esparse_tune(esparse_ctx* ctx, long long M, long long N, long long K, espars
   (void)hipEventDestroy(e1);
   if (rc) return rc;
   ESP_REQUIRE(ctx, best >= 0, ESPARSE_EUNSUPPORTED, "no variant can run this shape");
-  ctx->tuned[std::make_tuple(sparse, (int)dtype, M, N, K)] = best;
+  ctx->tuned[std::make_tuple(count, sparse, (int)dtype, M, N, K)] = best;
   if (best_variant) *best_variant = best;
   if (best_ms) *best_ms = best_t;
   return ESPARSE_OK;
+}
+
+int esparse_tune(esparse_ctx* ctx, long long M, long long N, long long K, esparse_dtype dtype, int sparse, int* best_variant,
+                 float* best_ms) {
+  return tune_impl(ctx, 1, M, N, K, dtype, sparse, best_variant, best_ms);
+}
+
+int esparse_tune_group(esparse_ctx* ctx, int count, long long M, long long N, long long K, esparse_dtype dtype, int sparse,
+                       int* best_variant, float* best_ms) {
+  return tune_impl(ctx, count, M, N, K, dtype, sparse, best_variant, best_ms);
 }
 
 int esparse_output_error(esparse_ctx* ctx, const void* Yref, const void* Y, long long M, long long N, esparse_dtype dtype,
@@ -504,10 +530,13 @@ int esparse_tune_save(const esparse_ctx* ctx, const char* path) {
   if (!ctx || !path) return ESPARSE_EINVAL;
   FILE* f = fopen(path, "w");
   if (!f) return ESPARSE_EINVAL;
-  fprintf(f, "# sparse dtype M N K variant-name\n");
-  for (const auto& kv : ctx->tuned)
-    fprintf(f, "%d %d %lld %lld %lld %s\n", std::get<0>(kv.first), std::get<1>(kv.first), std::get<2>(kv.first),
-            std::get<3>(kv.first), std::get<4>(kv.first), esp_variant_name(kv.second));
+  fprintf(f, "# sparse dtype M N K variant-name [products per launch, 1 if absent]\n");
+  for (const auto& kv : ctx->tuned) {
+    fprintf(f, "%d %d %lld %lld %lld %s", std::get<1>(kv.first), std::get<2>(kv.first), std::get<3>(kv.first),
+            std::get<4>(kv.first), std::get<5>(kv.first), esp_variant_name(kv.second));
+    if (std::get<0>(kv.first) != 1) fprintf(f, " %d", std::get<0>(kv.first));
+    fprintf(f, "\n");
+  }
   fclose(f);
   return ESPARSE_OK;
 }
@@ -519,12 +548,13 @@ int esparse_tune_load(esparse_ctx* ctx, const char* path) {
   char line[256];
   while (fgets(line, sizeof line, f)) {
     if (line[0] == '#') continue;
-    int sp, dt;
+    int sp, dt, count = 1;
     long long M, N, K;
     char name[128];
-    if (sscanf(line, "%d %d %lld %lld %lld %127s", &sp, &dt, &M, &N, &K, name) != 6) continue;
+    const int got = sscanf(line, "%d %d %lld %lld %lld %127s %d", &sp, &dt, &M, &N, &K, name, &count);
+    if (got < 6 || count < 1 || count > 4) continue;
     for (int v = 0; v < esp_num_variants(); v++)
-      if (!strcmp(name, esp_variant_name(v))) ctx->tuned[std::make_tuple(sp, dt, M, N, K)] = v;
+      if (!strcmp(name, esp_variant_name(v))) ctx->tuned[std::make_tuple(count, sp, dt, M, N, K)] = v;
   }
   fclose(f);
   return ESPARSE_OK;

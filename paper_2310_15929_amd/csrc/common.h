@@ -15,7 +15,7 @@ struct esparse_ctx {
   hipStream_t stream = nullptr;
   std::string err;
   // (sparse, dtype, M, N, K) -> variant chosen by esparse_tune
-  std::map<std::tuple<int, int, long long, long long, long long>, int> tuned;
+  std::map<std::tuple<int, int, int, long long, long long, long long>, int> tuned;  // (products per launch, mode, dtype, M, N, K) -> variant
   int* d_flags = nullptr;     // 64 ints of device scratch for error flags
 };
 

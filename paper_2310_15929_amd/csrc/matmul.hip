@@ -1049,6 +1049,8 @@ static const Variant kVariants[] = {
     {"stream_w8_r1_d7", KIND_STREAM, 1, 8, 1, 8},
     {"stream_w8_r2_d3", KIND_STREAM, 2, 4, 1, 8},
     {"stream_w8_r2_d5", KIND_STREAM, 2, 6, 1, 8},
+    {"ksplit_w8_r6", KIND_KSPLIT, 6, 0, 0, 8},  // M <= 32: 96 rows per workgroup, the activations are re-read by fewer workgroups
+    {"ksplit_w8_r3", KIND_KSPLIT, 3, 0, 0, 8},
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -1128,6 +1130,8 @@ static void launch_ksplit(const Variant& v, hipStream_t st, const KsplitArgs& ar
   else if (v.nw == 16 && v.rt == 3) LAUNCH(3, 16);
   else if (v.nw == 8 && v.rt == 1) LAUNCH(1, 8);
   else if (v.nw == 8 && v.rt == 2) LAUNCH(2, 8);
+  else if (v.nw == 8 && v.rt == 6) LAUNCH(6, 8);
+  else if (v.nw == 8 && v.rt == 3) LAUNCH(3, 8);
   else LAUNCH(4, 8);
 #undef LAUNCH
 }

@@ -369,6 +369,18 @@ def test_tune_picks_a_variant_and_persists(esp, ctx, tmp_path):
     c2 = esp.Context(0)
     c2.tune_load(p)
     assert esp.variant_name(best) in open(p).read()
+    # a choice for launches of three products of the shape is kept beside the single one and survives the file
+    bg, msg = ctx.tune_group(3, 16, 512, 1024, esp.F16, sparse=True)
+    assert 0 <= bg < esp.num_variants() and msg > 0
+    ctx.tune_save(p)
+    lines = [l.split() for l in open(p).read().splitlines() if not l.startswith("#")]
+    assert ["1", "0", "16", "512", "1024", esp.variant_name(best)] in lines
+    assert ["1", "0", "16", "512", "1024", esp.variant_name(bg), "3"] in lines
+    c3 = esp.Context(0)
+    c3.tune_load(p)
+    q = str(tmp_path / "again.txt")
+    c3.tune_save(q)
+    assert sorted(open(q).read().splitlines()) == sorted(open(p).read().splitlines())
 
 
 # ---------------------------------------------------------------- eq. 4 report

@@ -78,6 +78,8 @@ def test_argument_errors_need_no_gpu():
     assert lib.esparse_spmm_group_workspace(3, 8, 512, 512, C.byref(nb)) == 0 and nb.value >= 65536 + 3 * 16 * 512 * 2
     assert lib.esparse_spmm_group_workspace(0, 8, 512, 512, C.byref(nb)) == -1
     assert lib.esparse_output_error(None, None, None, 4, 4, 0, None, None) == -1        # null context
+    assert lib.esparse_tune_group(ctx._h, 0, 16, 512, 512, 0, 1, None, None) == -1       # count outside 1..4
+    assert lib.esparse_tune_group(ctx._h, 5, 16, 512, 512, 0, 1, None, None) == -1
 
 
 def test_tune_table_text_roundtrip(tmp_path):
@@ -88,6 +90,13 @@ def test_tune_table_text_roundtrip(tmp_path):
     q = tmp_path / "u.txt"
     ctx.tune_save(str(q))
     assert "1 0 16 512 512 " + esp.variant_name(1) in q.read_text()
+    # a trailing count marks a choice for group launches; lines without it are for single products
+    p.write_text("1 0 16 512 512 %s 3\n1 0 16 512 512 %s\n" % (esp.variant_name(4), esp.variant_name(1)))
+    c2 = esp.Context(0)
+    c2.tune_load(str(p))
+    c2.tune_save(str(q))
+    body = [l for l in q.read_text().splitlines() if not l.startswith("#")]
+    assert sorted(body) == sorted(["1 0 16 512 512 %s 3" % esp.variant_name(4), "1 0 16 512 512 %s" % esp.variant_name(1)])
 
 
 def test_missing_library_fails_loudly(monkeypatch):
