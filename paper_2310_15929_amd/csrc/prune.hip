@@ -14,6 +14,7 @@
 #include <cmath>
 #include <cstring>
 #include <numeric>
+#include <thread>
 
 #include "common.h"
 
@@ -49,30 +50,71 @@ static inline float from_ordered_bits(unsigned int o) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// pass A: per-channel min / max.  grid (ceil(K/512), row chunks), block 256; thread <-> 2 channels
+// pass A: per-channel min / max.  block 256 = 8 row lanes x 32 column lanes of CPL channels each
+// (CPL = 8: 16-byte loads, needs K % 8 == 0; CPL = 2 otherwise); grid (ceil(K / (32 CPL)), row chunks).
+// Four rows are in flight per thread; the row lanes meet in LDS, one atomic pair per channel and block.
 // ------------------------------------------------------------------------------------------------
-template <int DT>
+template <int DT, int CPL>
 __global__ void __launch_bounds__(256) k_minmax(const uint16_t* __restrict__ X, long long T, long long K,
                                                  long long rows_per_block, unsigned int* __restrict__ omin,
                                                  unsigned int* __restrict__ omax) {
-  long long c = ((long long)blockIdx.x * 256 + threadIdx.x) * 2;
-  if (c >= K) return;
-  long long r0 = (long long)blockIdx.y * rows_per_block;
-  long long r1 = r0 + rows_per_block < T ? r0 + rows_per_block : T;
-  float lo0 = INFINITY, hi0 = -INFINITY, lo1 = INFINITY, hi1 = -INFINITY;
-  for (long long r = r0; r < r1; r++) {
-    uint32_t two = *reinterpret_cast<const uint32_t*>(X + r * K + c);
-    float a = esp_to_float<DT>((uint16_t)(two & 0xffffu)), b = esp_to_float<DT>((uint16_t)(two >> 16));
-    lo0 = fminf(lo0, a);
-    hi0 = fmaxf(hi0, a);
-    lo1 = fminf(lo1, b);
-    hi1 = fmaxf(hi1, b);
+  __shared__ float s_lo[8][32 * CPL + 1], s_hi[8][32 * CPL + 1];
+  const int tid = threadIdx.x, cl = tid & 31, rl = tid >> 5;
+  const long long c = ((long long)blockIdx.x * 32 + cl) * CPL;
+  const long long r0 = (long long)blockIdx.y * rows_per_block;
+  const long long r1 = r0 + rows_per_block < T ? r0 + rows_per_block : T;
+  float lo[CPL], hi[CPL];
+#pragma unroll
+  for (int j = 0; j < CPL; j++) {
+    lo[j] = INFINITY;
+    hi[j] = -INFINITY;
   }
-  if (r1 > r0) {
-    atomicMin(&omin[c], ordered_bits(lo0));
-    atomicMax(&omax[c], ordered_bits(hi0));
-    atomicMin(&omin[c + 1], ordered_bits(lo1));
-    atomicMax(&omax[c + 1], ordered_bits(hi1));
+  if (c < K) {
+    for (long long r = r0 + rl; r < r1; r += 32) {
+      uint32_t w[4][CPL / 2];
+#pragma unroll
+      for (int u = 0; u < 4; u++) {
+        const long long rr = r + 8 * u < r1 ? r + 8 * u : r;  // past the end: the first row again (no effect on min / max)
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(X + rr * K + c);
+        if (CPL == 8) {
+          const uint4 v = *reinterpret_cast<const uint4*>(src);
+          w[u][0] = v.x;
+          w[u][1 % (CPL / 2)] = v.y;
+          w[u][2 % (CPL / 2)] = v.z;
+          w[u][3 % (CPL / 2)] = v.w;
+        } else {
+          w[u][0] = *src;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; u++)
+#pragma unroll
+        for (int j = 0; j < CPL; j++) {
+          const float x = esp_to_float<DT>((uint16_t)(w[u][j / 2] >> (16 * (j & 1))));
+          lo[j] = fminf(lo[j], x);
+          hi[j] = fmaxf(hi[j], x);
+        }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < CPL; j++) {
+    s_lo[rl][cl * CPL + j] = lo[j];
+    s_hi[rl][cl * CPL + j] = hi[j];
+  }
+  __syncthreads();
+  for (int i = tid; i < 32 * CPL; i += 256) {
+    const long long ch = (long long)blockIdx.x * 32 * CPL + i;
+    if (ch >= K || r1 <= r0) continue;
+    float a = s_lo[0][i], b = s_hi[0][i];
+#pragma unroll
+    for (int q = 1; q < 8; q++) {
+      a = fminf(a, s_lo[q][i]);
+      b = fmaxf(b, s_hi[q][i]);
+    }
+    if (a <= b) {  // some row lane saw the channel
+      atomicMin(&omin[ch], ordered_bits(a));
+      atomicMax(&omax[ch], ordered_bits(b));
+    }
   }
 }
 
@@ -103,8 +145,15 @@ __global__ void __launch_bounds__(256) k_hist_sumsq(const uint16_t* __restrict__
     const double nb = (double)bins;
     long long r0 = (long long)blockIdx.y * rows_per_block;
     long long r1 = r0 + rows_per_block < T ? r0 + rows_per_block : T;
-    for (long long r = r0 + rl; r < r1; r += 8) {
-      uint32_t two = *reinterpret_cast<const uint32_t*>(X + r * K + c);
+    constexpr int ROWS = 8;  // rows in flight per thread: the loop is bound by the latency of its loads otherwise
+    for (long long rb = r0 + rl; rb < r1; rb += 8 * ROWS) {
+     uint32_t ahead[ROWS];
+#pragma unroll
+     for (int u = 0; u < ROWS; u++) ahead[u] = *reinterpret_cast<const uint32_t*>(X + (rb + 8 * u < r1 ? rb + 8 * u : rb) * K + c);
+#pragma unroll
+     for (int u = 0; u < ROWS; u++) {
+      if (rb + 8 * u >= r1) break;
+      const uint32_t two = ahead[u];
       double x[2] = {(double)esp_to_float<DT>((uint16_t)(two & 0xffffu)), (double)esp_to_float<DT>((uint16_t)(two >> 16))};
 #pragma unroll
       for (int h = 0; h < 2; h++) {
@@ -129,6 +178,7 @@ __global__ void __launch_bounds__(256) k_hist_sumsq(const uint16_t* __restrict__
           }
         }
       }
+     }
     }
   }
   __syncthreads();
@@ -202,12 +252,22 @@ int esp_stats_device(esparse_ctx* ctx, const void* calib, long long T, long long
   const uint16_t* X = reinterpret_cast<const uint16_t*>(calib);
   std::vector<float> hmin((size_t)K), hmax((size_t)K);
   if (ir) {
-    long long rpb = std::max<long long>(64, (T + 63) / 64);
-    dim3 grid((unsigned)((K + 511) / 512), (unsigned)((T + rpb - 1) / rpb));
-    if (dtype == ESPARSE_F16)
-      hipLaunchKernelGGL(k_minmax<ESPARSE_F16>, grid, dim3(256), 0, st, X, T, K, rpb, dmin.as<unsigned int>(), dmax.as<unsigned int>());
-    else
-      hipLaunchKernelGGL(k_minmax<ESPARSE_BF16>, grid, dim3(256), 0, st, X, T, K, rpb, dmin.as<unsigned int>(), dmax.as<unsigned int>());
+    const int cpl = K % 8 == 0 ? 8 : 2;  // channels per lane: 16-byte loads where the rows allow them
+    const long long gx = (K + 32 * cpl - 1) / (32 * cpl);
+    const long long nchunk = std::max<long long>(1, std::min<long long>(T / 64, 4096 / gx + 1));  // about 4096 workgroups
+    long long rpb = (T + nchunk - 1) / nchunk;
+    rpb = (rpb + 31) / 32 * 32;
+    dim3 grid((unsigned)gx, (unsigned)((T + rpb - 1) / rpb));
+#define ESP_MINMAX(DTv, CPLv) \
+  hipLaunchKernelGGL((k_minmax<DTv, CPLv>), grid, dim3(256), 0, st, X, T, K, rpb, dmin.as<unsigned int>(), dmax.as<unsigned int>())
+    if (dtype == ESPARSE_F16) {
+      if (cpl == 8) ESP_MINMAX(ESPARSE_F16, 8);
+      else ESP_MINMAX(ESPARSE_F16, 2);
+    } else {
+      if (cpl == 8) ESP_MINMAX(ESPARSE_BF16, 8);
+      else ESP_MINMAX(ESPARSE_BF16, 2);
+    }
+#undef ESP_MINMAX
     ESP_HIP(ctx, hipGetLastError());
     std::vector<unsigned int> omin((size_t)K), omax((size_t)K);
     ESP_HIP(ctx, hipMemcpyAsync(omin.data(), dmin.p, K * 4, hipMemcpyDeviceToHost, st));
@@ -255,18 +315,26 @@ int esp_stats_device(esparse_ctx* ctx, const void* calib, long long T, long long
   if (ir) {
     // eq. 1: IR_c = - sum_k p_k ln p_k, ascending k, empty bins skipped
     ir->assign((size_t)K, 0.0);
-    for (long long c = 0; c < K; c++) {
-      double acc = 0.0;
-      for (int k = 0; k < bins; k++) {
-        unsigned int nk = hist[(size_t)c * bins + k];
-        if (nk) {
-          double p = (double)nk / (double)T;
-          double t = p * std::log(p);
-          acc = acc + t;
+    auto entropy_of = [&](long long c0, long long c1) {
+      for (long long c = c0; c < c1; c++) {
+        double acc = 0.0;
+        for (int k = 0; k < bins; k++) {
+          unsigned int nk = hist[(size_t)c * bins + k];
+          if (nk) {
+            double p = (double)nk / (double)T;
+            double t = p * std::log(p);
+            acc = acc + t;
+          }
         }
+        (*ir)[c] = -acc;
       }
-      (*ir)[c] = -acc;
-    }
+    };
+    // K * bins logarithms on the host (the host's log is the one the result is defined by): channels are independent
+    const int nthr = (int)std::max<long long>(1, std::min<long long>(8, K * bins / 65536));
+    std::vector<std::thread> pool;
+    for (int i = 1; i < nthr; i++) pool.emplace_back(entropy_of, K * i / nthr, K * (i + 1) / nthr);
+    entropy_of(0, K / nthr);
+    for (auto& th : pool) th.join();
   }
   if (am) {
     // eq. 2: AM_c = sqrt(exact sum of squares rounded once)
