@@ -134,17 +134,26 @@ struct KsplitArgs {
   uint16_t* Y[ESP_MAX_GROUP];
 };
 
-__global__ void __launch_bounds__(256) k_gather_x(GatherArgs args, long long M, long long K, long long Kp, long long units) {
+// mc > 0 (at most 16 tokens): a second, compact copy follows the fragment-major one (units [units, units + mc Kp / 8)):
+// unit (8-channel unit) * mc + token for tokens 0 .. mc - 1 only - the decode kernels then load the real tokens'
+// 16 bytes instead of a 16-token tile that is mostly padding.
+__global__ void __launch_bounds__(256) k_gather_x(GatherArgs args, long long M, long long K, long long Kp, long long units, int mc) {
   const uint16_t* __restrict__ X = args.X[blockIdx.y];
   const int32_t* __restrict__ perm = args.perm[blockIdx.y];
   uint4* __restrict__ Xf = args.Xf[blockIdx.y];
   long long u = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (u >= units) return;
-  const int lane = (int)(u & 63);
-  const long long ns = Kp / 32;
-  const long long s = (u >> 6) % ns, tt = (u >> 6) / ns;
-  const long long t = tt * 16 + (lane & 15);
-  const long long k0 = s * 32 + (lane >> 4) * 8;
+  if (u >= units + (long long)mc * (Kp / 8)) return;
+  long long t, k0;
+  if (u >= units) {
+    t = (u - units) % mc;
+    k0 = ((u - units) / mc) * 8;
+  } else {
+    const int lane = (int)(u & 63);
+    const long long ns = Kp / 32;
+    const long long s = (u >> 6) % ns, tt = (u >> 6) / ns;
+    t = tt * 16 + (lane & 15);
+    k0 = s * 32 + (lane >> 4) * 8;
+  }
   uint16_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   if (t < M && k0 < K) {
     const uint16_t* xr = X + t * K;
@@ -413,7 +422,7 @@ __global__ void __launch_bounds__(256) k_mm_wave_tile(const uint4* __restrict__ 
 // ------------------------------------------------------------------------------------------------
 template <int DT, int SPARSE, int MT, int RT, int NW>
 __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long long M, long long N, long long Mp, long long Np,
-                                                        long long Kp) {
+                                                        long long Kp, int mc) {
   const uint4* __restrict__ A = args.A[blockIdx.y];
   const uint16_t* __restrict__ meta16 = args.meta16[blockIdx.y];
   const uint4* __restrict__ Xf = args.Xf[blockIdx.y];
@@ -470,11 +479,21 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long lon
           a2[u][i] = A[(rts[i] * (2 * nks) + 2 * kk[u] + 1) * 64 + lane];
         }
       }
+      if (MT == 1 && mc) {
+        // compact activations (at most 16 tokens): lane (g, c) holds token c's channels 8 g .. 8 g + 7 of each half step
+        const uint4 zero = {0u, 0u, 0u, 0u};
+        const int c = lane & 15, g = lane >> 4;
+        const bool live = c < mc;
+        const uint4* Xc = Xf + Kp * 2;  // behind the 16 x Kp fragment-major copy
+        b0[u][0] = live ? Xc[((2 * kk[u]) * 4 + g) * mc + c] : zero;
+        b1[u][0] = live ? Xc[((2 * kk[u] + 1) * 4 + g) * mc + c] : zero;
+      } else {
 #pragma unroll
-      for (int j = 0; j < MT; j++) {
-        const long long tt = (j < ntt) ? j : ntt - 1;
-        b0[u][j] = Xf[(tt * (2 * nks) + 2 * kk[u]) * 64 + lane];
-        b1[u][j] = Xf[(tt * (2 * nks) + 2 * kk[u] + 1) * 64 + lane];
+        for (int j = 0; j < MT; j++) {
+          const long long tt = (j < ntt) ? j : ntt - 1;
+          b0[u][j] = Xf[(tt * (2 * nks) + 2 * kk[u]) * 64 + lane];
+          b1[u][j] = Xf[(tt * (2 * nks) + 2 * kk[u] + 1) * 64 + lane];
+        }
       }
     }
     if (SPARSE == 2) {
@@ -1096,10 +1115,22 @@ int esp_default_variant(long long M, long long N, long long K, int sparse) {
   return 14;                                       // tile_w8_r128_t128
 }
 
+// tokens of the compact copy of the staged activations (0: none), written when there are at most 16 tokens
+static int compact_tokens(long long M) {
+  if (M > 16) return 0;
+  int mc = 1;
+  while (mc < M) mc *= 2;
+  return mc;
+}
+// bytes of one staged activation matrix: the fragment-major form and, behind it, the compact copy
+static size_t staged_bytes(long long M, long long K) {
+  const size_t Mp = (size_t)esp_round_up(M, 16), Kp = (size_t)esp_round_up(K, 256);
+  return (Mp + (size_t)compact_tokens(M)) * Kp * 2;  // a multiple of 512
+}
+
 size_t esp_workspace_bytes(long long M, long long N, long long K) {
-  const size_t Mp = (size_t)esp_round_up(M, 16), Np = (size_t)esp_round_up(N, 16), Kp = (size_t)esp_round_up(K, 256);
-  size_t bytes = WS_HEADER_BYTES + Mp * Kp * 2;
-  bytes = (bytes + 255) / 256 * 256;
+  const size_t Mp = (size_t)esp_round_up(M, 16), Np = (size_t)esp_round_up(N, 16);
+  size_t bytes = WS_HEADER_BYTES + staged_bytes(M, K);
   if (M <= 128) bytes += (size_t)MAX_SPLIT * Mp * Np * 4;
   return bytes;
 }
@@ -1120,11 +1151,11 @@ static void launch_wave_tile(const Variant& v, dim3 grid, hipStream_t st, const 
 
 template <int DT, int SPARSE, int MT>
 static void launch_ksplit(const Variant& v, hipStream_t st, const KsplitArgs& args, int count, long long M, long long N, long long Mp,
-                          long long Np, long long Kp) {
+                          long long Np, long long Kp, int mc) {
   const long long nrt = Np / 16;
   dim3 grid((unsigned)((nrt + v.rt - 1) / v.rt), (unsigned)count);
   const size_t smem = (size_t)v.nw * v.rt * MT * 64 * 16;
-#define LAUNCH(R, W) hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp)
+#define LAUNCH(R, W) hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp, mc)
   if (v.nw == 16 && v.rt == 1) LAUNCH(1, 16);
   else if (v.nw == 16 && v.rt == 2) LAUNCH(2, 16);
   else if (v.nw == 16 && v.rt == 3) LAUNCH(3, 16);
@@ -1269,7 +1300,7 @@ static hipError_t launch_gather_rows(hipStream_t st, const uint16_t* X, const in
 }
 
 static int stage_activations(esparse_ctx* ctx, const void* X, const int32_t* perm, long long M, long long K, long long Mp,
-                             long long Kp, uint4* Xf) {
+                             long long Kp, uint4* Xf, int mc) {
   const uint16_t* Xh = reinterpret_cast<const uint16_t*>(X);
   const int tok = (M >= 64 && K % 8 == 0) ? gather_rows_tok(Mp, K) : 0;
   if (tok) {
@@ -1283,12 +1314,12 @@ static int stage_activations(esparse_ctx* ctx, const void* X, const int32_t* per
     }
     return ESPARSE_OK;
   }
-  const long long units = Mp * Kp / 8;
+  const long long units = Mp * Kp / 8, all = units + (long long)mc * (Kp / 8);
   GatherArgs ga = {};
   ga.X[0] = Xh;
   ga.perm[0] = perm;
   ga.Xf[0] = Xf;
-  hipLaunchKernelGGL(k_gather_x, dim3((unsigned)((units + 255) / 256), 1), dim3(256), 0, ctx->stream, ga, M, K, Kp, units);
+  hipLaunchKernelGGL(k_gather_x, dim3((unsigned)((all + 255) / 256), 1), dim3(256), 0, ctx->stream, ga, M, K, Kp, units, mc);
   ESP_HIP(ctx, hipGetLastError());
   return ESPARSE_OK;
 }
@@ -1296,10 +1327,11 @@ static int stage_activations(esparse_ctx* ctx, const void* X, const int32_t* per
 // the decode kernels on `count` products of one shape: members share M, N, K; ka holds their operands
 static int launch_ksplit_any(esparse_ctx* ctx, const Variant& v, int sparse, int dtype, KsplitArgs ka, int count, long long M,
                              long long N, long long Np, long long Kp) {
+  const int mc = compact_tokens(M);
   hipStream_t st = ctx->stream;
   const long long nks = Kp / 64;
   for (long long t0 = 0; t0 < M; t0 += 64) {  // more than 64 tokens (4:8 only): 64 at a time
-    const long long mc = (M - t0) < 64 ? (M - t0) : 64, mcp = esp_round_up(mc, 16);
+    const long long mcur = (M - t0) < 64 ? (M - t0) : 64, mcp = esp_round_up(mcur, 16);
     KsplitArgs kc = ka;
     for (int i = 0; i < count; i++) {
       kc.Xf[i] = ka.Xf[i] + (t0 / 16) * (2 * nks) * 64;
@@ -1307,9 +1339,9 @@ static int launch_ksplit_any(esparse_ctx* ctx, const Variant& v, int sparse, int
     }
 #define ESP_KSPLIT(DTv, SPv)                                                          \
   do {                                                                                \
-    if (mcp == 16) launch_ksplit<DTv, SPv, 1>(v, st, kc, count, mc, N, mcp, Np, Kp);  \
-    else if (mcp == 32) launch_ksplit<DTv, SPv, 2>(v, st, kc, count, mc, N, mcp, Np, Kp); \
-    else launch_ksplit<DTv, SPv, 4>(v, st, kc, count, mc, N, mcp, Np, Kp);            \
+    if (mcp == 16) launch_ksplit<DTv, SPv, 1>(v, st, kc, count, mcur, N, mcp, Np, Kp, mc);  \
+    else if (mcp == 32) launch_ksplit<DTv, SPv, 2>(v, st, kc, count, mcur, N, mcp, Np, Kp, 0); \
+    else launch_ksplit<DTv, SPv, 4>(v, st, kc, count, mcur, N, mcp, Np, Kp, 0);            \
   } while (0)
     if (dtype == ESPARSE_F16) {
       if (sparse == 2) ESP_KSPLIT(ESPARSE_F16, 2);
@@ -1332,8 +1364,7 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
   const long long Mp = esp_round_up(M, 16), Np = esp_round_up(N, 16), Kp = esp_round_up(K, 256);
   unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
   uint4* Xf = reinterpret_cast<uint4*>(ws + WS_HEADER_BYTES);
-  size_t xbytes = ((size_t)Mp * Kp * 2 + 255) / 256 * 256;
-  float* partial = reinterpret_cast<float*>(ws + WS_HEADER_BYTES + xbytes);
+  float* partial = reinterpret_cast<float*>(ws + WS_HEADER_BYTES + staged_bytes(M, K));
   uint16_t* Y = reinterpret_cast<uint16_t*>(Yv);
   const uint4* A = reinterpret_cast<const uint4*>(w);
   const unsigned char* meta_bytes = sparse ? reinterpret_cast<const unsigned char*>(w) + (size_t)Np * Kp : nullptr;
@@ -1341,7 +1372,7 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
   const Variant& v = kVariants[variant];
   const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
   int rc;
-  if ((phases & ESP_PHASE_STAGE) && (rc = stage_activations(ctx, X, perm, M, K, Mp, Kp, Xf))) return rc;
+  if ((phases & ESP_PHASE_STAGE) && (rc = stage_activations(ctx, X, perm, M, K, Mp, Kp, Xf, compact_tokens(M)))) return rc;
   if (!(phases & ESP_PHASE_MULTIPLY)) return ESPARSE_OK;
 
   if (v.kind == KIND_KSPLIT) {
@@ -1408,9 +1439,7 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
 // several products of one shape
 // ------------------------------------------------------------------------------------------------
 size_t esp_group_workspace_bytes(int count, long long M, long long N, long long K) {
-  const size_t Mp = (size_t)esp_round_up(M, 16), Kp = (size_t)esp_round_up(K, 256);
-  const size_t xbytes = (Mp * Kp * 2 + 255) / 256 * 256;
-  return std::max(esp_workspace_bytes(M, N, K), (size_t)WS_HEADER_BYTES + (size_t)count * xbytes);
+  return std::max(esp_workspace_bytes(M, N, K), (size_t)WS_HEADER_BYTES + (size_t)count * staged_bytes(M, K));
 }
 
 int esp_matmul_group_device(esparse_ctx* ctx, int sparse, int count, const void* const* X, long long M, const void* const* w,
@@ -1429,7 +1458,7 @@ int esp_matmul_group_device(esparse_ctx* ctx, int sparse, int count, const void*
   }
   const long long Mp = esp_round_up(M, 16), Np = esp_round_up(N, 16), Kp = esp_round_up(K, 256);
   unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
-  const size_t xbytes = ((size_t)Mp * Kp * 2 + 255) / 256 * 256;
+  const size_t xbytes = staged_bytes(M, K);
   GatherArgs ga = {};
   KsplitArgs ka = {};
   for (int i = 0; i < count; i++) {
@@ -1447,8 +1476,10 @@ int esp_matmul_group_device(esparse_ctx* ctx, int sparse, int count, const void*
     }
   }
   if (phases & ESP_PHASE_STAGE) {
-    const long long units = Mp * Kp / 8;
-    hipLaunchKernelGGL(k_gather_x, dim3((unsigned)((units + 255) / 256), (unsigned)count), dim3(256), 0, ctx->stream, ga, M, K, Kp, units);
+    const int mc = compact_tokens(M);
+    const long long units = Mp * Kp / 8, all = units + (long long)mc * (Kp / 8);
+    hipLaunchKernelGGL(k_gather_x, dim3((unsigned)((all + 255) / 256), (unsigned)count), dim3(256), 0, ctx->stream, ga, M, K, Kp, units,
+                       mc);
     ESP_HIP(ctx, hipGetLastError());
   }
   if (!(phases & ESP_PHASE_MULTIPLY)) return ESPARSE_OK;
