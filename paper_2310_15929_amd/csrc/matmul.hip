@@ -619,9 +619,17 @@ __device__ __forceinline__ void tile_load_a(TileState<SPARSE, TR, TC, NWC>& st, 
   }
 }
 
-template <int DT, int SPARSE, int TR, int TC, int NWC>
-__device__ __forceinline__ void tile_multiply(TileState<SPARSE, TR, TC, NWC>& st, const TileRegs<SPARSE, TR>& r, const uint4* sb,
-                                              unsigned k) {
+// the B operand (two 16-byte halves of a 64-channel step) of one token tile
+struct TileB {
+  uint4 b0, b1;
+};
+
+// multiplies of token tiles J0 .. J1 - 1 of stage k.  On entry `bq` holds the B operand of tile J0; the operand of
+// the next tile is read from LDS while a tile is multiplied (from `sb` for tiles of this stage; after the last tile
+// of the stage, from tile 0 of `sb_next`, the next stage's buffer - if NEXT), and `bq` holds it on return.
+template <int DT, int SPARSE, int TR, int TC, int NWC, int J0, int J1, bool NEXT>
+__device__ __forceinline__ void tile_multiply(TileState<SPARSE, TR, TC, NWC>& st, const TileRegs<SPARSE, TR>& r, TileB& bq,
+                                              const uint4* sb, const uint4* sb_next, unsigned k) {
   int idx[TR];
   if (SPARSE) {
     const unsigned sh = (k & 1u) * 16u;  // the word holds the index halves of an even and an odd stage
@@ -629,26 +637,27 @@ __device__ __forceinline__ void tile_multiply(TileState<SPARSE, TR, TC, NWC>& st
     for (int i = 0; i < TR; i++) idx[i] = (int)(r.m[i] >> sh);
   }
   const uint4* b = sb + (st.wc * TC) * 128 + st.lane;
-  // B operands are read one token tile ahead of the multiplies that use them
-  uint4 b0 = b[0], b1 = b[64];
+  const uint4* bn = sb_next + (st.wc * TC) * 128 + st.lane;
 #pragma unroll
-  for (int j = 0; j < TC; j++) {
-    uint4 n0 = b0, n1 = b1;
+  for (int j = J0; j < J1; j++) {
+    TileB nx = bq;
     if (j + 1 < TC) {
-      n0 = b[(j + 1) * 128];
-      n1 = b[(j + 1) * 128 + 64];
+      nx.b0 = b[(j + 1) * 128];
+      nx.b1 = b[(j + 1) * 128 + 64];
+    } else if (NEXT) {
+      nx.b0 = bn[0];
+      nx.b1 = bn[64];
     }
 #pragma unroll
     for (int i = 0; i < TR; i++) {
       if (SPARSE) {
-        st.acc[i][j] = smfmac16<DT, 0>(r.a[i], b0, b1, st.acc[i][j], idx[i]);
+        st.acc[i][j] = smfmac16<DT, 0>(r.a[i], bq.b0, bq.b1, st.acc[i][j], idx[i]);
       } else {
-        st.acc[i][j] = mfma16<DT>(r.a[2 * i], b0, st.acc[i][j]);
-        st.acc[i][j] = mfma16<DT>(r.a[2 * i + 1], b1, st.acc[i][j]);
+        st.acc[i][j] = mfma16<DT>(r.a[2 * i], bq.b0, st.acc[i][j]);
+        st.acc[i][j] = mfma16<DT>(r.a[2 * i + 1], bq.b1, st.acc[i][j]);
       }
     }
-    b0 = n0;
-    b1 = n1;
+    bq = nx;
   }
 }
 
@@ -666,41 +675,58 @@ __device__ __forceinline__ void tile_arrive() {
 #endif
 }
 
-// One pipeline stage k.  On entry the wave holds the A side of stage k in `cur`; the LDS buffers hold
-// B(k) (b_cur), A(k+1) (a_nxt / m_nxt) and, landed or landing, B(k+1) and A(k+2).  The stage
+// One pipeline stage k.  On entry the wave holds the A side of stage k in `cur` and the B operand of its first
+// token tile in `bq`; the LDS buffers hold B(k) (b_cur), A(k+1) (a_nxt / m_nxt) and, landed or landing, B(k+1)
+// (b_nxt) and A(k+2).  The stage
 //   - issues the DMA of B(k+2) into the buffer B(k-1) was in and of A(k+3) into the buffer A(k) was in,
 //   - copies A(k+1) from LDS to `nxt` (off the critical path: those registers are used one stage on),
-//   - multiplies stage k: B operands stream from LDS one token tile ahead,
-//   - waits for the DMA issued in stage k-1 (B(k+1), A(k+2)) and meets the other waves.
-// After a barrier a wave can thus start multiplying as soon as its first B operand is read.
+//   - multiplies all token tiles but the last, B operands streaming from LDS one token tile ahead,
+//   - waits for the DMA issued in stage k-1 (B(k+1), A(k+2)) and meets the other waves,
+//   - reads the first B operand of stage k+1 and, while that read is under way, multiplies the last token tile:
+//     the matrix pipe has work across the barrier and the LDS latency behind it.
+// With fewer than four token tiles per wave holding one back leaves too little ahead of the barrier to spread the
+// DMA over (measured slower): all tiles are multiplied first and the next stage's operand is read after the barrier.
 template <int DT, int SPARSE, int TR, int TC, int NWC>
 __device__ __forceinline__ void tile_stage(TileState<SPARSE, TR, TC, NWC>& st, const TileRegs<SPARSE, TR>& cur,
-                                           TileRegs<SPARSE, TR>& nxt, const uint4* b_cur, const uint4* a_nxt,
-                                           const uint32_t* m_nxt, uint4* b_pre, uint4* a_pre, uint32_t* m_pre, unsigned k) {
+                                           TileRegs<SPARSE, TR>& nxt, TileB& bq, const uint4* b_cur, const uint4* b_nxt,
+                                           const uint4* a_nxt, const uint32_t* m_nxt, uint4* b_pre, uint4* a_pre, uint32_t* m_pre,
+                                           unsigned k) {
   using State = TileState<SPARSE, TR, TC, NWC>;
   constexpr int DMA = State::BCOPIES + (SPARSE ? 2 : 1) * State::ACOPIES;
-  constexpr int DPJ = (DMA + TC - 1) / TC;                   // DMA operations issued per token tile
+  constexpr bool STRADDLE = TC >= 4;
+  constexpr int TH = STRADDLE ? TC - 1 : TC;                 // token tiles multiplied ahead of the barrier
+  constexpr int DPJ = (DMA + TH - 1) / TH;                   // DMA operations issued per token tile
   constexpr int AREADS = SPARSE ? 2 * TR : 2 * TR;           // LDS reads of tile_load_a
-  constexpr int APJ = (AREADS + TC - 1) / TC;
+  constexpr int APJ = (AREADS + TH - 1) / TH;
+  constexpr int MM = SPARSE ? TR : 2 * TR;                   // matrix instructions per token tile
   const unsigned last = st.k1 - 1;                           // past the end: reload the last stage (never used)
   tile_prefetch_b<SPARSE, TR, TC, NWC>(st, b_pre, k + 2 < st.k1 ? k + 2 : last);
   tile_prefetch_a<SPARSE, TR, TC, NWC>(st, a_pre, m_pre, k + 3 < st.k1 ? k + 3 : last);
-  tile_multiply<DT, SPARSE, TR, TC, NWC>(st, cur, b_cur, k);
+  tile_multiply<DT, SPARSE, TR, TC, NWC, 0, TH, false>(st, cur, bq, b_cur, b_nxt, k);
   tile_load_a<SPARSE, TR, TC, NWC>(st, a_nxt, m_nxt, nxt);
-  // the order wanted within the stage: first B operand; then per token tile "read the next B operand,
-  // multiply, issue a share of the DMA, read a share of the next stage's A side".  A wave that issued
-  // its DMA in one burst would sit at the (bandwidth-limited) vector-memory issue while the matrix
-  // pipe runs dry.
-  sched_group<0x100, 2>();
+  // the order wanted ahead of the barrier: per token tile "read the next B operand, multiply, issue a share of
+  // the DMA, read a share of the next stage's A side".  A wave that issued its DMA in one burst would sit at the
+  // (bandwidth-limited) vector-memory issue while the matrix pipe runs dry.
 #pragma unroll
-  for (int j = 0; j < TC; j++) {
+  for (int j = 0; j < TH; j++) {
     if (j + 1 < TC) sched_group<0x100, 2>();
-    sched_group<0x008, SPARSE ? TR : 2 * TR>();
+    sched_group<0x008, MM>();
     sched_group<0x010, DPJ>();
     sched_group<0x100, APJ>();
   }
   sched_fence();
   tile_arrive<DMA>();
+  sched_fence();
+  if (STRADDLE) {
+    tile_multiply<DT, SPARSE, TR, TC, NWC, TH, TC, true>(st, cur, bq, b_cur, b_nxt, k);
+    sched_group<0x100, 2>();
+    sched_group<0x008, MM>();
+    sched_fence();
+  } else {
+    const uint4* bn = b_nxt + (st.wc * TC) * 128 + st.lane;
+    bq.b0 = bn[0];
+    bq.b1 = bn[64];
+  }
 }
 
 template <int DT, int SPARSE, int TR, int TC, int NWC>
@@ -766,15 +792,18 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
   tile_load_a<SPARSE, TR, TC, NWC>(st, sa0, sm0, r0);
   sched_fence();
   tile_arrive<0>();  // every wave has its first A side in registers before the first stage overwrites its buffer
+  TileB bq;          // the B operand of the coming stage's first token tile
+  bq.b0 = sb0[(st.wc * TC) * 128 + st.lane];
+  bq.b1 = sb0[(st.wc * TC) * 128 + 64 + st.lane];
   unsigned k = kb;
   for (; k + 3 <= st.k1; k += 3) {
-    tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, sb0, sa1, sm1, sb2, sa0, sm0, k);
-    tile_stage<DT, SPARSE, TR, TC, NWC>(st, r1, r0, sb1, sa2, sm2, sb0, sa1, sm1, k + 1);
-    tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, sb2, sa0, sm0, sb1, sa2, sm2, k + 2);
+    tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, bq, sb0, sb1, sa1, sm1, sb2, sa0, sm0, k);
+    tile_stage<DT, SPARSE, TR, TC, NWC>(st, r1, r0, bq, sb1, sb2, sa2, sm2, sb0, sa1, sm1, k + 1);
+    tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, bq, sb2, sb0, sa0, sm0, sb1, sa2, sm2, k + 2);
     r0 = r1;
   }
-  if (k < st.k1) tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, sb0, sa1, sm1, sb2, sa0, sm0, k);
-  if (k + 1 < st.k1) tile_stage<DT, SPARSE, TR, TC, NWC>(st, r1, r0, sb1, sa2, sm2, sb0, sa1, sm1, k + 1);
+  if (k < st.k1) tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, bq, sb0, sb1, sa1, sm1, sb2, sa0, sm0, k);
+  if (k + 1 < st.k1) tile_stage<DT, SPARSE, TR, TC, NWC>(st, r1, r0, bq, sb1, sb2, sa2, sm2, sb0, sa1, sm1, k + 1);
 #if defined(__HIP_DEVICE_COMPILE__)
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no DMA into this workgroup's LDS is left in flight when the wave ends
 #endif
