@@ -29,6 +29,8 @@
 
 #define WS_HEADER_BYTES 65536
 #define MAX_SPLIT 16
+// fp32 partial tiles the workspace has room for: 16 K splits up to 128 tokens, 4 up to 512, none beyond
+static inline int esp_split_capacity(long long M) { return M <= 128 ? MAX_SPLIT : (M <= 512 ? 4 : 1); }
 #define ESP_MAX_GROUP 4  // products of one shape that may share a launch
 
 // ------------------------------------------------------------------------------------------------
@@ -1090,8 +1092,8 @@ static const Variant kVariants[] = {
     {"tile_w8_t256", KIND_TILE, 8, 4, 0, 4},  // 256 rows (dense 128) x 256 tokens per workgroup, 8 waves (two per SIMD)
     {"tile_w8_t128", KIND_TILE, 8, 2, 0, 4},  // 256 rows (dense 128) x 128 tokens per workgroup, 8 waves
     {"tile_w8_r128_t128", KIND_TILE, 4, 2, 0, 4},         // 128 rows (dense 64) x 128 tokens per workgroup, 8 waves
-    {"tile_w8_r128_t128_splitk", KIND_TILE, 4, 2, 1, 4},  // ... with K split over workgroups (M <= 128)
-    {"tile_w8_r128_t64_splitk", KIND_TILE, 4, 1, 1, 4},   // 128 rows (dense 64) x 64 tokens, K split (M <= 128)
+    {"tile_w8_r128_t128_splitk", KIND_TILE, 4, 2, 1, 4},  // ... with K split over workgroups (M <= 512)
+    {"tile_w8_r128_t64_splitk", KIND_TILE, 4, 1, 1, 4},   // 128 rows (dense 64) x 64 tokens, K split
     // stream kind: nw waves x rt row tiles per workgroup, all tokens (M <= 128), K split; tt = ring slots
     {"stream_w8_r1_d3", KIND_STREAM, 1, 4, 1, 8},
     {"stream_w8_r1_d7", KIND_STREAM, 1, 8, 1, 8},
@@ -1099,6 +1101,7 @@ static const Variant kVariants[] = {
     {"stream_w8_r2_d5", KIND_STREAM, 2, 6, 1, 8},
     {"ksplit_w8_r6", KIND_KSPLIT, 6, 0, 0, 8},  // M <= 32: 96 rows per workgroup, the activations are re-read by fewer workgroups
     {"ksplit_w8_r3", KIND_KSPLIT, 3, 0, 0, 8},
+    {"tile_w8_t128_splitk", KIND_TILE, 8, 2, 1, 4},  // 256 rows (dense 128) x 128 tokens, K split (M <= 512)
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -1117,7 +1120,7 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
     const long long mt = mc <= 16 ? 1 : (mc <= 32 ? 2 : 4);
     return (long long)var.nw * var.rt * mt * 1024 <= 160 * 1024;
   }
-  if (var.split_mode == 1 && M > 128) return false;  // partial buffers are sized for M <= 128 only
+  if (var.split_mode == 1 && esp_split_capacity(M) == 1) return false;  // no room for partial tiles beyond 512 tokens
   if (var.kind == KIND_KSPLIT) {
     if (M > 64) return false;
     const long long mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);  // token tiles; the waves' partial tiles must fit the LDS
@@ -1160,7 +1163,7 @@ static size_t staged_bytes(long long M, long long K) {
 size_t esp_workspace_bytes(long long M, long long N, long long K) {
   const size_t Mp = (size_t)esp_round_up(M, 16), Np = (size_t)esp_round_up(N, 16);
   size_t bytes = WS_HEADER_BYTES + staged_bytes(M, K);
-  if (M <= 128) bytes += (size_t)MAX_SPLIT * Mp * Np * 4;
+  if (esp_split_capacity(M) > 1) bytes += (size_t)esp_split_capacity(M) * Mp * Np * 4;
   return bytes;
 }
 
@@ -1210,8 +1213,9 @@ static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const
   if (v.split_mode == 1) {
     // about two workgroups per CU, splits of at least 8 stages (512 channels); no split once the macro
     // tiles alone cover half of the CUs (the fp32 partial tiles and their reduction then cost more)
-    const long long want = n_tiles >= 128 ? 1 : (512 + n_tiles - 1) / n_tiles;
-    nsplit = (int)std::max<long long>(1, std::min<long long>(std::min<long long>(want, nks / 8), MAX_SPLIT));
+    // M > 128 (at most 4 splits, larger partial tiles): as many splits as keep the items within one round of 256
+    const long long want = M > 128 ? 256 / n_tiles : (n_tiles >= 128 ? 1 : (512 + n_tiles - 1) / n_tiles);
+    nsplit = (int)std::max<long long>(1, std::min<long long>(std::min<long long>(want, nks / 8), esp_split_capacity(M)));
     sps = ((nks + nsplit - 1) / nsplit + 3) / 4 * 4;
     nsplit = (int)((nks + sps - 1) / sps);
   }
@@ -1438,7 +1442,7 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
     // enough waves for ~8 per CU (256 CUs), splits of at least 4 steps (256 channels)
     long long want = (256 * 8 + nrb * ntb - 1) / (nrb * ntb);
     long long maxs = nks / 4;
-    nsplit = (int)std::max<long long>(1, std::min<long long>(std::min<long long>(want, maxs), MAX_SPLIT));
+    nsplit = (int)std::max<long long>(1, std::min<long long>(std::min<long long>(want, maxs), esp_split_capacity(M)));
   }
   long long sps = (nks + nsplit - 1) / nsplit;
   sps = (sps + 3) / 4 * 4;

@@ -279,6 +279,7 @@ def test_spmm_k_split_over_workgroups(esp, ctx, dtype):
     # K long enough (64 stages of 64 channels) for the split-K variants to really split; ragged M and N
     _spmm_case(esp, ctx, 100, 300, 4096, dtype, 49)
     _spmm_case(esp, ctx, 64, 144, 2304, dtype, 50)
+    _spmm_case(esp, ctx, 300, 272, 4096, dtype, 51)   # 128 < M <= 512: up to four splits
 
 
 def test_stacked_matrices_share_one_theta(esp, ctx):
