@@ -210,7 +210,7 @@ int esparse_dense_gemm_group(esparse_ctx* ctx, int count, const void* const* X, 
 
 /* ---- Section 4, step 2: pick and remember the fastest variant for a shape --------------------
  * Times every applicable variant of esparse_spmm (sparse = 1: 2:4, sparse = 2: 4:8) or esparse_dense_gemm (sparse = 0) on
- * zero-filled scratch operands of shape (M, N, K) and stores the winner in the context; later
+ * scratch operands (finite pseudo-random values) of shape (M, N, K) and stores the winner in the context; later
  * calls with variant = -1 use it.  The timed launches rotate over copies of the weight operand
  * (about 640 MiB of them, at least two), so that the weights come from HBM as they do when a
  * model reads each matrix once per step.  best_variant (HOST, optional) receives its id.  The table can be

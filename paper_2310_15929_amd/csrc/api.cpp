@@ -443,11 +443,13 @@ static int tune_impl(esparse_ctx* ctx, int count, long long M, long long N, long
   const size_t wbytes = ((sparse ? Np * Kp + Np * Kp / 8 : Np * Kp * 2) + 255) / 256 * 256;
   const int ncopies = (int)std::max<size_t>(2 * count, std::min<size_t>(64, ((size_t)640 << 20) / wbytes + count));
   const size_t ybytes = ((size_t)M * N * 2 + 255) / 256 * 256;
-  if (w.alloc(wbytes * ncopies) != hipSuccess || x.alloc((size_t)M * K * 2) != hipSuccess ||
+  const size_t xbytes = ((size_t)M * K * 2 + 255) / 256 * 256;
+  if (w.alloc(wbytes * ncopies) != hipSuccess || x.alloc(xbytes) != hipSuccess ||
       y.alloc(ybytes * count) != hipSuccess || ws.alloc(esp_group_workspace_bytes(count, M, N, K)) != hipSuccess)
     return esp_fail(ctx, ESPARSE_ENOMEM, "scratch allocation for tuning failed");
-  ESP_HIP(ctx, hipMemsetAsync(w.p, 0, wbytes * ncopies, ctx->stream));
-  ESP_HIP(ctx, hipMemsetAsync(x.p, 0, (size_t)M * K * 2, ctx->stream));
+  // operands: finite pseudo-random 16-bit values (zeros would time differently, see esp_fill_pattern_device)
+  if ((rc = esp_fill_pattern_device(ctx, w.p, wbytes * ncopies))) return rc;
+  if ((rc = esp_fill_pattern_device(ctx, x.p, xbytes))) return rc;
   hipEvent_t e0, e1;
   ESP_HIP(ctx, hipEventCreate(&e0));
   ESP_HIP(ctx, hipEventCreate(&e1));

@@ -100,6 +100,7 @@ int esp_dense_pack_device(esparse_ctx* ctx, const void* W, long long N, long lon
                           void* packed);
 // products
 // report (eq. 4)
+int esp_fill_pattern_device(esparse_ctx* ctx, void* dst, size_t bytes);
 int esp_output_error_device(esparse_ctx* ctx, const void* Yref, const void* Y, long long count, int dtype, double* num_out,
                             double* den_out);
 

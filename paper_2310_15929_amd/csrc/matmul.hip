@@ -565,8 +565,9 @@ struct TileState {
   static constexpr int BCOPIES = (NWC * TC * 128) / NT;     // 16-byte units of activations per lane and stage
   static constexpr int RTM = 2 * TR;                        // row tiles of 16 in the macro tile
   static constexpr int AUNITS = RTM * (SPARSE ? 64 : 128);  // 16-byte units of weights per stage
-  static constexpr int ACOPIES = AUNITS / NT;               // ... per lane
-  static_assert(AUNITS % NT == 0 && (NWC * TC * 128) % NT == 0, "every wave copies whole 64-unit chunks");
+  static constexpr int ACOPIES = (AUNITS + NT - 1) / NT;    // ... per lane; when the chunks do not divide among the waves the
+  static constexpr int ASLOTS = ACOPIES * NT;               //     last copies fetch a row tile past the macro tile into spare slots
+  static_assert((NWC * TC * 128) % NT == 0, "every wave copies whole 64-unit chunks");
   floatx4_t acc[TR][TC];
   const uint4* a_src[ACOPIES];  // wave-uniform global bases of this wave's DMA copies
   const uint4* x_src[BCOPIES];
@@ -834,16 +835,16 @@ __global__ void __launch_bounds__(128 * NWC) k_mm_tile(const uint4* __restrict__
                                                         float* __restrict__ partial, long long M, long long N, long long Mp,
                                                         long long Np, long long Kp, long long n_tiles, long long ntb, int nsplit,
                                                         int sps) {
-  constexpr int AUNITS = TileState<SPARSE, TR, TC, NWC>::AUNITS;
-  __shared__ uint4 s_a0[AUNITS];  // one stage of weights each
-  __shared__ uint4 s_a1[AUNITS];
-  __shared__ uint4 s_a2[AUNITS];
+  constexpr int ASLOTS = TileState<SPARSE, TR, TC, NWC>::ASLOTS;
+  __shared__ uint4 s_a0[ASLOTS];  // one stage of weights each
+  __shared__ uint4 s_a1[ASLOTS];
+  __shared__ uint4 s_a2[ASLOTS];
   __shared__ uint4 s_b0[NWC * TC * 128];  // one stage of activations each: [NWC TC token tiles][2 half steps][64 lanes]
   __shared__ uint4 s_b1[NWC * TC * 128];
   __shared__ uint4 s_b2[NWC * TC * 128];
-  __shared__ uint32_t s_m0[SPARSE ? 2 * TR * 64 : 1];  // one stage pair of index words each: [row tiles][64 lanes]
-  __shared__ uint32_t s_m1[SPARSE ? 2 * TR * 64 : 1];
-  __shared__ uint32_t s_m2[SPARSE ? 2 * TR * 64 : 1];
+  __shared__ uint32_t s_m0[SPARSE ? ASLOTS : 1];  // one stage pair of index words each: [row tiles][64 lanes]
+  __shared__ uint32_t s_m1[SPARSE ? ASLOTS : 1];
+  __shared__ uint32_t s_m2[SPARSE ? ASLOTS : 1];
   tile_pipeline<DT, SPARSE, TR, TC, NWC>(s_a0, s_a1, s_a2, s_b0, s_b1, s_b2, s_m0, s_m1, s_m2, A, meta16, Xf, Y, partial, M, N, Mp,
                                          Np, Kp, n_tiles, ntb, nsplit, sps);
 }
@@ -1102,6 +1103,10 @@ static const Variant kVariants[] = {
     {"ksplit_w8_r6", KIND_KSPLIT, 6, 0, 0, 8},  // M <= 32: 96 rows per workgroup, the activations are re-read by fewer workgroups
     {"ksplit_w8_r3", KIND_KSPLIT, 3, 0, 0, 8},
     {"tile_w8_t128_splitk", KIND_TILE, 8, 2, 1, 4},  // 256 rows (dense 128) x 128 tokens, K split (M <= 512)
+    // macro tiles of 288 / 320 rows x 128 tokens: row counts with a factor 9 or 5 (9216, 5120) then give a number of
+    // macro tiles that fills the 256 CUs exactly where 256-row tiles leave a partly filled round
+    {"tile_w8_r288_t128", KIND_TILE, 9, 2, 0, 4},
+    {"tile_w8_r320_t128", KIND_TILE, 10, 2, 0, 4},
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -1203,7 +1208,7 @@ template <int DT, int SPARSE>
 static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const uint4* A, const uint16_t* meta16, const uint4* Xf,
                        uint16_t* Y, float* partial, long long M, long long N, long long Mp, long long Np, long long Kp) {
   // the dense operand is twice as wide: half the row tiles per wave
-  const long long rtm = SPARSE ? 2 * v.rt : v.rt;  // row tiles per macro tile
+  const long long rtm = SPARSE ? 2 * v.rt : 2 * (v.rt / 2);  // row tiles per macro tile
   const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
   const long long cols = (long long)v.nw * v.tt;  // token tiles per macro tile
   const long long nrb = (nrt + rtm - 1) / rtm, ntb = (ntt + cols - 1) / cols;
@@ -1230,6 +1235,8 @@ static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const
   else if (v.rt == 8 && v.nw == 4 && v.tt == 2) ESP_TILE(8, 2, 4);
   else if (v.rt == 4 && v.nw == 4 && v.tt == 2) ESP_TILE(4, 2, 4);
   else if (v.rt == 4 && v.nw == 4 && v.tt == 1) ESP_TILE(4, 1, 4);
+  else if (v.rt == 9 && v.nw == 4 && v.tt == 2) ESP_TILE(9, 2, 4);
+  else if (v.rt == 10 && v.nw == 4 && v.tt == 2) ESP_TILE(10, 2, 4);
   else return esp_fail(ctx, ESPARSE_EINVAL, "unknown tile variant");
 #undef ESP_TILE
   ESP_HIP(ctx, hipGetLastError());
