@@ -262,6 +262,13 @@ def test_spmm_small_ragged(esp, ctx, M, dtype):
     _spmm_case(esp, ctx, M, 72, 576, dtype, 41)
 
 
+@pytest.mark.parametrize("M", [2, 3, 5, 9, 15, 17])
+def test_spmm_few_tokens_compact_staging(esp, ctx, M):
+    """Up to 16 tokens the decode kernels read the compact copy of the staged activations (token count rounded up
+    to a power of two, the padding tokens zero); 17 is the first size that does not."""
+    _spmm_case(esp, ctx, M, 88, 832, torch.float16, 46 + M)
+
+
 def test_spmm_stream_spans(esp, ctx):
     """Stream kernels cut the steps of all row blocks into equal spans: a span inside one row block (partial
     pieces), a span across a row block boundary, and spans holding several whole row blocks (stored directly)."""
