@@ -65,6 +65,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--calib-tokens", type=int, default=128 * 2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune-save", default="", help="write the tuned variant table (the library's text format) to this file")
+    ap.add_argument("--tune-load", default="", help="take the variants from such a file instead of timing them (runs under a "
+                                                    "profiler, whose per-launch overhead would distort the tuner's timing)")
     ap.add_argument("--config", type=int, default=2, choices=(2, 3, 4, 5),
                     help="workload configuration (default 2, the one the headline metric is quoted on)")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer instances per step (0 = the workload's default)")
@@ -152,12 +155,25 @@ def main():
     # every shape gets the variant the library's own tuner finds fastest (sparse and dense alike)
     tuned = {}
     dcode = esp.F16 if tdtype == torch.float16 else esp.BF16
+    loaded = {}
+    if args.tune_load:
+        ctx.tune_load(args.tune_load)
+        for line in open(args.tune_load):
+            f = line.split()
+            if len(f) >= 6 and not line.startswith("#"):
+                loaded[(int(f[0]), int(f[1]), int(f[2]), int(f[3]), int(f[4]), int(f[6]) if len(f) > 6 else 1)] = f[5]
+
+    def tuned_name(count, M, N, K, sparse):
+        key = (1 if sparse else 0, dcode, M, N, K, count)
+        if key in loaded:
+            return loaded[key]
+        v, _ = ctx.tune_group(count, M, N, K, dcode, sparse) if count > 1 else ctx.tune(M, N, K, dcode, sparse)
+        return esp.variant_name(v)
+
     for skey in {m[1] for m in MATS}:
         N, K = shapes[skey]
         for M in M_LIST:
-            vs, _ = ctx.tune(M, N, K, dcode, True)
-            vd, _ = ctx.tune(M, N, K, dcode, False)
-            tuned[f"{skey}/M={M}"] = [esp.variant_name(vs), esp.variant_name(vd)]
+            tuned[f"{skey}/M={M}"] = [tuned_name(1, M, N, K, True), tuned_name(1, M, N, K, False)]
 
     # ------------------------------------------------------------------ steps
     # the linears of a layer that have one shape and read one input (q/k/v; gate/up) go through the library's
@@ -174,9 +190,9 @@ def main():
         if len(names) > 1:
             N, K = shapes[skey]
             for M in M_LIST:
-                vs, _ = ctx.tune_group(len(names), M, N, K, dcode, True)
-                vd, _ = ctx.tune_group(len(names), M, N, K, dcode, False)
-                tuned[f"{skey}/M={M}/x{len(names)}"] = [esp.variant_name(vs), esp.variant_name(vd)]
+                tuned[f"{skey}/M={M}/x{len(names)}"] = [tuned_name(len(names), M, N, K, True), tuned_name(len(names), M, N, K, False)]
+    if args.tune_save:
+        ctx.tune_save(args.tune_save)
 
     def step_sparse():
         for mats in layers:
