@@ -422,7 +422,7 @@ __global__ void __launch_bounds__(256) k_mm_wave_tile(const uint4* __restrict__ 
 // the result does not depend on timing and no global synchronisation is needed.
 // grid = ceil(row tiles / RT), block = 64 * NW.
 // ------------------------------------------------------------------------------------------------
-template <int DT, int SPARSE, int MT, int RT, int NW>
+template <int DT, int SPARSE, int MT, int RT, int NW, bool PAIRS>
 __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long long M, long long N, long long Mp, long long Np,
                                                         long long Kp, int mc) {
   const uint4* __restrict__ A = args.A[blockIdx.y];
@@ -463,19 +463,33 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long lon
 #pragma unroll
     for (int j = 0; j < MT; j++) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
-  // two steps per trip (all loads of both steps are issued before the first multiply)
-  for (long long ks = wave; ks < nks; ks += 2 * NW) {
-    const bool second = ks + NW < nks;  // wave-uniform
-    const long long kk[2] = {ks, second ? ks + NW : ks};
+  // two steps per trip (all loads of both steps are issued before the first multiply).  PAIRS (chosen by the host where
+  // the step pairs divide evenly among the waves and there are two or more token tiles): a trip takes the two steps of
+  // a pair, whose index halves are one 32-bit word - one load per row tile instead of two; the vector-memory path of
+  // the CU, which these kernels saturate, counts instructions as well as bytes.  Otherwise wave w takes steps
+  // w, w + NW, ... as they come.
+  constexpr bool pairs = PAIRS;
+  const uint32_t* meta32 = reinterpret_cast<const uint32_t*>(meta16);
+  for (long long ks = pairs ? 2 * wave : wave; ks < nks; ks += 2 * NW) {
+    const bool second = pairs || ks + NW < nks;  // wave-uniform
+    const long long kk[2] = {ks, pairs ? ks + 1 : (second ? ks + NW : ks)};
     uint4 a[2][RT], a2[2][RT], b0[2][MT], b1[2][MT];
     int idx[2][RT];
+    if (pairs) {
+#pragma unroll
+      for (int i = 0; i < RT; i++) {
+        const uint32_t w = meta32[((rts[i] * (nks / 4) + ks / 4) * 64 + lane) * 2 + ((ks >> 1) & 1)];
+        idx[0][i] = (int)w;           // the instruction reads the low half
+        idx[1][i] = (int)(w >> 16);
+      }
+    }
 #pragma unroll
     for (int u = 0; u < 2; u++) {
 #pragma unroll
       for (int i = 0; i < RT; i++) {
         if (SPARSE) {  // 2:4: kept values + index half; 4:8: kept values of two groups + their two bitmaps
           a[u][i] = A[(rts[i] * nks + kk[u]) * 64 + lane];
-          idx[u][i] = (int)meta16[((rts[i] * (nks / 4) + kk[u] / 4) * 64 + lane) * 4 + (kk[u] & 3)];
+          if (!pairs) idx[u][i] = (int)meta16[((rts[i] * (nks / 4) + kk[u] / 4) * 64 + lane) * 4 + (kk[u] & 3)];
         } else {
           a[u][i] = A[(rts[i] * (2 * nks) + 2 * kk[u]) * 64 + lane];
           a2[u][i] = A[(rts[i] * (2 * nks) + 2 * kk[u] + 1) * 64 + lane];
@@ -1192,7 +1206,15 @@ static void launch_ksplit(const Variant& v, hipStream_t st, const KsplitArgs& ar
   const long long nrt = Np / 16;
   dim3 grid((unsigned)((nrt + v.rt - 1) / v.rt), (unsigned)count);
   const size_t smem = (size_t)v.nw * v.rt * MT * 64 * 16;
-#define LAUNCH(R, W) hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp, mc)
+  const bool pairs = SPARSE == 1 && MT >= 2 && ((Kp / 128) % v.nw) == 0;
+#define LAUNCH(R, W)                                                                                                          \
+  do {                                                                                                                        \
+    if (SPARSE == 1 && MT >= 2 && pairs)                                                                                      \
+      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, (SPARSE == 1 && MT >= 2)>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, \
+                         Kp, mc);                                                                                             \
+    else                                                                                                                      \
+      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, false>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp, mc); \
+  } while (0)
   if (v.nw == 16 && v.rt == 1) LAUNCH(1, 16);
   else if (v.nw == 16 && v.rt == 2) LAUNCH(2, 16);
   else if (v.nw == 16 && v.rt == 3) LAUNCH(3, 16);
