@@ -134,6 +134,8 @@ struct KsplitArgs {
   const uint16_t* meta16[ESP_MAX_GROUP];
   const uint4* Xf[ESP_MAX_GROUP];
   uint16_t* Y[ESP_MAX_GROUP];
+  float* partial;  // single products with K split over workgroups (gridDim.z > 1): fp32 partial tiles [split][Mp][Np]
+  int sps;         // ... and the steps per split
 };
 
 // mc > 0 (at most 16 tokens): a second, compact copy follows the fragment-major one (units [units, units + mc Kp / 8)):
@@ -470,8 +472,12 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long lon
   // w, w + NW, ... as they come.
   constexpr bool pairs = PAIRS;
   const uint32_t* meta32 = reinterpret_cast<const uint32_t*>(meta16);
-  for (long long ks = pairs ? 2 * wave : wave; ks < nks; ks += 2 * NW) {
-    const bool second = pairs || ks + NW < nks;  // wave-uniform
+  // K split over workgroups (matrices with few rows and many tokens, where every workgroup re-reading all the
+  // activations costs more than the weights): workgroup z takes steps [kb, ke), an even kb
+  const long long kb = gridDim.z > 1 ? (long long)blockIdx.z * args.sps : 0;
+  const long long ke = gridDim.z > 1 && kb + args.sps < nks ? kb + args.sps : nks;
+  for (long long ks = kb + (pairs ? 2 * wave : wave); ks < ke; ks += 2 * NW) {
+    const bool second = pairs || ks + NW < ke;  // wave-uniform
     const long long kk[2] = {ks, pairs ? ks + 1 : (second ? ks + NW : ks)};
     uint4 a[2][RT], a2[2][RT], b0[2][MT], b1[2][MT];
     int idx[2][RT];
@@ -552,7 +558,12 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long lon
     const int i = q / MT, j = q % MT;
     floatx4_t sum = s_red[q * 64 + lane];
     for (int w = 1; w < NW; w++) sum += s_red[(w * (RT * MT) + q) * 64 + lane];
-    if (rt0 + i < nrt && j < ntt) store_y4<DT>(Y, M, N, (long long)j * 16 + c, (rt0 + i) * 16 + g * 4, sum);
+    if (rt0 + i < nrt && j < ntt) {
+      if (gridDim.z > 1)
+        *reinterpret_cast<floatx4_t*>(args.partial + (((long long)blockIdx.z * Mp + (long long)j * 16 + c) * Np + (rt0 + i) * 16 + g * 4)) = sum;
+      else
+        store_y4<DT>(Y, M, N, (long long)j * 16 + c, (rt0 + i) * 16 + g * 4, sum);
+    }
   }
 }
 
@@ -1117,6 +1128,11 @@ static const Variant kVariants[] = {
     {"ksplit_w8_r6", KIND_KSPLIT, 6, 0, 0, 8},  // M <= 32: 96 rows per workgroup, the activations are re-read by fewer workgroups
     {"ksplit_w8_r3", KIND_KSPLIT, 3, 0, 0, 8},
     {"tile_w8_t128_splitk", KIND_TILE, 8, 2, 1, 4},  // 256 rows (dense 128) x 128 tokens, K split (M <= 512)
+    // decode kernels with K split over workgroups (tt = splits; single products): for matrices with few rows and
+    // tens of tokens, where each workgroup re-reading all the staged activations costs several times the weights
+    {"ksplit_w16_r4_k4", KIND_KSPLIT, 4, 4, 1, 16},
+    {"ksplit_w16_r2_k2", KIND_KSPLIT, 2, 2, 1, 16},
+    {"ksplit_w8_r4_k4", KIND_KSPLIT, 4, 4, 1, 8},
     // macro tiles of 288 / 320 rows x 128 tokens: row counts with a factor 9 or 5 (9216, 5120) then give a number of
     // macro tiles that fills the 256 CUs exactly where 256-row tiles leave a partly filled round
     {"tile_w8_r288_t128", KIND_TILE, 9, 2, 0, 4},
@@ -1201,12 +1217,16 @@ static void launch_wave_tile(const Variant& v, dim3 grid, hipStream_t st, const 
 }
 
 template <int DT, int SPARSE, int MT>
-static void launch_ksplit(const Variant& v, hipStream_t st, const KsplitArgs& args, int count, long long M, long long N, long long Mp,
-                          long long Np, long long Kp, int mc) {
-  const long long nrt = Np / 16;
-  dim3 grid((unsigned)((nrt + v.rt - 1) / v.rt), (unsigned)count);
+static void launch_ksplit(const Variant& v, hipStream_t st, KsplitArgs args, int count, long long M, long long N, long long Mp,
+                          long long Np, long long Kp, int mc, int nsplit) {
+  const long long nrt = Np / 16, nks = Kp / 64;
+  // K split over workgroups: single products only; splits of a multiple of four steps
+  const long long sps = nsplit > 1 ? ((nks + nsplit - 1) / nsplit + 3) / 4 * 4 : nks;
+  nsplit = (int)((nks + sps - 1) / sps);
+  args.sps = (int)sps;
+  dim3 grid((unsigned)((nrt + v.rt - 1) / v.rt), (unsigned)count, (unsigned)nsplit);
   const size_t smem = (size_t)v.nw * v.rt * MT * 64 * 16;
-  const bool pairs = SPARSE == 1 && MT >= 2 && ((Kp / 128) % v.nw) == 0;
+  const bool pairs = SPARSE == 1 && MT >= 2 && ((sps / 2) % v.nw) == 0 && nks % sps == 0;
 #define LAUNCH(R, W)                                                                                                          \
   do {                                                                                                                        \
     if (SPARSE == 1 && MT >= 2 && pairs)                                                                                      \
@@ -1222,8 +1242,13 @@ static void launch_ksplit(const Variant& v, hipStream_t st, const KsplitArgs& ar
   else if (v.nw == 8 && v.rt == 2) LAUNCH(2, 8);
   else if (v.nw == 8 && v.rt == 6) LAUNCH(6, 8);
   else if (v.nw == 8 && v.rt == 3) LAUNCH(3, 8);
+  else if (v.nw == 16 && v.rt == 4) LAUNCH(4, 16);
   else LAUNCH(4, 8);
 #undef LAUNCH
+  if (nsplit > 1) {
+    const long long e = M * (Np / 4);
+    hipLaunchKernelGGL(k_reduce_splits<DT>, dim3((unsigned)((e + 255) / 256)), dim3(256), 0, st, args.partial, nsplit, M, N, Mp, Np, args.Y[0]);
+  }
 }
 
 template <int DT, int SPARSE>
@@ -1390,6 +1415,8 @@ static int stage_activations(esparse_ctx* ctx, const void* X, const int32_t* per
 static int launch_ksplit_any(esparse_ctx* ctx, const Variant& v, int sparse, int dtype, KsplitArgs ka, int count, long long M,
                              long long N, long long Np, long long Kp) {
   const int mc = compact_tokens(M);
+  // variants with K split over workgroups (tt = splits): single products of at most 64 tokens with room for the partial tiles
+  const int nsplit = (v.split_mode == 1 && count == 1 && M <= 64 && ka.partial) ? v.tt : 1;
   hipStream_t st = ctx->stream;
   const long long nks = Kp / 64;
   for (long long t0 = 0; t0 < M; t0 += 64) {  // more than 64 tokens (4:8 only): 64 at a time
@@ -1401,9 +1428,9 @@ static int launch_ksplit_any(esparse_ctx* ctx, const Variant& v, int sparse, int
     }
 #define ESP_KSPLIT(DTv, SPv)                                                          \
   do {                                                                                \
-    if (mcp == 16) launch_ksplit<DTv, SPv, 1>(v, st, kc, count, mcur, N, mcp, Np, Kp, mc);  \
-    else if (mcp == 32) launch_ksplit<DTv, SPv, 2>(v, st, kc, count, mcur, N, mcp, Np, Kp, 0); \
-    else launch_ksplit<DTv, SPv, 4>(v, st, kc, count, mcur, N, mcp, Np, Kp, 0);            \
+    if (mcp == 16) launch_ksplit<DTv, SPv, 1>(v, st, kc, count, mcur, N, mcp, Np, Kp, mc, nsplit);  \
+    else if (mcp == 32) launch_ksplit<DTv, SPv, 2>(v, st, kc, count, mcur, N, mcp, Np, Kp, 0, nsplit); \
+    else launch_ksplit<DTv, SPv, 4>(v, st, kc, count, mcur, N, mcp, Np, Kp, 0, nsplit);            \
   } while (0)
     if (dtype == ESPARSE_F16) {
       if (sparse == 2) ESP_KSPLIT(ESPARSE_F16, 2);
@@ -1443,6 +1470,7 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
     ka.meta16[0] = reinterpret_cast<const uint16_t*>(meta_bytes);
     ka.Xf[0] = Xf;
     ka.Y[0] = Y;
+    ka.partial = partial;
     return launch_ksplit_any(ctx, v, sparse, dtype, ka, 1, M, N, Np, Kp);
   }
 
@@ -1508,8 +1536,9 @@ int esp_matmul_group_device(esparse_ctx* ctx, int sparse, int count, const void*
                             const int32_t* const* perm, long long N, long long K, int dtype, void* const* Y, void* workspace,
                             int variant, int phases) {
   const Variant& v = kVariants[variant];
-  if (v.kind != KIND_KSPLIT) {
-    // no grouped form of the other kernels: one product after the other through the same workspace
+  if (v.kind != KIND_KSPLIT || v.split_mode == 1) {
+    // no grouped form of the other kernels (nor of the decode kernels with K split over workgroups, whose partial
+    // tiles live in the workspace of one product): one product after the other through the same workspace
     // (callers that split the phases get EUNSUPPORTED before they reach this point)
     for (int i = 0; i < count; i++) {
       int rc = esp_matmul_device(ctx, sparse, X[i], M, w[i], perm ? perm[i] : nullptr, N, K, dtype, Y[i], workspace, variant,
@@ -1548,4 +1577,6 @@ int esp_matmul_group_device(esparse_ctx* ctx, int sparse, int count, const void*
   return launch_ksplit_any(ctx, v, sparse, dtype, ka, count, M, N, Np, Kp);
 }
 
-bool esp_variant_is_decode_kernel(int v) { return v >= 0 && v < kNumVariants && kVariants[v].kind == KIND_KSPLIT; }
+bool esp_variant_is_decode_kernel(int v) {
+  return v >= 0 && v < kNumVariants && kVariants[v].kind == KIND_KSPLIT && kVariants[v].split_mode == 0;
+}
