@@ -269,6 +269,14 @@ def test_spmm_few_tokens_compact_staging(esp, ctx, M):
     _spmm_case(esp, ctx, M, 88, 832, torch.float16, 46 + M)
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+def test_spmm_decode_step_pairs(esp, ctx, dtype):
+    """K = 2048: 16 step pairs divide among 8 and 16 waves, so the decode kernels with two or four token tiles take
+    the steps pairwise and read one index word per pair."""
+    _spmm_case(esp, ctx, 33, 80, 2048, dtype, 52)
+    _spmm_case(esp, ctx, 20, 48, 2048, dtype, 53)
+
+
 def test_spmm_stream_spans(esp, ctx):
     """Stream kernels cut the steps of all row blocks into equal spans: a span inside one row block (partial
     pieces), a span across a row block boundary, and spans holding several whole row blocks (stored directly)."""
