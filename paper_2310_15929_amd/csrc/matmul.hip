@@ -197,11 +197,18 @@ __global__ void __launch_bounds__(256) k_gather_x(GatherArgs args, long long M, 
 // unit l / TOK, so consecutive lanes write consecutive 16-byte units of X'.  Needs K % 8 == 0.
 template <int TOK>
 __global__ void __launch_bounds__(512) k_gather_rows(const uint16_t* __restrict__ X, const int32_t* __restrict__ perm, long long M,
-                                                      long long K, long long Kp, uint4* __restrict__ Xf) {
+                                                      long long Mp, long long K, long long Kp, uint4* __restrict__ Xf) {
   extern __shared__ uint4 s_rows4[];
   uint16_t* s_rows = reinterpret_cast<uint16_t*>(s_rows4);
   const int tid = threadIdx.x;
-  const long long t0 = (long long)blockIdx.x * TOK;
+  // Workgroups b, b + 8, b + 16, ... run on one XCD (round-robin dispatch): the 16 / TOK workgroups whose tokens
+  // share a token tile - and with it every 256-byte run of X' - are numbered that way, so that their 16 TOK-byte
+  // pieces meet in that XCD's L2 and leave it as whole lines
+  constexpr int PER = 16 / TOK;
+  const long long j = blockIdx.x / 8;
+  const long long tile = (j / PER) * 8 + blockIdx.x % 8;
+  const long long t0 = tile * 16 + (j % PER) * TOK;
+  if (t0 >= Mp) return;
   const int stride = (int)K + 8;
   const long long nrows = (M - t0) < TOK ? (M - t0 > 0 ? M - t0 : 0) : TOK;
   const int kc = (int)(K / 8);  // 16-byte chunks per row
@@ -1360,14 +1367,22 @@ static int launch_stream(esparse_ctx* ctx, const Variant& v, hipStream_t st, con
   return ESPARSE_OK;
 }
 
-// rows of X per workgroup of k_gather_rows: the largest power of two <= 16 whose padded rows fit the
-// LDS budget, lowered while that leaves fewer than ~2 workgroups per CU
+// rows of X per workgroup of k_gather_rows (a power of two <= 16; 0 = a row does not fit the LDS)
 static int gather_rows_tok(long long Mp, long long K) {
-  const long long budget = 144 * 1024;
+  const long long row = (K + 8) * 2, all = 160 * 1024;  // the kernel has no other LDS
+  if (row > all) return 0;
+  // two workgroups per CU (one loads while the other gathers) if that still leaves two tokens per workgroup,
+  // else whatever fits one workgroup
   int tok = 16;
-  while (tok > 1 && (long long)tok * (K + 8) * 2 > budget) tok >>= 1;
-  if ((long long)tok * (K + 8) * 2 > budget) return 0;
-  while (tok > 1 && Mp / tok < 512) tok >>= 1;
+  while (tok > 2 && tok * row > all / 2) tok >>= 1;
+  if (tok * row > all / 2) {
+    tok = 16;
+    while (tok > 1 && tok * row > all) tok >>= 1;
+  }
+  // fewer tokens where that fills the chip better, but single tokens (16-byte pieces of every line of X') only for
+  // short inputs
+  const int floor_tok = Mp >= 512 ? 2 : 1;
+  while (tok > floor_tok && Mp / tok < 512) tok >>= 1;
   return tok;
 }
 
@@ -1382,7 +1397,8 @@ static hipError_t launch_gather_rows(hipStream_t st, const uint16_t* X, const in
     if (e != hipSuccess) return e;
     raised = true;
   }
-  hipLaunchKernelGGL(k_gather_rows<TOK>, dim3((unsigned)(Mp / TOK)), dim3(512), smem, st, X, perm, M, K, Kp, Xf);
+  const long long ntiles = Mp / 16, per = 16 / TOK;
+  hipLaunchKernelGGL(k_gather_rows<TOK>, dim3((unsigned)((ntiles + 7) / 8 * 8 * per)), dim3(512), smem, st, X, perm, M, Mp, K, Kp, Xf);
   return hipGetLastError();
 }
 

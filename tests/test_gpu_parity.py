@@ -297,6 +297,14 @@ def test_spmm_k_split_over_workgroups(esp, ctx, dtype):
     _spmm_case(esp, ctx, 300, 272, 4096, dtype, 51)   # 128 < M <= 512: up to four splits
 
 
+def test_spmm_many_tokens_row_staging(esp, ctx):
+    """Long inputs are staged by workgroups that hold 2 to 16 whole rows of X; the workgroups of one token tile are
+    numbered 8 apart.  8 and 16 rows per workgroup need thousands of tokens; the tile counts (257, 513) are not
+    multiples of 8 and the last tile is ragged."""
+    _spmm_case(esp, ctx, 4100, 32, 512, torch.float16, 54)
+    _spmm_case(esp, ctx, 8200, 32, 320, torch.bfloat16, 55)
+
+
 def test_stacked_matrices_share_one_theta(esp, ctx):
     """Matrices that read the same input (q/k/v, gate/up) pruned as one stacked matrix: one theta, one mask;
     the product of the stack is the concatenation of the products of its slices (bitwise: rows are independent)
