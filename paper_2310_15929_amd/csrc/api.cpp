@@ -450,9 +450,16 @@ static int tune_impl(esparse_ctx* ctx, int count, long long M, long long N, long
   // operands: finite pseudo-random 16-bit values (zeros would time differently, see esp_fill_pattern_device)
   if ((rc = esp_fill_pattern_device(ctx, w.p, wbytes * ncopies))) return rc;
   if ((rc = esp_fill_pattern_device(ctx, x.p, xbytes))) return rc;
-  hipEvent_t e0, e1;
-  ESP_HIP(ctx, hipEventCreate(&e0));
-  ESP_HIP(ctx, hipEventCreate(&e1));
+  struct Events {  // destroyed on every way out
+    hipEvent_t e[2] = {nullptr, nullptr};
+    ~Events() {
+      for (hipEvent_t ev : e)
+        if (ev) (void)hipEventDestroy(ev);
+    }
+  } events;
+  ESP_HIP(ctx, hipEventCreate(&events.e[0]));
+  ESP_HIP(ctx, hipEventCreate(&events.e[1]));
+  const hipEvent_t e0 = events.e[0], e1 = events.e[1];
   int best = -1;
   float best_t = 0.f;
   const int reps = 20;
@@ -493,8 +500,6 @@ static int tune_impl(esparse_ctx* ctx, int count, long long M, long long N, long
       best_t = ms;
     }
   }
-  (void)hipEventDestroy(e0);
-  (void)hipEventDestroy(e1);
   if (rc) return rc;
   ESP_REQUIRE(ctx, best >= 0, ESPARSE_EUNSUPPORTED, "no variant can run this shape");
   ctx->tuned[std::make_tuple(count, sparse, (int)dtype, M, N, K)] = best;

@@ -24,11 +24,23 @@
 //     operand of the dense instruction for token tile tt and step s; the channel re-ordering theta
 //     of Section 3.3 is applied here (X'[t, p] = X[t, theta[p]]), zero padded in both directions.
 #include <algorithm>
+#include <atomic>
 
 #include "common.h"
 
 #define WS_HEADER_BYTES 65536
 #define MAX_SPLIT 16
+// Kernels that need more than the default 64 KiB of dynamic LDS have that limit raised once per device; `done` is the
+// kernel's own mask of the devices where that has happened.
+template <class F>
+static hipError_t raise_dynamic_lds(std::atomic<unsigned long long>& done, int device, F* kernel, size_t bytes) {
+  const unsigned long long bit = 1ull << (device & 63);
+  if (device < 64 && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess && device < 64) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
+
 // fp32 partial tiles the workspace has room for: 16 K splits up to 128 tokens, 4 up to 512, none beyond
 static inline int esp_split_capacity(long long M) { return M <= 128 ? MAX_SPLIT : (M <= 512 ? 4 : 1); }
 #define ESP_MAX_GROUP 4  // products of one shape that may share a launch
@@ -1306,16 +1318,14 @@ static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const
 }
 
 template <int DT, int SPARSE, int MT, int RT, int NW, int NB>
-static hipError_t launch_stream_kernel(dim3 grid, hipStream_t st, const uint4* A, const uint16_t* meta16, const uint4* Xf, uint16_t* Y,
+static hipError_t launch_stream_kernel(int device, dim3 grid, hipStream_t st, const uint4* A, const uint16_t* meta16, const uint4* Xf, uint16_t* Y,
                                        float* partial, long long M, long long N, long long Mp, long long Np, long long Kp,
                                        long long span) {
   constexpr size_t smem = (size_t)NB * MT * 128 * 16;
-  static bool raised = false;  // once per process: allow the kernel more than the default 64 KiB of dynamic LDS
-  if (smem > 64 * 1024 && !raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_mm_stream<DT, SPARSE, MT, RT, NW, NB>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  static std::atomic<unsigned long long> raised{0};
+  if (smem > 64 * 1024) {
+    hipError_t e = raise_dynamic_lds(raised, device, &k_mm_stream<DT, SPARSE, MT, RT, NW, NB>, smem);
     if (e != hipSuccess) return e;
-    raised = true;
   }
   hipLaunchKernelGGL((k_mm_stream<DT, SPARSE, MT, RT, NW, NB>), grid, dim3(NW * 64), smem, st, A, meta16, Xf, Y, partial, M, N, Mp, Np,
                      Kp, span);
@@ -1344,10 +1354,10 @@ static int launch_stream(esparse_ctx* ctx, const Variant& v, hipStream_t st, con
   hipError_t e = hipErrorInvalidValue;
 #define ESP_STREAM(RTv, NWv, NBv)                                                                                           \
   if (v.rt == RTv && v.nw == NWv && v.tt == NBv)                                                                            \
-  e = (mt == 1)   ? launch_stream_kernel<DT, SPARSE, 1, RTv, NWv, NBv>(grid, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span) \
-      : (mt == 2) ? launch_stream_kernel<DT, SPARSE, 2, RTv, NWv, NBv>(grid, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span) \
-      : (mt == 4) ? launch_stream_kernel<DT, SPARSE, 4, RTv, NWv, NBv>(grid, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span) \
-                  : launch_stream_kernel<DT, SPARSE, 8, RTv, NWv, NBv>(grid, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span)
+  e = (mt == 1)   ? launch_stream_kernel<DT, SPARSE, 1, RTv, NWv, NBv>(ctx->device, grid, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span) \
+      : (mt == 2) ? launch_stream_kernel<DT, SPARSE, 2, RTv, NWv, NBv>(ctx->device, grid, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span) \
+      : (mt == 4) ? launch_stream_kernel<DT, SPARSE, 4, RTv, NWv, NBv>(ctx->device, grid, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span) \
+                  : launch_stream_kernel<DT, SPARSE, 8, RTv, NWv, NBv>(ctx->device, grid, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span)
   ESP_STREAM(1, 8, 4);
   ESP_STREAM(1, 8, 8);
   ESP_STREAM(2, 8, 4);
@@ -1387,16 +1397,12 @@ static int gather_rows_tok(long long Mp, long long K) {
 }
 
 template <int TOK>
-static hipError_t launch_gather_rows(hipStream_t st, const uint16_t* X, const int32_t* perm, long long M, long long K,
+static hipError_t launch_gather_rows(int device, hipStream_t st, const uint16_t* X, const int32_t* perm, long long M, long long K,
                                      long long Mp, long long Kp, uint4* Xf) {
   const size_t smem = (size_t)TOK * (K + 8) * 2;
-  static bool raised = false;  // once per process: allow the kernel more than the default 64 KiB of dynamic LDS
-  if (!raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gather_rows<TOK>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    raised = true;
-  }
+  static std::atomic<unsigned long long> raised{0};
+  hipError_t e = raise_dynamic_lds(raised, device, &k_gather_rows<TOK>, 160 * 1024);
+  if (e != hipSuccess) return e;
   const long long ntiles = Mp / 16, per = 16 / TOK;
   hipLaunchKernelGGL(k_gather_rows<TOK>, dim3((unsigned)((ntiles + 7) / 8 * 8 * per)), dim3(512), smem, st, X, perm, M, Mp, K, Kp, Xf);
   return hipGetLastError();
@@ -1409,11 +1415,11 @@ static int stage_activations(esparse_ctx* ctx, const void* X, const int32_t* per
   if (tok) {
     hipStream_t st = ctx->stream;
     switch (tok) {
-      case 16: ESP_HIP(ctx, launch_gather_rows<16>(st, Xh, perm, M, K, Mp, Kp, Xf)); break;
-      case 8: ESP_HIP(ctx, launch_gather_rows<8>(st, Xh, perm, M, K, Mp, Kp, Xf)); break;
-      case 4: ESP_HIP(ctx, launch_gather_rows<4>(st, Xh, perm, M, K, Mp, Kp, Xf)); break;
-      case 2: ESP_HIP(ctx, launch_gather_rows<2>(st, Xh, perm, M, K, Mp, Kp, Xf)); break;
-      default: ESP_HIP(ctx, launch_gather_rows<1>(st, Xh, perm, M, K, Mp, Kp, Xf)); break;
+      case 16: ESP_HIP(ctx, launch_gather_rows<16>(ctx->device, st, Xh, perm, M, K, Mp, Kp, Xf)); break;
+      case 8: ESP_HIP(ctx, launch_gather_rows<8>(ctx->device, st, Xh, perm, M, K, Mp, Kp, Xf)); break;
+      case 4: ESP_HIP(ctx, launch_gather_rows<4>(ctx->device, st, Xh, perm, M, K, Mp, Kp, Xf)); break;
+      case 2: ESP_HIP(ctx, launch_gather_rows<2>(ctx->device, st, Xh, perm, M, K, Mp, Kp, Xf)); break;
+      default: ESP_HIP(ctx, launch_gather_rows<1>(ctx->device, st, Xh, perm, M, K, Mp, Kp, Xf)); break;
     }
     return ESPARSE_OK;
   }
