@@ -368,6 +368,53 @@ def test_spmm_repeat_is_bitwise_identical_and_m0(esp, ctx):
     assert Y0.shape == (0, N)
 
 
+@pytest.mark.parametrize("M", [8, 100, 300])
+def test_spmm_replayed_from_a_hip_graph(esp, ctx, M):
+    """The calls enqueue kernels only (no allocation, no memset, no synchronisation), so a caller may capture them
+    into a HIP graph: every variant, staging included, captured once on a side stream and replayed three times with
+    new activations and eager work of the same context between the replays, must reproduce the eager result bit
+    for bit (decode, K-split, stream and tile kernels with their reduction launches)."""
+    N, K = 272, 2048
+    W = _rand((N, K), torch.float16, 61, scale=K ** -0.5)
+    theta = np.random.default_rng(2).permutation(K)
+    mask = orc.nm_mask_vectorised(_np(W), np.ones(K), theta, 2, 4)
+    th = torch.tensor(theta, dtype=torch.int32).cuda()
+    comp = ctx.compress(W.cuda(), torch.tensor(mask).cuda(), th, canonical=False)
+    Xs = [_rand((M, K), torch.float16, 62 + i).cuda() for i in range(3)]
+    other = _rand((M + 5, K), torch.float16, 70).cuda()
+    side = torch.cuda.Stream()
+    for v in range(esp.num_variants()):
+        try:
+            eager = [_bits(ctx.spmm(x, comp, th, variant=v)) for x in Xs]
+        except esp.EsparseError as e:
+            assert e.code == -2
+            continue
+        print(f"graph replay M={M} variant={esp.variant_name(v)}", flush=True)
+        xin = Xs[0].clone()
+        yout = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+        ws = torch.empty(esp.spmm_workspace(M, N, K) + 256, dtype=torch.uint8, device="cuda")
+        ws = ws[(-ws.data_ptr()) % 256:]
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            ctx.stage_activations(xin, th, N, ws)
+            ctx.spmm_staged(M, comp, ws, yout, variant=v)       # warm-up on the side stream
+            torch.cuda.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                ctx.stage_activations(xin, th, N, ws)
+                ctx.spmm_staged(M, comp, ws, yout, variant=v)
+        torch.cuda.synchronize()
+        for i in (1, 2, 0):
+            xin.copy_(Xs[i])
+            yout.zero_()
+            ctx.spmm(other, comp, th, variant=v)                # eager work between the replays (own workspace)
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert (_bits(yout) == eager[i]).all(), (esp.variant_name(v), i)
+        del g
+
+
 def test_workspace_too_small_and_bad_variant(esp, ctx):
     import ctypes as C
     N, K, M = 32, 256, 4
