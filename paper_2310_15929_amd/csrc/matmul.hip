@@ -443,7 +443,7 @@ __global__ void __launch_bounds__(256) k_mm_wave_tile(const uint4* __restrict__ 
 // the result does not depend on timing and no global synchronisation is needed.
 // grid = ceil(row tiles / RT), block = 64 * NW.
 // ------------------------------------------------------------------------------------------------
-template <int DT, int SPARSE, int MT, int RT, int NW, bool PAIRS>
+template <int DT, int SPARSE, int MT, int RT, int NW, int IDXM>
 __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long long M, long long N, long long Mp, long long Np,
                                                         long long Kp, int mc) {
   const uint4* __restrict__ A = args.A[blockIdx.y];
@@ -489,12 +489,75 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long lon
   // a pair, whose index halves are one 32-bit word - one load per row tile instead of two; the vector-memory path of
   // the CU, which these kernels saturate, counts instructions as well as bytes.  Otherwise wave w takes steps
   // w, w + NW, ... as they come.
-  constexpr bool pairs = PAIRS;
+  constexpr bool pairs = IDXM == 1;
   const uint32_t* meta32 = reinterpret_cast<const uint32_t*>(meta16);
   // K split over workgroups (matrices with few rows and many tokens, where every workgroup re-reading all the
   // activations costs more than the weights): workgroup z takes steps [kb, ke), an even kb
   const long long kb = gridDim.z > 1 ? (long long)blockIdx.z * args.sps : 0;
   const long long ke = gridDim.z > 1 && kb + args.sps < nks ? kb + args.sps : nks;
+  if constexpr (IDXM == 2) {
+    // quads (2:4): wave w takes the four steps 4 w .. 4 w + 3, then 4 (w + NW) .., whose index halves are one 8-byte
+    // unit per lane: one index load per row tile and quad instead of four.  The vector-memory path of a CU works
+    // through a load lane by lane whatever its width, so a 2-byte index load costs what a 16-byte weight load costs.
+    const uint2* meta64 = reinterpret_cast<const uint2*>(meta16);
+    for (long long ks = kb + 4 * wave; ks < ke; ks += 4 * NW) {
+      uint32_t iw[2][RT];
+#pragma unroll
+      for (int i = 0; i < RT; i++) {
+        const uint2 w = meta64[(rts[i] * (nks / 4) + ks / 4) * 64 + lane];
+        iw[0][i] = w.x;
+        iw[1][i] = w.y;
+      }
+      uint4 a[4][RT], b0[4][MT], b1[4][MT];
+      if (MT == 1 && mc) {
+        // the padding lanes hold zeros; set before the loads (and opaque to the compiler), so that the loads of the
+        // live lanes land on top of them: a zero moved in after the load would have to wait for the load
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+          b0[u][0] = uint4{0u, 0u, 0u, 0u};
+          b1[u][0] = uint4{0u, 0u, 0u, 0u};
+          asm volatile("" : "+v"(b0[u][0].x), "+v"(b0[u][0].y), "+v"(b0[u][0].z), "+v"(b0[u][0].w));
+          asm volatile("" : "+v"(b1[u][0].x), "+v"(b1[u][0].y), "+v"(b1[u][0].z), "+v"(b1[u][0].w));
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; u++) {
+        const long long k = ks + u;
+#pragma unroll
+        for (int i = 0; i < RT; i++) a[u][i] = A[(rts[i] * nks + k) * 64 + lane];
+      }
+      if (MT == 1 && mc) {
+        const int c = lane & 15, g = lane >> 4;
+        const uint4* Xc = Xf + Kp * 2;  // the compact copy behind the 16 x Kp fragment-major one
+        if (c < mc) {
+#pragma unroll
+          for (int u = 0; u < 4; u++) {
+            const long long k = ks + u;
+            b0[u][0] = Xc[((2 * k) * 4 + g) * mc + c];
+            b1[u][0] = Xc[((2 * k + 1) * 4 + g) * mc + c];
+          }
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+          const long long k = ks + u;
+#pragma unroll
+          for (int j = 0; j < MT; j++) {
+            const long long tt = (j < ntt) ? j : ntt - 1;
+            b0[u][j] = Xf[(tt * (2 * nks) + 2 * k) * 64 + lane];
+            b1[u][j] = Xf[(tt * (2 * nks) + 2 * k + 1) * 64 + lane];
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; u++)
+#pragma unroll
+        for (int i = 0; i < RT; i++)
+#pragma unroll
+          for (int j = 0; j < MT; j++)
+            acc[i][j] = smfmac16<DT, 0>(a[u][i], b0[u][j], b1[u][j], acc[i][j], (int)((u & 1) ? iw[u >> 1][i] >> 16 : iw[u >> 1][i]));
+    }
+  } else
   for (long long ks = kb + (pairs ? 2 * wave : wave); ks < ke; ks += 2 * NW) {
     const bool second = pairs || ks + NW < ke;  // wave-uniform
     const long long kk[2] = {ks, pairs ? ks + 1 : (second ? ks + NW : ks)};
@@ -1120,6 +1183,7 @@ struct Variant {
   int rt, tt;      // row tiles / token tiles per wave (ksplit: row tiles per workgroup, tt unused: MT follows M)
   int split_mode;  // wave and tile kinds: 0 = never split K, 1 = split K over workgroups to fill the chip
   int nw;          // ksplit kind: waves per workgroup; tile kind: waves along the tokens (the workgroup has 2 x nw waves)
+  int quads;       // ksplit kind: 1 = a wave takes four consecutive steps with one index load (2:4, at most 16 tokens)
 };
 static const Variant kVariants[] = {
     {"wave_r2_t1_splitk", KIND_WAVE, 2, 1, 1, 0},
@@ -1156,6 +1220,12 @@ static const Variant kVariants[] = {
     // macro tiles that fills the 256 CUs exactly where 256-row tiles leave a partly filled round
     {"tile_w8_r288_t128", KIND_TILE, 9, 2, 0, 4},
     {"tile_w8_r320_t128", KIND_TILE, 10, 2, 0, 4},
+    // decode kernels for at most 16 tokens whose waves take four consecutive steps and read their index halves with
+    // one 8-byte load (2:4 only): 7-13 % on 4096 x 11008, 2-5 % on q/k/v in one launch, level or behind elsewhere
+    {"ksplit_w8_r1_q", KIND_KSPLIT, 1, 0, 0, 8, 1},
+    {"ksplit_w16_r1_q", KIND_KSPLIT, 1, 0, 0, 16, 1},
+    {"ksplit_w8_r2_q", KIND_KSPLIT, 2, 0, 0, 8, 1},
+    {"ksplit_w8_r4_q", KIND_KSPLIT, 4, 0, 0, 8, 1},
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -1169,7 +1239,7 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
   const Variant& var = kVariants[v];
   if (sparse == 2) {
     // 4:8: decode kernels only; longer inputs go through them 64 tokens at a time
-    if (var.kind != KIND_KSPLIT) return false;
+    if (var.kind != KIND_KSPLIT || var.quads) return false;
     const long long mc = M < 64 ? M : 64;
     const long long mt = mc <= 16 ? 1 : (mc <= 32 ? 2 : 4);
     return (long long)var.nw * var.rt * mt * 1024 <= 160 * 1024;
@@ -1177,6 +1247,7 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
   if (var.split_mode == 1 && esp_split_capacity(M) == 1) return false;  // no room for partial tiles beyond 512 tokens
   if (var.kind == KIND_KSPLIT) {
     if (M > 64) return false;
+    if (var.quads && (sparse != 1 || M > 16)) return false;
     const long long mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);  // token tiles; the waves' partial tiles must fit the LDS
     if ((long long)var.nw * var.rt * mt * 1024 > 160 * 1024) return false;
   }
@@ -1246,13 +1317,17 @@ static void launch_ksplit(const Variant& v, hipStream_t st, KsplitArgs args, int
   dim3 grid((unsigned)((nrt + v.rt - 1) / v.rt), (unsigned)count, (unsigned)nsplit);
   const size_t smem = (size_t)v.nw * v.rt * MT * 64 * 16;
   const bool pairs = SPARSE == 1 && MT >= 2 && ((sps / 2) % v.nw) == 0 && nks % sps == 0;
+  const bool quads = v.quads != 0;
 #define LAUNCH(R, W)                                                                                                          \
   do {                                                                                                                        \
-    if (SPARSE == 1 && MT >= 2 && pairs)                                                                                      \
-      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, (SPARSE == 1 && MT >= 2)>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, \
+    if (SPARSE == 1 && MT == 1 && quads && ((R == 1) || (W == 8 && (R == 2 || R == 4))))                                      \
+      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, (SPARSE == 1 && MT == 1 && ((R == 1) || (W == 8 && (R == 2 || R == 4))) ? 2 : 0)>), \
+                         grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp, mc);                                           \
+    else if (SPARSE == 1 && MT >= 2 && pairs)                                                                                 \
+      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, (SPARSE == 1 && MT >= 2 ? 1 : 0)>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, \
                          Kp, mc);                                                                                             \
     else                                                                                                                      \
-      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, false>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp, mc); \
+      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, 0>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp, mc); \
   } while (0)
   if (v.nw == 16 && v.rt == 1) LAUNCH(1, 16);
   else if (v.nw == 16 && v.rt == 2) LAUNCH(2, 16);

@@ -247,7 +247,11 @@ def _spmm_case(esp, ctx, M, N, K, dtype, seed, use_perm=True):
         torch.cuda.synchronize()
         err = orc.rowwise_rel_error(_np(Y), Yref)
         assert err.max() <= TOL[dtype], ("sparse", esp.variant_name(v), err.max())
-        Yd = ctx.dense_gemm(Xd, packed, N, variant=v)
+        try:
+            Yd = ctx.dense_gemm(Xd, packed, N, variant=v)
+        except esp.EsparseError as e:
+            assert e.code == -2                      # a variant of the 2:4 product only (index loads)
+            continue
         torch.cuda.synchronize()
         err = orc.rowwise_rel_error(_np(Yd), Ydref)
         assert err.max() <= TOL[dtype], ("dense", esp.variant_name(v), err.max())
