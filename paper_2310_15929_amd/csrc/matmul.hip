@@ -484,7 +484,9 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long lon
 #pragma unroll
     for (int j = 0; j < MT; j++) acc[i][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
-  // two steps per trip (all loads of both steps are issued before the first multiply).  PAIRS (chosen by the host where
+  // IDXM = how a wave takes its steps and reads their index halves: 0 = steps w, w + NW, ... with a 16-bit load each;
+  // 1 = step pairs; 2 = quads (below).
+  // Two steps per trip (all loads of both steps are issued before the first multiply).  Pairs (chosen by the host where
   // the step pairs divide evenly among the waves and there are two or more token tiles): a trip takes the two steps of
   // a pair, whose index halves are one 32-bit word - one load per row tile instead of two; the vector-memory path of
   // the CU, which these kernels saturate, counts instructions as well as bytes.  Otherwise wave w takes steps
