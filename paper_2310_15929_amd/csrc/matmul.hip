@@ -1228,6 +1228,9 @@ static const Variant kVariants[] = {
     {"ksplit_w16_r1_q", KIND_KSPLIT, 1, 0, 0, 16, 1},
     {"ksplit_w8_r2_q", KIND_KSPLIT, 2, 0, 0, 8, 1},
     {"ksplit_w8_r4_q", KIND_KSPLIT, 4, 0, 0, 8, 1},
+    // stream kernel with nine waves (144 rows per workgroup): 36864 rows are then exactly 256 row blocks, one per CU,
+    // and no span cuts a row block (no partial tiles, no reduction launch)
+    {"stream_w9_r1_d3", KIND_STREAM, 1, 4, 1, 9},
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -1439,6 +1442,7 @@ static int launch_stream(esparse_ctx* ctx, const Variant& v, hipStream_t st, con
   ESP_STREAM(1, 8, 8);
   ESP_STREAM(2, 8, 4);
   ESP_STREAM(2, 8, 6);
+  ESP_STREAM(1, 9, 4);
 #undef ESP_STREAM
   ESP_HIP(ctx, e);
   if (span % nks != 0) {  // some row block is cut
