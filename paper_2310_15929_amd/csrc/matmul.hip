@@ -1231,6 +1231,8 @@ static const Variant kVariants[] = {
     // stream kernel with nine waves (144 rows per workgroup): 36864 rows are then exactly 256 row blocks, one per CU,
     // and no span cuts a row block (no partial tiles, no reduction launch)
     {"stream_w9_r1_d3", KIND_STREAM, 1, 4, 1, 9},
+    // eleven waves (176 rows): 22016 rows are 126 row blocks, two aligned spans each
+    {"stream_w11_r1_d3", KIND_STREAM, 1, 4, 1, 11},
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -1443,6 +1445,7 @@ static int launch_stream(esparse_ctx* ctx, const Variant& v, hipStream_t st, con
   ESP_STREAM(2, 8, 4);
   ESP_STREAM(2, 8, 6);
   ESP_STREAM(1, 9, 4);
+  ESP_STREAM(1, 11, 4);
 #undef ESP_STREAM
   ESP_HIP(ctx, e);
   if (span % nks != 0) {  // some row block is cut
