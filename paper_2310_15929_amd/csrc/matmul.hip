@@ -1098,7 +1098,7 @@ __device__ __attribute__((always_inline)) void stream_pipeline(uint4* __restrict
     st.x_src[p] = Xf + (tt * (2 * nks) + (q & 1)) * 64;
     st.x_dst[p] = (unsigned)q * 64;
   }
-  // the segments of this span: one per row block it touches (spans, nks and hence k0, k1 are multiples of four steps)
+  // the segments of this span: one per row block it touches (spans and nks, and hence k0 and k1, are even)
   for (long long s = s_begin; s < s_end;) {
     const long long rb = s / nks;
     const unsigned k0 = (unsigned)(s - rb * nks);
@@ -1415,12 +1415,18 @@ static hipError_t launch_stream_kernel(int device, dim3 grid, hipStream_t st, co
 }
 
 // span of the stream kernels: steps per workgroup when `slots` workgroups share nrb row blocks of nks steps.
-// A multiple of four steps, at least 8, and long enough that a row block has at most MAX_SPLIT pieces.
+// An even number of steps (a step's index half is addressed by its parity within a pair, and its ring slot has
+// that parity), at least 8, and long enough that a row block has at most MAX_SPLIT pieces.
 static long long stream_span(long long nrb, long long nks, long long slots) {
   long long span = (nrb * nks + slots - 1) / slots;
   span = std::max<long long>(span, 8);
   span = std::max<long long>(span, (nks + MAX_SPLIT - 3) / (MAX_SPLIT - 2));  // pieces <= (nks - 1) / span + 2
-  return (span + 3) / 4 * 4;
+  span = (span + 1) / 2 * 2;
+  // a span that divides the steps of a row block keeps every span inside one row block (one segment and one partial
+  // tile per workgroup instead of two): worth up to a fifth fewer workgroups
+  for (long long a = span; a <= nks && a * 5 <= span * 6; a += 2)
+    if (nks % a == 0) return a;
+  return span;
 }
 
 template <int DT, int SPARSE>
