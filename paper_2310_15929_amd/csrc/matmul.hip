@@ -24,6 +24,7 @@
 //     operand of the dense instruction for token tile tt and step s; the channel re-ordering theta
 //     of Section 3.3 is applied here (X'[t, p] = X[t, theta[p]]), zero padded in both directions.
 #include <algorithm>
+#include <cstring>
 #include <atomic>
 
 #include "common.h"
@@ -1263,14 +1264,37 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
   return true;
 }
 
+static int variant_index(const char* name) {
+  for (int v = 0; v < kNumVariants; v++)
+    if (!strcmp(kVariants[v].name, name)) return v;
+  return -1;
+}
+
 int esp_default_variant(long long M, long long N, long long K, int sparse) {
-  (void)K;
   if (M <= 32 || sparse == 2) {
     const long long nrt = esp_round_up(N, 16) / 16;
     return nrt <= 320 ? 4 : 5;  // ksplit_w16_r1 / ksplit_w16_r2
   }
-  if (M <= 64) return 19;   // stream_w8_r2_d3
-  if (M <= 128) return 17;  // stream_w8_r1_d3
+  if (M <= 128) {
+    // stream kernels: the number of waves (rows per workgroup) whose row blocks, each cut into p equal spans of an even
+    // number of steps, come closest to one workgroup per CU without a span crossing a row block
+    const long long nrt = esp_round_up(N, 16) / 16, nks = esp_round_up(K, 256) / 64;
+    static const struct { int nw; const char* name; } cand[] = {{8, "stream_w8_r1_d3"}, {9, "stream_w9_r1_d3"}, {11, "stream_w11_r1_d3"}};
+    long long best = 0;
+    const char* pick = nullptr;
+    for (const auto& c : cand) {
+      const long long nrb = (nrt + c.nw - 1) / c.nw;
+      if (nrb > 256) continue;
+      long long pcs = 256 / nrb;
+      while (pcs > 1 && (nks % pcs != 0 || (nks / pcs) % 2 != 0 || nks / pcs < 8)) pcs--;
+      if (nrb * pcs > best) {
+        best = nrb * pcs;
+        pick = c.name;
+      }
+    }
+    if (best >= 200) return variant_index(pick);
+    return M <= 64 ? 19 : 17;  // stream_w8_r2_d3 / stream_w8_r1_d3 with spans cut where they fall
+  }
   // 8-wave tile kernels: the largest macro tile that still gives half of the 256 CUs a tile
   const long long rows = sparse ? 256 : 128;
   const long long nrb = (N + rows - 1) / rows;
