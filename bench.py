@@ -195,29 +195,29 @@ def main():
         ctx.tune_save(args.tune_save)
 
     def step_sparse():
-        for mats in layers:
-            for M in M_LIST:
+        for M in M_LIST:          # M outermost: between two uses of a matrix lie all the other layers' weights
+            for mats in layers:
                 for names, _, stream in GROUPS:
                     ctx.spmm_group([acts[(stream, M)]] * len(names), [mats[n]["comp"] for n in names],
                                    [mats[n]["perm"] for n in names], outs=[outs[(n, M)] for n in names])
 
     def step_dense():
-        for mats in layers:
-            for M in M_LIST:
+        for M in M_LIST:          # M outermost: between two uses of a matrix lie all the other layers' weights
+            for mats in layers:
                 for names, skey, stream in GROUPS:
                     ctx.dense_gemm_group([acts[(stream, M)]] * len(names), [mats[n]["packed"] for n in names], shapes[skey][0],
                                          outs=[outs[(n, M)] for n in names])
 
     def step_sparse_single():
-        for mats in layers:
-            for M in M_LIST:
+        for M in M_LIST:          # M outermost: between two uses of a matrix lie all the other layers' weights
+            for mats in layers:
                 for name, _, stream in MATS:
                     m = mats[name]
                     ctx.spmm(acts[(stream, M)], m["comp"], m["perm"], out=outs[(name, M)])
 
     def step_hipblaslt():
-        for mats in layers:
-            for M in M_LIST:
+        for M in M_LIST:          # M outermost: between two uses of a matrix lie all the other layers' weights
+            for mats in layers:
                 for name, _, stream in MATS:
                     m = mats[name]
                     torch.matmul(acts[(stream, M)], m["W"].t(), out=outs[(name, M)])
@@ -529,14 +529,14 @@ def main():
             ctx.tune(M, m["N"], m["K"], dcode, False)
 
     def step_fused_sparse():
-        for fl_ in fused_layers:
-            for M in M_LIST:
+        for M in M_LIST:
+            for fl_ in fused_layers:
                 for n, m in fl_.items():
                     ctx.spmm(acts[(m["stream"], M)], m["comp"], m["perm"], out=f_outs[(n, M)])
 
     def step_fused_dense():
-        for fl_ in fused_layers:
-            for M in M_LIST:
+        for M in M_LIST:
+            for fl_ in fused_layers:
                 for n, m in fl_.items():
                     ctx.dense_gemm(acts[(m["stream"], M)], m["packed"], m["N"], out=f_outs[(n, M)])
 

@@ -527,7 +527,7 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long lon
       for (int u = 0; u < 4; u++) {
         const long long k = ks + u;
 #pragma unroll
-        for (int i = 0; i < RT; i++) a[u][i] = A[(rts[i] * nks + k) * 64 + lane];
+        for (int i = 0; i < RT; i++) a[u][i] = load_stream_16(A + (rts[i] * nks + k) * 64 + lane);
       }
       if (MT == 1 && mc) {
         const int c = lane & 15, g = lane >> 4;
@@ -579,11 +579,11 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long lon
 #pragma unroll
       for (int i = 0; i < RT; i++) {
         if (SPARSE) {  // 2:4: kept values + index half; 4:8: kept values of two groups + their two bitmaps
-          a[u][i] = A[(rts[i] * nks + kk[u]) * 64 + lane];
+          a[u][i] = load_stream_16(A + (rts[i] * nks + kk[u]) * 64 + lane);
           if (!pairs) idx[u][i] = (int)meta16[((rts[i] * (nks / 4) + kk[u] / 4) * 64 + lane) * 4 + (kk[u] & 3)];
         } else {
-          a[u][i] = A[(rts[i] * (2 * nks) + 2 * kk[u]) * 64 + lane];
-          a2[u][i] = A[(rts[i] * (2 * nks) + 2 * kk[u] + 1) * 64 + lane];
+          a[u][i] = load_stream_16(A + (rts[i] * (2 * nks) + 2 * kk[u]) * 64 + lane);
+          a2[u][i] = load_stream_16(A + (rts[i] * (2 * nks) + 2 * kk[u] + 1) * 64 + lane);
         }
       }
       if (MT == 1 && mc) {
