@@ -8,8 +8,8 @@ shuffle (blocks of 64), compressed, and multiplied with the sparse-MFMA kernels.
 runs the same measurement on the other full-size workloads (prefill sizes among them).
 
 One step = every linear layer of LAYERS distinct layer instances at every M (LAYERS x 7 x 3 sparse
-products).  The instances' compressed weights total > 512 MB, so the 256 MB last-level cache cannot
-hold them between uses.  All inputs are resident in HBM before the timed region; a step is replayed
+products), M outermost: between two uses of a matrix come the weights of all instances (> 512 MB
+compressed), so the 256 MB last-level cache cannot hold them from one use to the next.  All inputs are resident in HBM before the timed region; a step is replayed
 as one HIP graph.  value = dense-equivalent flops (2 M N K per product) per second over the timed
 steps.  The same steps run with the in-repo dense MFMA kernels give the speedup; hipBLASLt (through
 torch.matmul) is quoted as a reference point only.
