@@ -34,12 +34,12 @@ HBM_PEAK_GBS = 8000.0
 # `bench.py --counter-probe` and scaled by the same counters' reading for a copy kernel of known size;
 # key (config, M, N, K), value = fetched + written bytes.  The summaries are kept under profiles/.
 MEASURED_TRAFFIC = {
-    (2, 1, 4096, 4096): 19008938, (2, 8, 4096, 4096): 19518502, (2, 32, 4096, 4096): 21288835,
-    (2, 1, 11008, 4096): 50863653, (2, 8, 11008, 4096): 51519559, (2, 32, 11008, 4096): 53581481,
-    (2, 1, 4096, 11008): 50958533, (2, 8, 4096, 11008): 52247280, (2, 32, 4096, 11008): 56657213,
+    (2, 1, 4096, 4096): 19000067, (2, 8, 4096, 4096): 19515433, (2, 32, 4096, 4096): 21280647,
+    (2, 1, 11008, 4096): 50857348, (2, 8, 11008, 4096): 51494226, (2, 32, 11008, 4096): 53579441,
+    (2, 1, 4096, 11008): 50969804, (2, 8, 4096, 11008): 52258551, (2, 32, 4096, 11008): 56674628,
     # group launches (config, M, N, K, members)
-    (2, 1, 4096, 4096, 3): 56900193, (2, 8, 4096, 4096, 3): 58442878, (2, 32, 4096, 4096, 3): 63757974,
-    (2, 1, 11008, 4096, 2): 101681446, (2, 8, 11008, 4096, 2): 102983700, (2, 32, 11008, 4096, 2): 107106647,
+    (2, 1, 4096, 4096, 3): 56889280, (2, 8, 4096, 4096, 3): 58435720, (2, 32, 4096, 4096, 3): 63747745,
+    (2, 1, 11008, 4096, 2): 101700062, (2, 8, 11008, 4096, 2): 102918379, (2, 32, 11008, 4096, 2): 107121009,
     (3, 512, 5120, 5120): 76809032, (3, 2048, 5120, 5120): 225381167, (3, 512, 13824, 5120): 144959199,
     (3, 2048, 13824, 5120): 510778932, (3, 512, 5120, 13824): 198251888, (3, 2048, 5120, 13824): 572712129,
 }
