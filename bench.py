@@ -44,7 +44,7 @@ MEASURED_TRAFFIC = {
     (3, 2048, 13824, 5120): 510778932, (3, 512, 5120, 13824): 198251888, (3, 2048, 5120, 13824): 572712129,
 }
 SPARSE_MFMA_PEAK_TFLOPS = 5000.0   # dense-equivalent flops of the 2:4 MFMA path: twice the dense 16-bit peak of 2.5 PFLOP/s
-DEFAULT_LAYERS = {2: 6, 3: 3, 4: 2, 5: 2}   # enough instances that every shape rotates over > 256 MB of weights
+DEFAULT_LAYERS = {2: 6, 3: 4, 4: 2, 5: 2}   # enough instances that every shape rotates over > 256 MB of weights
 # (name, layer-shape key, calibration / activation stream, products per layer with this shape)
 MATS_LLAMA = [("q", "qkvo", "attn_in"), ("k", "qkvo", "attn_in"), ("v", "qkvo", "attn_in"), ("o", "qkvo", "o_in"),
               ("gate", "gate_up", "mlp_in"), ("up", "gate_up", "mlp_in"), ("down", "down", "down_in")]
