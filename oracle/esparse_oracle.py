@@ -175,25 +175,38 @@ def _top_n_sum_rows(xi_cols: np.ndarray, n: int) -> np.ndarray:
     return t
 
 
-ROW_SUM_LANES = 16
+def sum_rows(t: np.ndarray, order="sequential") -> float:
+    """Sum of the per-row terms t[0..N-1] in float64.
 
-
-def group_value(xi_cols: np.ndarray, n: int) -> float:
-    """v(g) = sum over the output rows of the row's retained metric in the group: the
-    contribution of one group of m channels to eq. (5).
-
-    Reading (the paper does not fix the order of this sum; float64 addition is not
-    associative, so one must be fixed): 16 interleaved sub-sums - sub-sum l adds the rows
-    j = l, l + 16, l + 32, ... in ascending order - which are then added in ascending l.
+    Reading (eq. 5 does not say in which order its terms are added, and float64 addition is not
+    associative): the plain one - rows in ascending order, one running sum.  The other orders exist
+    for the pin that shows the search result does not depend on this choice on the workloads:
+    ("lanes", L): L interleaved sub-sums (sub-sum l takes rows l, l + L, ...) added in ascending l;
+    "exact": the correctly rounded sum (math.fsum).
     """
-    t = _top_n_sum_rows(np.asarray(xi_cols, dtype=np.float64), n)
-    lanes = [0.0] * ROW_SUM_LANES
+    if order == "sequential":
+        acc = 0.0
+        for j in range(t.shape[0]):
+            acc = acc + float(t[j])
+        return acc
+    if order == "exact":
+        return math.fsum(t.tolist())
+    kind, L = order
+    assert kind == "lanes"
+    lanes = [0.0] * L
     for j in range(t.shape[0]):
-        lanes[j % ROW_SUM_LANES] = lanes[j % ROW_SUM_LANES] + float(t[j])
+        lanes[j % L] = lanes[j % L] + float(t[j])
     acc = lanes[0]
-    for l in range(1, ROW_SUM_LANES):
+    for l in range(1, L):
         acc = acc + lanes[l]
     return acc
+
+
+def group_value(xi_cols: np.ndarray, n: int, order="sequential") -> float:
+    """v(g) = sum over the output rows of the row's retained metric in the group: the
+    contribution of one group of m channels to eq. (5).  Rows are added in ascending order."""
+    t = _top_n_sum_rows(np.asarray(xi_cols, dtype=np.float64), n)
+    return sum_rows(t, order)
 
 
 def retained_metric(W: np.ndarray, s: np.ndarray, theta: np.ndarray, n: int, m: int) -> float:
@@ -210,7 +223,7 @@ def retained_metric(W: np.ndarray, s: np.ndarray, theta: np.ndarray, n: int, m: 
 # Section 3.3: local block shuffle (Algorithm 1, steps 3-14)
 # --------------------------------------------------------------------------------------
 
-def _block_swap_search(xi_blk: np.ndarray, n: int, m: int):
+def _block_swap_search(xi_blk: np.ndarray, n: int, m: int, order="sequential"):
     """One call of the search step of Algorithm 1 on a block whose columns are in the
     block's current order.  Returns (i, j, delta) for the pair of positions in different
     groups whose exchange raises the retained metric most, or None if no exchange raises it.
@@ -222,7 +235,7 @@ def _block_swap_search(xi_blk: np.ndarray, n: int, m: int):
     """
     Bsz = xi_blk.shape[1]
     G = Bsz // m
-    v = [group_value(xi_blk[:, g * m:(g + 1) * m], n) for g in range(G)]
+    v = [group_value(xi_blk[:, g * m:(g + 1) * m], n, order) for g in range(G)]
     best = None
     for i in range(Bsz):
         a = i // m
@@ -234,8 +247,8 @@ def _block_swap_search(xi_blk: np.ndarray, n: int, m: int):
             cols_b = list(range(b * m, (b + 1) * m))
             cols_a[i - a * m] = j
             cols_b[j - b * m] = i
-            va2 = group_value(xi_blk[:, cols_a], n)
-            vb2 = group_value(xi_blk[:, cols_b], n)
+            va2 = group_value(xi_blk[:, cols_a], n, order)
+            vb2 = group_value(xi_blk[:, cols_b], n, order)
             delta = (va2 + vb2) - (v[a] + v[b])
             if delta > 0.0 and (best is None or delta > best[2]):
                 best = (i, j, delta)
@@ -243,13 +256,13 @@ def _block_swap_search(xi_blk: np.ndarray, n: int, m: int):
 
 
 def local_block_shuffle(W: np.ndarray, s: np.ndarray, theta0: np.ndarray, n: int, m: int,
-                        B: int, max_swaps: int = 0, blocks=None):
+                        B: int, max_swaps: int = 0, blocks=None, order="sequential"):
     """Greedy channel exchanges inside blocks of B consecutive positions (Algorithm 1).
 
     For every block: repeat { find the best exchange; stop if none improves; apply it and
     update theta }.  `max_swaps` > 0 caps the number of exchanges per block (0 = no cap).
-    `blocks` restricts the work to the listed block numbers (others keep theta0).
-    Returns (theta, swaps_per_block).
+    `blocks` restricts the work to the listed block numbers (others keep theta0); `order` is
+    the order of the row sums (see sum_rows).  Returns (theta, swaps_per_block).
     """
     theta = np.array(theta0, dtype=np.int64).copy()
     K = theta.shape[0]
@@ -264,7 +277,7 @@ def local_block_shuffle(W: np.ndarray, s: np.ndarray, theta0: np.ndarray, n: int
             if max_swaps > 0 and swaps[blk] >= max_swaps:
                 break
             xi_blk = xi_full[:, theta[lo:lo + B]]
-            res = _block_swap_search(xi_blk, n, m)
+            res = _block_swap_search(xi_blk, n, m, order)
             if res is None:
                 break
             i, j = res[0], res[1]
@@ -482,14 +495,23 @@ def prune(Xc: np.ndarray, W: np.ndarray, n: int, m: int, B: int, alpha: float, b
 # return bit-identical results to the loop versions on small inputs.
 # --------------------------------------------------------------------------------------
 
-def _seq_sum_rows(t: np.ndarray) -> np.ndarray:
-    """Sum over axis 0 in the order of `group_value` (16 interleaved sub-sums added in
-    ascending order), for every column.  Rows are padded with +0.0, which changes no sum of
-    non-negative terms."""
-    L = ROW_SUM_LANES
+def _sum_rows_axis0(t: np.ndarray, order="sequential") -> np.ndarray:
+    """`sum_rows` for every column of t at once (axis 0 = rows): the same additions in the same
+    order, each a numpy operation over the columns."""
+    if order == "sequential":
+        acc = np.zeros(t.shape[1:], dtype=np.float64)
+        for j in range(t.shape[0]):
+            acc = acc + t[j]
+        return acc
+    if order == "exact":
+        flat = t.reshape(t.shape[0], -1)
+        out = np.array([math.fsum(flat[:, q].tolist()) for q in range(flat.shape[1])], dtype=np.float64)
+        return out.reshape(t.shape[1:])
+    kind, L = order
+    assert kind == "lanes"
     N = t.shape[0]
     pad = (-N) % L
-    if pad:
+    if pad:     # +0.0 changes no sum of non-negative terms
         t = np.concatenate([t, np.zeros((pad,) + t.shape[1:], dtype=np.float64)], axis=0)
     r = t.reshape((t.shape[0] // L, L) + t.shape[1:])
     lanes = np.zeros(r.shape[1:], dtype=np.float64)
@@ -509,10 +531,10 @@ def _top_n_sum_lastaxis(x: np.ndarray, n: int) -> np.ndarray:
     return t
 
 
-def _block_swap_search_vectorised(xi_blk: np.ndarray, n: int, m: int):
+def _block_swap_search_vectorised(xi_blk: np.ndarray, n: int, m: int, order="sequential"):
     N, Bsz = xi_blk.shape
     G = Bsz // m
-    v = _seq_sum_rows(_top_n_sum_lastaxis(xi_blk.reshape(N, G, m), n))       # [G]
+    v = _sum_rows_axis0(_top_n_sum_lastaxis(xi_blk.reshape(N, G, m), n), order)       # [G]
     pairs = [(i, j) for i in range(Bsz) for j in range(i + 1, Bsz) if i // m != j // m]
     best = None
     chunk = max(1, (1 << 24) // max(1, N * 2 * m))
@@ -528,7 +550,7 @@ def _block_swap_search_vectorised(xi_blk: np.ndarray, n: int, m: int):
             cb[j - b * m] = i
             cols[q, 0] = ca
             cols[q, 1] = cb
-        vals = _seq_sum_rows(_top_n_sum_lastaxis(xi_blk[:, cols], n))          # [P, 2]
+        vals = _sum_rows_axis0(_top_n_sum_lastaxis(xi_blk[:, cols], n), order)          # [P, 2]
         for q, (i, j) in enumerate(pr):
             a, b = i // m, j // m
             delta = (float(vals[q, 0]) + float(vals[q, 1])) - (float(v[a]) + float(v[b]))
@@ -537,7 +559,7 @@ def _block_swap_search_vectorised(xi_blk: np.ndarray, n: int, m: int):
     return best
 
 
-def local_block_shuffle_vectorised(W, s, theta0, n, m, B, max_swaps=0, blocks=None):
+def local_block_shuffle_vectorised(W, s, theta0, n, m, B, max_swaps=0, blocks=None, order="sequential"):
     theta = np.array(theta0, dtype=np.int64).copy()
     K = theta.shape[0]
     assert K % B == 0 and B % m == 0
@@ -553,7 +575,7 @@ def local_block_shuffle_vectorised(W, s, theta0, n, m, B, max_swaps=0, blocks=No
                 break
             ch = theta[lo:lo + B]
             xi_blk = A[:, ch] * s[ch][None, :]
-            res = _block_swap_search_vectorised(xi_blk, n, m)
+            res = _block_swap_search_vectorised(xi_blk, n, m, order)
             if res is None:
                 break
             i, j = res[0], res[1]

@@ -7,8 +7,11 @@
 //   - sums of squares and column sums of |w| are accumulated EXACTLY: every term is split by its
 //     binary exponent into one of a few 64-bit integer accumulators (16 exponents per accumulator),
 //     and the host adds the accumulators exactly and rounds once;
-//   - the retained metric of a candidate group is summed over the output rows 0..N-1 by ONE thread,
-//     in that order, in float64 without contraction;
+//   - the retained metric of a candidate group is summed over the output rows in a FIXED order (16
+//     interleaved sub-sums, see ROW_LANES) in float64 without contraction, so repeated runs make the
+//     same exchanges; eq. (5) fixes no order for that sum, and the exchanges Algorithm 1 makes do not
+//     hinge on it where candidates are not tied to the last bit (the tests compare them with a plain
+//     ascending-row sum);
 //   - logs, square roots and the sort of K channel means run on the host (K values each).
 #include <algorithm>
 #include <cmath>
@@ -378,9 +381,10 @@ __device__ __forceinline__ double top_n_sum(double* v) {
   return t;
 }
 
-// Order of every sum over output rows (eq. 5): ROW_LANES = 16 interleaved sub-sums - sub-sum l adds the
-// rows j = l, l + 16, l + 32, ... in ascending order - which are then added in ascending l.  A fixed
-// order that 16 lanes can work on at once; the lanes of one sum are 16 neighbouring lanes of a wave.
+// Order of every sum over output rows (eq. 5 prescribes none): ROW_LANES = 16 interleaved sub-sums -
+// sub-sum l adds the rows j = l, l + 16, l + 32, ... in ascending order - which are then added in
+// ascending l.  A fixed order that 16 lanes can work on at once; the lanes of one sum are 16
+// neighbouring lanes of a wave.  It differs from an ascending-row sum in the last bits only.
 #define ROW_LANES 16
 
 __device__ __forceinline__ double lanes_total(double part) {

@@ -28,6 +28,12 @@ def main():
     X = wl.activations(1, "linear", 16).numpy()
     alpha = wl.default_alpha(Xc.shape[0])
     theta, mask, s, swaps = orc.prune(Xc, W, 2, 4, 64, alpha)
+    # eq. (5) fixes no order for its sum over the rows: the result must not hinge on the oracle's choice
+    theta0 = orc.global_naive_shuffle(W, s, 4)
+    orders = ["sequential", ("lanes", 16), "exact"]
+    for order in orders[1:]:
+        t2, s2 = orc.local_block_shuffle_vectorised(W, s, theta0, 2, 4, 64, order=order)
+        assert (t2 == theta).all() and (s2 == swaps).all(), f"result depends on the row-sum order ({order})"
     values, meta = orc.compress_vectorised(W, theta, mask, 2, 4)
     nv, nm = orc.native_tiling(values, meta, *W.shape)
     out = {
@@ -42,6 +48,7 @@ def main():
         "native_values_sha256": sha(nv),
         "native_meta_sha256": sha(nm),
         "retained": orc.retained_metric(W, s, theta, 2, 4),
+        "row_sum_orders_cross_checked": [str(o) for o in orders],
     }
     path = os.path.join(ROOT, "tests", "golden", "cfg1_oracle.json")
     with open(path, "w") as f:

@@ -5,12 +5,19 @@ The oracle cannot finish these sizes as a whole, so every stage is compared on s
 compute one by one, all from seeded inputs:
   channel statistics   - the full calibration set (T = 262144), oracle on sampled channels (bit-exact)
   scores + GNS         - a calibration subset (the first T_SUB rows), oracle complete (bit-exact)
-  LBS                  - first swaps of sampled blocks (bit-exact); the final order of a sampled block
-                         is a permutation of the block's channels at which the oracle's search finds no
-                         improving swap (a property that holds at any size)
+  LBS                  - one block per stored oracle result (tests/golden/lbs_block_*.json) run to termination,
+                         order and number of exchanges bit-exact; first swaps of further sampled blocks
+                         (bit-exact); the final order of a sampled block is a permutation of the block's
+                         channels at which the oracle's search finds no improving swap
+  products             - every kernel variant that applies to a shape (the ones the tuner picks among) and the
+                         group launches, on one shape per kernel family
   mask, compression    - sampled rows over all of K (bit-exact), closed-form sizes
   products             - sampled tokens x sampled output features, normwise relative error per row
 """
+import glob
+import hashlib
+import json
+import os
 import time
 
 import numpy as np
@@ -171,6 +178,120 @@ def test_full_size_pipeline_on_sampled_units(esp, ctx, cfg, layer):
         assert err.max() <= TOL[dtype], (M, err.max())
         _log(f"product M={M}: max row error {err.max():.2e}", t0)
     del W, Xc, comp, res, res_gns
+    torch.cuda.empty_cache()
+
+
+# ---------------------------------------------------------------- LBS run to termination on one full-size block
+def _sha(a):
+    return hashlib.sha256(np.ascontiguousarray(a).tobytes()).hexdigest()
+
+
+GOLDEN_BLOCKS = sorted(glob.glob(os.path.join(os.path.dirname(__file__), "golden", "lbs_block_cfg*.json")))
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("path", GOLDEN_BLOCKS, ids=[os.path.basename(p) for p in GOLDEN_BLOCKS])
+def test_complete_lbs_block_against_stored_oracle_result(esp, ctx, path):
+    """Algorithm 1 to termination on one block of a full-size matrix: the device's final channel order of the
+    block and its number of exchanges equal what the oracle wrote (make_lbs_block_golden.py), bit for bit.  The
+    inputs are generated on the host, as the script does, and their hashes are checked first."""
+    g = json.load(open(path))
+    cfg, layer, B, blk = g["cfg"], g["layer"], g["B"], g["block"]
+    t0 = time.time()
+    print(f"complete LBS block cfg={cfg} {layer} B={B} block={blk} ({g['swaps']} exchanges in the oracle)", flush=True)
+    W = wl.weights(cfg, layer)
+    Xc = wl.calibration(cfg, layer, T=g["T_sub"])
+    assert _sha(W.numpy()) == g["inputs_sha256"]["W"] and _sha(Xc.numpy()) == g["inputs_sha256"]["Xc"]
+    _log("inputs generated, hashes agree", t0)
+    res = ctx.prune(Xc.cuda(), W.cuda(), esp.PruneOpts(block=B, alpha=g["alpha"]))
+    torch.cuda.synchronize()
+    _log(f"device prune done ({int(res.swaps.sum())} exchanges over all blocks)", t0)
+    assert _sha(res.score) == g["score_sha256"], "scores differ"
+    theta = res.perm.cpu().numpy()
+    assert theta[blk * B:(blk + 1) * B].tolist() == g["theta_block"], "final order of the block differs"
+    assert int(res.swaps[blk]) == g["swaps"]
+
+
+# ---------------------------------------------------------------- every variant / group launch at full size
+VARIANT_CASES = [
+    # (cfg, layer, M, products in the group launch (0 = none))    kernel family the shape exercises
+    (2, "gate_up", 32, 2),      # decode kernels, two token tiles, 96 rows per workgroup; gate + up in one launch
+    (2, "down", 8, 0),          # decode kernels for at most 16 tokens (step quads), K split over workgroups
+    (2, "qkvo", 1, 3),          # q / k / v in one launch
+    (3, "qkvo", 2048, 0),       # tile kernels incl. the 320-row macro tile
+    (3, "qkvo", 512, 0),        # tile kernels with K split over workgroups
+    (4, "gate_up", 128, 0),     # stream kernels, bf16, eleven waves
+    (5, "fc1", 64, 0),          # stream kernels, nine waves
+]
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("cfg,layer,M,group", VARIANT_CASES)
+def test_full_size_every_variant_and_group_launch(esp, ctx, cfg, layer, M, group):
+    """What the benchmark times is whatever the tuner picks: every variant that accepts the shape is run at
+    full size and compared with the oracle on sampled tokens x sampled output features, and so are the group
+    launches (every decode-kernel variant, members with their own permutation and mask)."""
+    c = wl.CONFIGS[cfg]
+    N, K = c["layers"][layer]
+    dtype = wl.TORCH_DTYPE[c["dtype"]]
+    alpha = wl.default_alpha(T_SUB)
+    t0 = time.time()
+    rng = np.random.default_rng(cfg * 31 + M)
+    Xc = wl.calibration(cfg, layer, T=T_SUB, device="cuda")
+    s = orc.channel_score(_np(Xc), alpha, 100)
+    del Xc
+    feat = np.sort(rng.choice(N, 768, replace=False))
+    feat_t = torch.as_tensor(feat, device="cuda")
+    tok = np.sort(rng.choice(M, min(M, 5), replace=False))
+    tok_t = torch.as_tensor(tok, device="cuda")
+    X = wl.activations(cfg, layer, M, device="cuda")
+    members = []
+    for inst in range(max(1, group)):
+        W = wl.weights(cfg, layer, instance=inst, device="cuda")
+        res = ctx.prune(None, W, esp.PruneOpts(block=c["block"], alpha=alpha), score=s)
+        comp = ctx.compress(W, res.mask, res.perm, canonical=False)
+        theta = res.perm.cpu().numpy().astype(np.int64)
+        Wf = _np(W[feat_t])
+        Yref = orc.spmm_ref(_np(X[tok_t]), Wf, theta, orc.nm_mask_vectorised(Wf, s, theta, 2, 4))
+        members.append((comp, res.perm, Yref))
+        del W, res
+    _log(f"{len(members)} matrices pruned and compressed, oracle outputs on {tok.size} x {feat.size} samples", t0)
+    ran = []
+    for v in range(esp.num_variants()):
+        name = esp.variant_name(v)
+        print(f"  cfg={cfg} {layer} M={M} variant={name}", flush=True)
+        try:
+            Y = ctx.spmm(X, members[0][0], members[0][1], variant=v)
+        except esp.EsparseError as e:
+            assert e.code == -2
+            continue
+        torch.cuda.synchronize()
+        err = orc.rowwise_rel_error(_np(Y[tok_t][:, feat_t]), members[0][2])
+        assert err.max() <= TOL[dtype], (name, err.max())
+        ran.append(name)
+        if group:
+            Ys = ctx.spmm_group([X] * group, [m_[0] for m_ in members], [m_[1] for m_ in members], variant=v)
+            torch.cuda.synchronize()
+            for i in range(group):
+                err = orc.rowwise_rel_error(_np(Ys[i][tok_t][:, feat_t]), members[i][2])
+                assert err.max() <= TOL[dtype], ("group", name, i, err.max())
+    _log("variants run: " + " ".join(ran), t0)
+    # the tuner's picks (single product and group launch), then the default path through them
+    code = esp.F16 if dtype == torch.float16 else esp.BF16
+    v1, _ = ctx.tune(M, N, K, code, True)
+    Y = ctx.spmm(X, members[0][0], members[0][1])
+    assert orc.rowwise_rel_error(_np(Y[tok_t][:, feat_t]), members[0][2]).max() <= TOL[dtype]
+    picked = [esp.variant_name(v1)]
+    if group:
+        vg, _ = ctx.tune_group(group, M, N, K, code, True)
+        Ys = ctx.spmm_group([X] * group, [m_[0] for m_ in members], [m_[1] for m_ in members])
+        torch.cuda.synchronize()
+        for i in range(group):
+            assert orc.rowwise_rel_error(_np(Ys[i][tok_t][:, feat_t]), members[i][2]).max() <= TOL[dtype]
+        picked.append(esp.variant_name(vg) + f" x{group}")
+    _log("tuner picked " + ", ".join(picked) + ": parity holds", t0)
+    assert ran
+    members.clear()
     torch.cuda.empty_cache()
 
 

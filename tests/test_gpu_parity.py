@@ -95,7 +95,8 @@ def _prune_case(esp, ctx, N, K, T, B, n, m, dtype, flags, seed, max_swaps=0):
     if flags & esp.USE_LBS:
         assert (res.swaps == swaps).all(), "swap counts differ"
     assert (res.mask.cpu().numpy() == mask).all(), "mask differs"
-    assert res.retained == orc.retained_metric(_np(W), s, theta, n, m)
+    # a float64 sum of N * K / m terms: the device adds them in its own order (eq. 5 fixes none)
+    assert res.retained == pytest.approx(orc.retained_metric(_np(W), s, theta, n, m), rel=1e-12)
     return res, W, Xc, theta, mask, s
 
 
@@ -140,7 +141,7 @@ def test_config1_against_stored_oracle_results(esp, ctx):
     assert res.swaps.tolist() == gold["swaps"]
     assert _sha(res.score) == gold["score_sha256"]
     assert _sha(res.mask.cpu().numpy()) == gold["mask_sha256"]
-    assert res.retained == gold["retained"]
+    assert res.retained == pytest.approx(gold["retained"], rel=1e-12)
     comp = ctx.compress(W.cuda(), res.mask, res.perm)
     assert _sha(_bits(comp.values)) == gold["values_sha256"]
     assert _sha(comp.meta.cpu().numpy()) == gold["meta_sha256"]
