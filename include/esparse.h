@@ -146,6 +146,20 @@ int esparse_spmm_workspace(long long M, long long N, long long K, size_t* bytes)
 int esparse_spmm(esparse_ctx* ctx, const void* X, long long M, const void* native_w,
                  const int32_t* perm, long long N, long long K, esparse_dtype dtype, int n_keep,
                  int m_group, void* Y, void* workspace, size_t workspace_bytes, int variant);
+/* esparse_spmm for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same product, same kernels and bitwise the same
+ * result as esparse_spmm with the same variant; the scratch (staged activations, partial tiles of the variants
+ * that split K) is a fixed array of ESPARSE_STATIC_SCRATCH_BYTES in the library's device image, one per GPU,
+ * held until the process ends.  The call allocates and frees nothing on the device.  A shape whose variant needs
+ * more scratch than that is rejected with ESPARSE_EWORKSPACE and nothing is launched (the message gives both
+ * sizes); the first call on a GPU looks the array's device address up (that GPU current).  Every call on one GPU
+ * uses the same array, on whatever stream its context has: calls that overlap on one GPU race - order them on
+ * one stream or with events.  No part of the array needs clearing between calls (each kernel reads only what an
+ * earlier kernel of the same call wrote).  Other errors as esparse_spmm.  Does not synchronise. */
+#define ESPARSE_STATIC_SCRATCH_BYTES (64u << 20)
+int esparse_spmm_static(esparse_ctx* ctx, const void* X, long long M, const void* native_w,
+                        const int32_t* perm, long long N, long long K, esparse_dtype dtype, int n_keep,
+                        int m_group, void* Y, int variant);
 /* The two halves of esparse_spmm as separate calls, for callers that multiply one activation
  * matrix with several weight matrices sharing one perm, or that time the multiply alone:
  * esparse_stage_activations writes X[:, perm] in the kernels' operand order into the workspace

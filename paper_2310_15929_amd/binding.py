@@ -62,6 +62,7 @@ def load_library():
         "esparse_compress": (i32, [vp, vp, vp, vp, ll, ll, i32, i32, i32, vp, vp, vp]),
         "esparse_spmm_workspace": (i32, [ll, ll, ll, P(sz)]),
         "esparse_spmm": (i32, [vp, vp, ll, vp, vp, ll, ll, i32, i32, i32, vp, vp, sz, i32]),
+        "esparse_spmm_static": (i32, [vp, vp, ll, vp, vp, ll, ll, i32, i32, i32, vp, i32]),
         "esparse_stage_activations": (i32, [vp, vp, ll, vp, ll, ll, i32, vp, sz]),
         "esparse_spmm_staged": (i32, [vp, ll, vp, ll, ll, i32, i32, i32, vp, vp, sz, i32]),
         "esparse_dense_gemm_staged": (i32, [vp, ll, vp, ll, ll, i32, vp, vp, sz, i32]),
@@ -87,7 +88,7 @@ EXPORTED = ["esparse_create", "esparse_destroy", "esparse_set_stream", "esparse_
             "esparse_version", "esparse_channel_stats", "esparse_prune", "esparse_prune_with_scores", "esparse_output_error",
             "esparse_spmm_group_workspace", "esparse_spmm_group", "esparse_dense_gemm_group",
             "esparse_stage_activations_group", "esparse_spmm_group_staged",
-            "esparse_compressed_size", "esparse_compress", "esparse_spmm_workspace", "esparse_spmm",
+            "esparse_compressed_size", "esparse_compress", "esparse_spmm_workspace", "esparse_spmm", "esparse_spmm_static",
             "esparse_stage_activations", "esparse_spmm_staged", "esparse_dense_gemm_staged",
             "esparse_spmm_num_variants", "esparse_spmm_variant_name", "esparse_dense_packed_size",
             "esparse_dense_pack", "esparse_dense_gemm", "esparse_tune", "esparse_tune_group", "esparse_tune_save",
@@ -281,6 +282,17 @@ class Context:
         self._check(self._lib.esparse_spmm(self._h, _ptr(X), M, _ptr(comp.native), _ptr(perm), comp.N, K, comp.dtype,
                                            comp.n_keep, comp.m_group, _ptr(Y), _ptr(ws), nbytes, variant))
         return Y
+
+    def spmm_static(self, X: torch.Tensor, comp: Compressed, perm: Optional[torch.Tensor], *, variant: int = -1,
+                    out: torch.Tensor) -> torch.Tensor:
+        """esparse_spmm_static: the product with the library's own fixed scratch; nothing is allocated (the caller
+        brings the output)."""
+        M, K = X.shape
+        assert K == comp.K and _dtype_code(X) == comp.dtype and tuple(out.shape) == (M, comp.N)
+        self._sync_stream()
+        self._check(self._lib.esparse_spmm_static(self._h, _ptr(X), M, _ptr(comp.native), _ptr(perm), comp.N, K, comp.dtype,
+                                                  comp.n_keep, comp.m_group, _ptr(out), variant))
+        return out
 
     def spmm_group(self, Xs, comps, perms, *, variant: int = -1, outs=None):
         """Products of one shape (same M, N, K, dtype, n:m) through one staging and one multiply launch

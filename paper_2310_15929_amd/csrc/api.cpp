@@ -234,20 +234,20 @@ int esparse_compress(esparse_ctx* ctx, const void* W, const uint8_t* mask, const
 
 static int check_matmul(esparse_ctx* ctx, const void* X, long long M, const void* w, long long N,
                         long long K, int dtype, const void* Y, const void* ws, size_t ws_bytes,
-                        int variant, int sparse, int phases = 3) {
+                        int variant, int sparse, int phases = 3, bool own_scratch = false) {
   int rc = check_dtype(ctx, dtype);
   if (rc) return rc;
   ESP_REQUIRE(ctx, M >= 0 && M < (1ll << 24), ESPARSE_EINVAL, "M = %lld out of range", M);
   ESP_REQUIRE(ctx, N >= 1 && N < (1ll << 31) && K >= 4 && K < (1ll << 31), ESPARSE_EINVAL, "N or K out of range");
   ESP_REQUIRE(ctx, K % 4 == 0, ESPARSE_EINVAL, "K = %lld is not a multiple of 4", K);
   if (M == 0) return ESPARSE_OK;
-  ESP_REQUIRE(ctx, ws && ((phases & ESP_PHASE_STAGE) ? X != nullptr : true) &&
+  ESP_REQUIRE(ctx, (ws || own_scratch) && ((phases & ESP_PHASE_STAGE) ? X != nullptr : true) &&
                        ((phases & ESP_PHASE_MULTIPLY) ? (w && Y) : true),
               ESPARSE_EINVAL, "X / weights / Y / workspace is null");
   ESP_REQUIRE(ctx, esp_aligned16(X) && esp_aligned16(w) && esp_aligned16(Y), ESPARSE_EINVAL,
               "X / weights / Y is not 16-byte aligned");
   ESP_REQUIRE(ctx, (reinterpret_cast<uintptr_t>(ws) & 255u) == 0, ESPARSE_EINVAL, "workspace is not 256-byte aligned");
-  ESP_REQUIRE(ctx, ws_bytes >= esp_workspace_bytes(M, N, K), ESPARSE_EWORKSPACE,
+  ESP_REQUIRE(ctx, own_scratch || ws_bytes >= esp_workspace_bytes(M, N, K), ESPARSE_EWORKSPACE,
               "workspace has %zu bytes, %zu needed", ws_bytes, esp_workspace_bytes(M, N, K));
   ESP_REQUIRE(ctx, variant >= -1 && variant < esp_num_variants(), ESPARSE_EINVAL, "variant %d does not exist", variant);
   ESP_REQUIRE(ctx, variant < 0 || esp_variant_applicable(variant, M, N, K, sparse), ESPARSE_EUNSUPPORTED,
@@ -295,6 +295,28 @@ int esparse_spmm(esparse_ctx* ctx, const void* X, long long M, const void* nativ
                  long long N, long long K, esparse_dtype dtype, int n, int m, void* Y, void* workspace,
                  size_t workspace_bytes, int variant) {
   return spmm_phases(ctx, X, M, native_w, perm, N, K, dtype, n, m, Y, workspace, workspace_bytes, variant, 3);
+}
+
+int esparse_spmm_static(esparse_ctx* ctx, const void* X, long long M, const void* native_w, const int32_t* perm,
+                        long long N, long long K, esparse_dtype dtype, int n, int m, void* Y, int variant) {
+  if (!ctx) return ESPARSE_EINVAL;
+  ESP_REQUIRE(ctx, (n == 2 && m == 4) || (n == 4 && m == 8), ESPARSE_EUNSUPPORTED,
+              "the sparse product exists for 2:4 and 4:8 only (got %d:%d)", n, m);
+  const int mode = m == 4 ? 1 : 2;
+  int rc = check_matmul(ctx, X, M, native_w, N, K, dtype, Y, nullptr, 0, variant, mode, 3, true);
+  if (rc) return rc;
+  ESP_REQUIRE(ctx, K % m == 0, ESPARSE_EINVAL, "K = %lld is not a multiple of %d", K, m);
+  ESP_REQUIRE(ctx, esp_aligned16(perm), ESPARSE_EINVAL, "perm is not 16-byte aligned");
+  if (M == 0) return ESPARSE_OK;
+  const int v = pick_variant(ctx, mode, dtype, M, N, K, variant);
+  const size_t need = esp_variant_workspace_bytes(v, M, N, K);
+  ESP_REQUIRE(ctx, need <= (size_t)ESPARSE_STATIC_SCRATCH_BYTES, ESPARSE_EWORKSPACE,
+              "M=%lld N=%lld K=%lld with variant %s needs %zu bytes of scratch, the static scratch holds %zu: use esparse_spmm "
+              "with a workspace of the caller's", M, N, K, esp_variant_name(v), need, (size_t)ESPARSE_STATIC_SCRATCH_BYTES);
+  ESP_HIP(ctx, hipSetDevice(ctx->device));
+  void* ws = nullptr;
+  if ((rc = esp_static_scratch(ctx, &ws))) return rc;
+  return esp_matmul_device(ctx, mode, X, M, native_w, perm, N, K, dtype, Y, ws, v, ESP_PHASE_STAGE | ESP_PHASE_MULTIPLY);
 }
 
 int esparse_stage_activations(esparse_ctx* ctx, const void* X, long long M, const int32_t* perm, long long N,

@@ -109,6 +109,8 @@ const char* esp_variant_name(int v);
 bool esp_variant_applicable(int v, long long M, long long N, long long K, int sparse);
 int esp_default_variant(long long M, long long N, long long K, int sparse);
 size_t esp_workspace_bytes(long long M, long long N, long long K);
+size_t esp_variant_workspace_bytes(int variant, long long M, long long N, long long K);
+int esp_static_scratch(esparse_ctx* ctx, void** out);  // device address of this GPU's static scratch (ctx->device current)
 #define ESP_PHASE_STAGE 1     // gather X through theta into the workspace
 #define ESP_PHASE_MULTIPLY 2  // multiply the staged activations with the weights
 int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, const void* w,

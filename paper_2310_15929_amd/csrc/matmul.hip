@@ -1323,6 +1323,36 @@ size_t esp_workspace_bytes(long long M, long long N, long long K) {
   return bytes;
 }
 
+// what one variant really uses of the workspace: the header, the staged activations and - only for variants that split
+// K over workgroups - the fp32 partial tiles
+size_t esp_variant_workspace_bytes(int variant, long long M, long long N, long long K) {
+  const Variant& v = kVariants[variant];
+  const bool partial = v.split_mode == 1 || v.kind == KIND_STREAM;
+  if (partial && esp_split_capacity(M) > 1) return esp_workspace_bytes(M, N, K);
+  return (size_t)WS_HEADER_BYTES + staged_bytes(M, K);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Scratch for callers that cannot allocate: one array per GPU, in the library's own device image, held until the
+// process ends.  The array's name is a host-side stand-in; its device address is looked up once per device (with
+// that device current) and only that address is ever handed to kernels.
+// ------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[ESPARSE_STATIC_SCRATCH_BYTES];
+static std::atomic<void*> g_scratch_ptr[64];
+
+int esp_static_scratch(esparse_ctx* ctx, void** out) {
+  const int dev = ctx->device;
+  ESP_REQUIRE(ctx, dev >= 0 && dev < 64, ESPARSE_EUNSUPPORTED, "device %d: the static scratch is kept for devices 0..63", dev);
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    ESP_HIP(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));  // the caller has made ctx->device current
+    ESP_REQUIRE(ctx, p && (reinterpret_cast<uintptr_t>(p) & 255u) == 0, ESPARSE_EHIP, "the static scratch has no usable device address");
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return ESPARSE_OK;
+}
+
 template <int DT, int SPARSE>
 static void launch_wave_tile(const Variant& v, dim3 grid, hipStream_t st, const uint4* A, const uint2* meta, const uint4* Xf,
                              uint16_t* Y, float* partial, long long M, long long N, long long Mp, long long Np, long long Kp,
