@@ -45,159 +45,251 @@ __device__ __forceinline__ unsigned int ordered_bits(float f) {
   unsigned int u = __float_as_uint(f);
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
-static inline float from_ordered_bits(unsigned int o) {
-  unsigned int u = (o & 0x80000000u) ? (o & 0x7fffffffu) : ~o;
-  float f;
-  memcpy(&f, &u, 4);
-  return f;
-}
 
 // ------------------------------------------------------------------------------------------------
-// pass A: per-channel min / max.  block 256 = 8 row lanes x 32 column lanes of CPL channels each
-// (CPL = 8: 16-byte loads, needs K % 8 == 0; CPL = 2 otherwise); grid (ceil(K / (32 CPL)), row chunks).
-// Four rows are in flight per thread; the row lanes meet in LDS, one atomic pair per channel and block.
+// Channel statistics in two scans of the calibration features, each at memory speed.
+// Both kernels: block 1024 = 32 column lanes of CPL channels (CPL = 4: 8-byte loads, needs K % 4 == 0;
+// CPL = 2 otherwise) x 32 row lanes, eight rows in flight per thread; grid (ceil(K / (32 CPL)), row chunks).
+//
+// Scan A: per-channel min / max and the exact sum of squares.  A 16-bit value is m * 2^E with an integer m of
+// at most 11 bits, so its square is the integer m * m at binary position 2 E: bin and quotient of the exponent-
+// binned accumulation come from integer shifts (no float64 arithmetic, no ilogb / ldexp).
+// Scan B: the histogram over [min, max].  The bin of x is floor(((x - lo) * bins) / (hi - lo)) evaluated in
+// float64, clamped to bins - 1 (the definition).  A float32 estimate q of that quotient is at most 5e-5 off for
+// bins <= 256 (three roundings of 2^-24 relative), the float64 quotient at most 2^-44: whenever q is farther
+// than 1e-4 from the nearest integer both have the same floor, so only the lanes near a bin edge (and the lanes
+// where the estimate overflowed) evaluate the definition itself.
 // ------------------------------------------------------------------------------------------------
+// bin and quotient of the square of a 16-bit value for the exponent-binned exact accumulation, from the bits of the
+// (exact) floating-point square: fp16 squares have at most 22 significant bits and fit float32, bf16 squares have 16
+// and fit float64 (their exponents go beyond float32).  With t = ilogb(x^2) + SQ_EOFF the bin is t / 16 and the
+// quotient x^2 / 2^(16 bin - SQ_EOFF - SQ_SIG) is the square's integer significand shifted left by t % 16 (less than
+// 2^37).  Zero gives quotient 0.
+template <int DT>
+__device__ __forceinline__ void square_bin(float x, unsigned int* bin, unsigned long long* q) {
+  if (DT == ESPARSE_F16) {
+    const float xs = x * x;
+    const uint32_t bits = __float_as_uint(xs);
+    const uint32_t t = (bits >> 23) + (uint32_t)(SQ_EOFF - 127);
+    uint32_t mant = ((bits & 0x7fffffu) | 0x800000u) >> 2;  // 24-bit significand, its two low bits are zero: SQ_SIG + 1 = 22 bits
+    mant = bits ? mant : 0u;
+    *bin = t >> 4;
+    *q = (unsigned long long)mant << (t & 15u);
+  } else {
+    const double xs = (double)x * (double)x;
+    const uint32_t hi = (uint32_t)(__double_as_longlong(xs) >> 32);  // the low word of the significand is zero
+    const uint32_t t = (hi >> 20) + (uint32_t)(SQ_EOFF - 1023);
+    uint32_t mant = (hi & 0xfffffu) | 0x100000u;  // top 21 bits of the significand
+    mant = hi ? mant : 0u;
+    *bin = t >> 4;
+    *q = (unsigned long long)mant << ((t & 15u) + 1u);
+  }
+}
+
+// the 16-bit values of ROWS rows (32 rows apart) x CPL channels of one thread; FULL: all rows exist, else rows past the
+// end are replaced by the thread's first row (callers give those no weight)
+template <int CPL, int ROWS, bool FULL>
+__device__ __forceinline__ void load_rows(const uint16_t* __restrict__ p, long long stride32, long long rb, long long r1,
+                                          uint32_t (&w)[ROWS][CPL / 2]) {
+#pragma unroll
+  for (int u = 0; u < ROWS; u++) {
+    const uint16_t* src = (FULL || rb + 32 * u < r1) ? p + u * stride32 : p;
+    if (CPL == 4) {
+      const uint2 v = *reinterpret_cast<const uint2*>(src);
+      w[u][0] = v.x;
+      w[u][1 % (CPL / 2)] = v.y;
+    } else {
+      w[u][0] = *reinterpret_cast<const uint32_t*>(src);
+    }
+  }
+}
+
+template <int DT, int CPL, int ROWS, bool FULL>
+__device__ __forceinline__ void minmax_sumsq_trip(const uint16_t* __restrict__ p, long long stride32, long long rb, long long r1,
+                                                  float (&lo)[CPL], float (&hi)[CPL], unsigned long long* s_sq_lane, int want_sq) {
+  uint32_t w[ROWS][CPL / 2];
+  load_rows<CPL, ROWS, FULL>(p, stride32, rb, r1, w);
+#pragma unroll
+  for (int u = 0; u < ROWS; u++) {
+    // a repeated row changes neither min nor max; its square is replaced by zero (no branches in this loop)
+    const bool live = FULL || rb + 32 * u < r1;
+#pragma unroll
+    for (int j = 0; j < CPL; j++) {
+      const float x = esp_to_float<DT>((uint16_t)(w[u][j / 2] >> (16 * (j & 1))));
+      lo[j] = fminf(lo[j], x);
+      hi[j] = fmaxf(hi[j], x);
+      if (want_sq) {
+        unsigned int bi;
+        unsigned long long q;
+        square_bin<DT>(live ? x : 0.0f, &bi, &q);
+        atomicAdd(s_sq_lane + j * (32 * SQ_NB) + bi, q);
+      }
+    }
+  }
+}
+
 template <int DT, int CPL>
-__global__ void __launch_bounds__(256) k_minmax(const uint16_t* __restrict__ X, long long T, long long K,
-                                                 long long rows_per_block, unsigned int* __restrict__ omin,
-                                                 unsigned int* __restrict__ omax) {
-  __shared__ float s_lo[8][32 * CPL + 1], s_hi[8][32 * CPL + 1];
+__global__ void __launch_bounds__(1024) k_minmax_sumsq(const uint16_t* __restrict__ X, long long T, long long K,
+                                                        long long rows_per_block, unsigned int* __restrict__ omin,
+                                                        unsigned int* __restrict__ omax,
+                                                        unsigned long long* __restrict__ sq /*[K][SQ_NB]*/, int want_sq) {
+  constexpr int CH = 32 * CPL;  // channels per block
+  // LDS row of a channel = j * 32 + cl (cl: column lane, j: which of the lane's CPL channels)
+  __shared__ unsigned long long s_sq[CH * SQ_NB];
+  __shared__ unsigned int s_lo[CH], s_hi[CH];
   const int tid = threadIdx.x, cl = tid & 31, rl = tid >> 5;
+  for (int i = tid; i < CH * SQ_NB; i += 1024) s_sq[i] = 0ull;
+  if (tid < CH) {
+    s_lo[tid] = 0xffffffffu;
+    s_hi[tid] = 0u;
+  }
+  __syncthreads();
   const long long c = ((long long)blockIdx.x * 32 + cl) * CPL;
   const long long r0 = (long long)blockIdx.y * rows_per_block;
   const long long r1 = r0 + rows_per_block < T ? r0 + rows_per_block : T;
-  float lo[CPL], hi[CPL];
+  if (c < K && r0 + rl < r1) {
+    float lo[CPL], hi[CPL];
 #pragma unroll
-  for (int j = 0; j < CPL; j++) {
-    lo[j] = INFINITY;
-    hi[j] = -INFINITY;
-  }
-  if (c < K) {
-    for (long long r = r0 + rl; r < r1; r += 32) {
-      uint32_t w[4][CPL / 2];
-#pragma unroll
-      for (int u = 0; u < 4; u++) {
-        const long long rr = r + 8 * u < r1 ? r + 8 * u : r;  // past the end: the first row again (no effect on min / max)
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(X + rr * K + c);
-        if (CPL == 8) {
-          const uint4 v = *reinterpret_cast<const uint4*>(src);
-          w[u][0] = v.x;
-          w[u][1 % (CPL / 2)] = v.y;
-          w[u][2 % (CPL / 2)] = v.z;
-          w[u][3 % (CPL / 2)] = v.w;
-        } else {
-          w[u][0] = *src;
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < 4; u++)
-#pragma unroll
-        for (int j = 0; j < CPL; j++) {
-          const float x = esp_to_float<DT>((uint16_t)(w[u][j / 2] >> (16 * (j & 1))));
-          lo[j] = fminf(lo[j], x);
-          hi[j] = fmaxf(hi[j], x);
-        }
+    for (int j = 0; j < CPL; j++) {
+      lo[j] = INFINITY;
+      hi[j] = -INFINITY;
     }
-  }
+    constexpr int ROWS = 8;
+    const long long stride32 = 32 * K;
+    const uint16_t* p = X + (r0 + rl) * K + c;
+    unsigned long long* s_sq_lane = s_sq + cl * SQ_NB;
+    long long rb = r0 + rl;
+    for (; rb + 32 * (ROWS - 1) < r1; rb += 32 * ROWS, p += ROWS * stride32)
+      minmax_sumsq_trip<DT, CPL, ROWS, true>(p, stride32, rb, r1, lo, hi, s_sq_lane, want_sq);
+    if (rb < r1) minmax_sumsq_trip<DT, CPL, ROWS, false>(p, stride32, rb, r1, lo, hi, s_sq_lane, want_sq);
 #pragma unroll
-  for (int j = 0; j < CPL; j++) {
-    s_lo[rl][cl * CPL + j] = lo[j];
-    s_hi[rl][cl * CPL + j] = hi[j];
+    for (int j = 0; j < CPL; j++) {
+      atomicMin(&s_lo[j * 32 + cl], ordered_bits(lo[j]));
+      atomicMax(&s_hi[j * 32 + cl], ordered_bits(hi[j]));
+    }
   }
   __syncthreads();
-  for (int i = tid; i < 32 * CPL; i += 256) {
-    const long long ch = (long long)blockIdx.x * 32 * CPL + i;
-    if (ch >= K || r1 <= r0) continue;
-    float a = s_lo[0][i], b = s_hi[0][i];
-#pragma unroll
-    for (int q = 1; q < 8; q++) {
-      a = fminf(a, s_lo[q][i]);
-      b = fmaxf(b, s_hi[q][i]);
-    }
-    if (a <= b) {  // some row lane saw the channel
-      atomicMin(&omin[ch], ordered_bits(a));
-      atomicMax(&omax[ch], ordered_bits(b));
+  const long long cbase = (long long)blockIdx.x * CH;
+  if (tid < CH && r0 < r1) {
+    const long long ch = cbase + (long long)(tid & 31) * CPL + (tid >> 5);  // LDS row tid = j * 32 + cl
+    if (ch < K) {
+      atomicMin(&omin[ch], s_lo[tid]);
+      atomicMax(&omax[ch], s_hi[tid]);
     }
   }
+  if (want_sq)
+    for (int i = tid; i < CH * SQ_NB; i += 1024) {
+      const int row = i / SQ_NB;
+      const long long ch = cbase + (long long)(row & 31) * CPL + (row >> 5);
+      const unsigned long long v = s_sq[i];
+      if (ch < K && v) atomicAdd(&sq[ch * SQ_NB + (i % SQ_NB)], v);
+    }
 }
 
-// ------------------------------------------------------------------------------------------------
-// pass B: histogram over [min, max] and exact sum of squares.
-// grid (ceil(K/64), row chunks), block 256 = 8 row lanes x 32 channel pairs
-// ------------------------------------------------------------------------------------------------
-template <int DT>
-__global__ void __launch_bounds__(256) k_hist_sumsq(const uint16_t* __restrict__ X, long long T, long long K,
-                                                     long long rows_per_block, int bins,
-                                                     const float* __restrict__ cmin, const float* __restrict__ cmax,
-                                                     unsigned int* __restrict__ hist /*[K][bins]*/,
-                                                     unsigned long long* __restrict__ sq /*[K][SQ_NB]*/,
-                                                     int want_hist, int want_sq) {
-  extern __shared__ unsigned char smem_raw[];
-  unsigned long long* s_sq = reinterpret_cast<unsigned long long*>(smem_raw);           // [64][SQ_NB]
-  unsigned int* s_hist = reinterpret_cast<unsigned int*>(smem_raw + 64 * SQ_NB * 8);    // [64][bins]
-  const int tid = threadIdx.x;
-  for (int i = tid; i < 64 * SQ_NB; i += 256) s_sq[i] = 0ull;
-  for (int i = tid; i < 64 * bins; i += 256) s_hist[i] = 0u;
-  __syncthreads();
-  const int cp = tid & 31, rl = tid >> 5;
-  const long long c = (long long)blockIdx.x * 64 + cp * 2;
-  if (c < K) {
-    const double lo0 = (double)cmin[c], hi0 = (double)cmax[c];
-    const double lo1 = (double)cmin[c + 1], hi1 = (double)cmax[c + 1];
-    const double w0 = hi0 - lo0, w1 = hi1 - lo1;
+__device__ __forceinline__ float float_from_ordered_bits(unsigned int o) {
+  return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
+}
+
+__device__ __forceinline__ float fraction_of(float q) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_amdgcn_fractf(q);
+#else
+  return q - floorf(q);
+#endif
+}
+
+// the float32 estimate of a value's bin and whether it can be trusted: farther than 1e-4 from both neighbouring
+// integers and inside [0, bins)
+__device__ __forceinline__ bool bin_estimate(float x, float lo32, float c32, int bins, int* bi) {
+  const float q = (x - lo32) * c32;
+  *bi = (int)q;
+  return fabsf(fraction_of(q) - 0.5f) < 0.4999f && (unsigned int)*bi < (unsigned int)bins;
+}
+
+template <int DT, int CPL, int ROWS, bool FULL>
+__device__ __forceinline__ void hist_trip(const uint16_t* __restrict__ p, long long stride32, long long rb, long long r1,
+                                          const float (&lo32)[CPL], const float (&c32)[CPL], const double (&lo)[CPL],
+                                          const double (&wd)[CPL], int bins, unsigned int* s_hist_lane, int row_stride) {
+  uint32_t w[ROWS][CPL / 2];
+  load_rows<CPL, ROWS, FULL>(p, stride32, rb, r1, w);
+  // all estimates first, without branches (whether all can be trusted is kept in a lane mask, not in registers);
+  // the rare values near a bin edge are redone afterwards from the definition
+  int bsel[ROWS][CPL];
+  bool all_ok = true;
+#pragma unroll
+  for (int u = 0; u < ROWS; u++)
+#pragma unroll
+    for (int j = 0; j < CPL; j++)
+      all_ok &= bin_estimate(esp_to_float<DT>((uint16_t)(w[u][j / 2] >> (16 * (j & 1)))), lo32[j], c32[j], bins, &bsel[u][j]);
+  if (!all_ok) {
     const double nb = (double)bins;
-    long long r0 = (long long)blockIdx.y * rows_per_block;
-    long long r1 = r0 + rows_per_block < T ? r0 + rows_per_block : T;
-    constexpr int ROWS = 8;  // rows in flight per thread: the loop is bound by the latency of its loads otherwise
-    for (long long rb = r0 + rl; rb < r1; rb += 8 * ROWS) {
-     uint32_t ahead[ROWS];
 #pragma unroll
-     for (int u = 0; u < ROWS; u++) ahead[u] = *reinterpret_cast<const uint32_t*>(X + (rb + 8 * u < r1 ? rb + 8 * u : rb) * K + c);
+    for (int u = 0; u < ROWS; u++)
 #pragma unroll
-     for (int u = 0; u < ROWS; u++) {
-      if (rb + 8 * u >= r1) break;
-      const uint32_t two = ahead[u];
-      double x[2] = {(double)esp_to_float<DT>((uint16_t)(two & 0xffffu)), (double)esp_to_float<DT>((uint16_t)(two >> 16))};
-#pragma unroll
-      for (int h = 0; h < 2; h++) {
-        const int lc = cp * 2 + h;
-        if (want_hist) {
-          const double lo = h ? lo1 : lo0, w = h ? w1 : w0;
-          int b = 0;
-          if (w > 0.0) {
-            double d = (x[h] - lo) * nb / w;
+      for (int j = 0; j < CPL; j++) {
+        const float x = esp_to_float<DT>((uint16_t)(w[u][j / 2] >> (16 * (j & 1))));
+        int b;
+        if (!bin_estimate(x, lo32[j], c32[j], bins, &b)) {
+          b = 0;
+          if (wd[j] > 0.0) {
+            const double d = ((double)x - lo[j]) * nb / wd[j];  // the definition
             b = (int)floor(d);
             if (b > bins - 1) b = bins - 1;
           }
-          atomicAdd(&s_hist[lc * bins + b], 1u);
-        }
-        if (want_sq) {
-          double v = x[h] * x[h];
-          if (v > 0.0) {
-            int bi;
-            unsigned long long q;
-            exact_bin(v, SQ_EOFF, SQ_SIG, &bi, &q);
-            atomicAdd(&s_sq[lc * SQ_NB + bi], q);
-          }
+          bsel[u][j] = b;
         }
       }
-     }
+  }
+#pragma unroll
+  for (int u = 0; u < ROWS; u++) {
+    const unsigned int one = (FULL || rb + 32 * u < r1) ? 1u : 0u;  // a repeated row counts nothing
+#pragma unroll
+    for (int j = 0; j < CPL; j++) atomicAdd(s_hist_lane + j * (32 * row_stride) + bsel[u][j], one);
+  }
+}
+
+template <int DT, int CPL>
+__global__ void __launch_bounds__(1024) k_hist(const uint16_t* __restrict__ X, long long T, long long K,
+                                                long long rows_per_block, int bins, const unsigned int* __restrict__ omin,
+                                                const unsigned int* __restrict__ omax, unsigned int* __restrict__ hist /*[K][bins]*/) {
+  constexpr int CH = 32 * CPL;
+  extern __shared__ unsigned int s_hist[];  // [CH rows][stride]: the row of a channel is j * 32 + cl, the stride odd, so
+  const int stride = bins | 1;              // that the column lanes of one instruction start in 32 different banks
+  const int tid = threadIdx.x, cl = tid & 31, rl = tid >> 5;
+  for (int i = tid; i < CH * stride; i += 1024) s_hist[i] = 0u;
+  __syncthreads();
+  const long long c = ((long long)blockIdx.x * 32 + cl) * CPL;
+  const long long r0 = (long long)blockIdx.y * rows_per_block;
+  const long long r1 = r0 + rows_per_block < T ? r0 + rows_per_block : T;
+  if (c < K && r0 + rl < r1) {
+    float lo32[CPL], c32[CPL];
+    double lo[CPL], wd[CPL];
+    const double nb = (double)bins;
+#pragma unroll
+    for (int j = 0; j < CPL; j++) {
+      lo32[j] = float_from_ordered_bits(omin[c + j]);
+      lo[j] = (double)lo32[j];
+      wd[j] = (double)float_from_ordered_bits(omax[c + j]) - lo[j];
+      // the estimate's factor; a constant channel (width 0) gets NaN, which sends every value to the definition
+      c32[j] = wd[j] > 0.0 ? (float)(nb / wd[j]) : __uint_as_float(0x7fc00000u);
     }
+    constexpr int ROWS = 8;
+    const long long stride32 = 32 * K;
+    const uint16_t* p = X + (r0 + rl) * K + c;
+    unsigned int* s_hist_lane = s_hist + cl * stride;
+    long long rb = r0 + rl;
+    for (; rb + 32 * (ROWS - 1) < r1; rb += 32 * ROWS, p += ROWS * stride32)
+      hist_trip<DT, CPL, ROWS, true>(p, stride32, rb, r1, lo32, c32, lo, wd, bins, s_hist_lane, stride);
+    if (rb < r1) hist_trip<DT, CPL, ROWS, false>(p, stride32, rb, r1, lo32, c32, lo, wd, bins, s_hist_lane, stride);
   }
   __syncthreads();
-  const long long cbase = (long long)blockIdx.x * 64;
-  if (want_hist)
-    for (int i = tid; i < 64 * bins; i += 256) {
-      long long ch = cbase + i / bins;
-      unsigned int v = s_hist[i];
-      if (ch < K && v) atomicAdd(&hist[ch * bins + (i % bins)], v);
-    }
-  if (want_sq)
-    for (int i = tid; i < 64 * SQ_NB; i += 256) {
-      long long ch = cbase + i / SQ_NB;
-      unsigned long long v = s_sq[i];
-      if (ch < K && v) atomicAdd(&sq[ch * SQ_NB + (i % SQ_NB)], v);
-    }
+  const long long cbase = (long long)blockIdx.x * CH;
+  for (int i = tid; i < CH * bins; i += 1024) {
+    const int row = i / bins, b = i - row * bins;
+    const long long ch = cbase + (long long)(row & 31) * CPL + (row >> 5);
+    const unsigned int v = s_hist[row * stride + b];
+    if (ch < K && v) atomicAdd(&hist[ch * bins + b], v);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -253,57 +345,47 @@ int esp_stats_device(esparse_ctx* ctx, const void* calib, long long T, long long
   ESP_HIP(ctx, hipMemsetAsync(dhist.p, 0, (size_t)K * bins * 4, st));
   ESP_HIP(ctx, hipMemsetAsync(dsq.p, 0, (size_t)K * SQ_NB * 8, st));
   const uint16_t* X = reinterpret_cast<const uint16_t*>(calib);
-  std::vector<float> hmin((size_t)K), hmax((size_t)K);
+  const int cpl = K % 4 == 0 ? 4 : 2;  // channels per lane: 8-byte loads where the rows allow them
+  const long long gx = (K + 32 * cpl - 1) / (32 * cpl);
+  // about 1024 workgroups (four per CU over the two that fit at once), whole trips of 256 rows
+  const long long nchunk = std::max<long long>(1, std::min<long long>((T + 255) / 256, 1024 / gx + 1));
+  long long rpb = (T + nchunk - 1) / nchunk;
+  rpb = (rpb + 255) / 256 * 256;
+  dim3 grid((unsigned)gx, (unsigned)((T + rpb - 1) / rpb));
+#define ESP_SCAN_A(DTv, CPLv)                                                                                        \
+  hipLaunchKernelGGL((k_minmax_sumsq<DTv, CPLv>), grid, dim3(1024), 0, st, X, T, K, rpb, dmin.as<unsigned int>(),     \
+                     dmax.as<unsigned int>(), dsq.as<unsigned long long>(), am ? 1 : 0)
+#define ESP_SCAN_B(DTv, CPLv)                                                                                        \
+  hipLaunchKernelGGL((k_hist<DTv, CPLv>), grid, dim3(1024), (size_t)32 * CPLv * (bins | 1) * 4, st, X, T, K, rpb, bins,     \
+                     dmin.as<unsigned int>(), dmax.as<unsigned int>(), dhist.as<unsigned int>())
+  if (dtype == ESPARSE_F16) {
+    if (cpl == 4) ESP_SCAN_A(ESPARSE_F16, 4);
+    else ESP_SCAN_A(ESPARSE_F16, 2);
+  } else {
+    if (cpl == 4) ESP_SCAN_A(ESPARSE_BF16, 4);
+    else ESP_SCAN_A(ESPARSE_BF16, 2);
+  }
+  ESP_HIP(ctx, hipGetLastError());
   if (ir) {
-    const int cpl = K % 8 == 0 ? 8 : 2;  // channels per lane: 16-byte loads where the rows allow them
-    const long long gx = (K + 32 * cpl - 1) / (32 * cpl);
-    const long long nchunk = std::max<long long>(1, std::min<long long>(T / 64, 4096 / gx + 1));  // about 4096 workgroups
-    long long rpb = (T + nchunk - 1) / nchunk;
-    rpb = (rpb + 31) / 32 * 32;
-    dim3 grid((unsigned)gx, (unsigned)((T + rpb - 1) / rpb));
-#define ESP_MINMAX(DTv, CPLv) \
-  hipLaunchKernelGGL((k_minmax<DTv, CPLv>), grid, dim3(256), 0, st, X, T, K, rpb, dmin.as<unsigned int>(), dmax.as<unsigned int>())
-    if (dtype == ESPARSE_F16) {
-      if (cpl == 8) ESP_MINMAX(ESPARSE_F16, 8);
-      else ESP_MINMAX(ESPARSE_F16, 2);
-    } else {
-      if (cpl == 8) ESP_MINMAX(ESPARSE_BF16, 8);
-      else ESP_MINMAX(ESPARSE_BF16, 2);
-    }
-#undef ESP_MINMAX
-    ESP_HIP(ctx, hipGetLastError());
-    std::vector<unsigned int> omin((size_t)K), omax((size_t)K);
-    ESP_HIP(ctx, hipMemcpyAsync(omin.data(), dmin.p, K * 4, hipMemcpyDeviceToHost, st));
-    ESP_HIP(ctx, hipMemcpyAsync(omax.data(), dmax.p, K * 4, hipMemcpyDeviceToHost, st));
-    ESP_HIP(ctx, hipStreamSynchronize(st));
-    for (long long c = 0; c < K; c++) {
-      hmin[c] = from_ordered_bits(omin[c]);
-      hmax[c] = from_ordered_bits(omax[c]);
-    }
-    // reuse the two buffers for the float bounds
-    ESP_HIP(ctx, hipMemcpyAsync(dmin.p, hmin.data(), K * 4, hipMemcpyHostToDevice, st));
-    ESP_HIP(ctx, hipMemcpyAsync(dmax.p, hmax.data(), K * 4, hipMemcpyHostToDevice, st));
-  }
-  {
-    long long nchunk = std::max<long long>(1, std::min<long long>(T / 256, 2048 / std::max<long long>(1, (K + 63) / 64) + 1));
-    long long rpb = (T + nchunk - 1) / nchunk;
-    rpb = (rpb + 7) / 8 * 8;
-    dim3 grid((unsigned)((K + 63) / 64), (unsigned)((T + rpb - 1) / rpb));
-    size_t smem = (size_t)64 * SQ_NB * 8 + (size_t)64 * bins * 4;
+    // 32 * 4 channels x 256 bins x 4 bytes = 128 KiB of LDS at most
+    const size_t smem = (size_t)32 * cpl * (bins | 1) * 4;
     if (smem > 48 * 1024) {
-      ESP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist_sumsq<ESPARSE_F16>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-      ESP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist_sumsq<ESPARSE_BF16>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      ESP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist<ESPARSE_F16, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      ESP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist<ESPARSE_BF16, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      ESP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist<ESPARSE_F16, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      ESP_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(&k_hist<ESPARSE_BF16, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     }
-    if (dtype == ESPARSE_F16)
-      hipLaunchKernelGGL(k_hist_sumsq<ESPARSE_F16>, grid, dim3(256), smem, st, X, T, K, rpb, bins, dmin.as<float>(),
-                         dmax.as<float>(), dhist.as<unsigned int>(), dsq.as<unsigned long long>(), ir ? 1 : 0, am ? 1 : 0);
-    else
-      hipLaunchKernelGGL(k_hist_sumsq<ESPARSE_BF16>, grid, dim3(256), smem, st, X, T, K, rpb, bins, dmin.as<float>(),
-                         dmax.as<float>(), dhist.as<unsigned int>(), dsq.as<unsigned long long>(), ir ? 1 : 0, am ? 1 : 0);
+    if (dtype == ESPARSE_F16) {
+      if (cpl == 4) ESP_SCAN_B(ESPARSE_F16, 4);
+      else ESP_SCAN_B(ESPARSE_F16, 2);
+    } else {
+      if (cpl == 4) ESP_SCAN_B(ESPARSE_BF16, 4);
+      else ESP_SCAN_B(ESPARSE_BF16, 2);
+    }
     ESP_HIP(ctx, hipGetLastError());
   }
+#undef ESP_SCAN_A
+#undef ESP_SCAN_B
   std::vector<unsigned int> hist;
   std::vector<unsigned long long> sq;
   if (ir) {

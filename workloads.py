@@ -155,6 +155,11 @@ CONFIGS = {
     5: dict(name="opt66b", dtype="f16", act="student3", T=128 * 2048, block=64,
             layers={"qkv_out": (9216, 9216), "fc1": (36864, 9216), "fc2": (9216, 36864)},
             M=(1, 64, 1024)),
+    # the GEMM shapes of the paper's own latency table (Table 5): decoder rows (16 tokens) and context rows
+    # (16384 tokens); weights [N, K] = (output features, input features) of each "Input x Weights" row
+    6: dict(name="table5", dtype="f16", act="lognormal", T=4096, block=64,
+            layers={"qkv": (5376, 14336), "att_out": (14336, 1792), "ffn1": (7168, 14336), "ffn2": (14336, 7168)},
+            M=(16, 16384)),
 }
 
 TORCH_DTYPE = {"f16": torch.float16, "bf16": torch.bfloat16}
