@@ -25,6 +25,7 @@
 //     of Section 3.3 is applied here (X'[t, p] = X[t, theta[p]]), zero padded in both directions.
 #include <algorithm>
 #include <cstring>
+#include <cstdlib>
 #include <atomic>
 
 #include "common.h"
@@ -737,11 +738,13 @@ struct TileB {
   uint4 b0, b1;
 };
 
-// multiplies of token tiles J0 .. J1 - 1 of stage k.  On entry `bq` holds the B operand of tile J0; the operand of
-// the next tile is read from LDS while a tile is multiplied (from `sb` for tiles of this stage; after the last tile
-// of the stage, from tile 0 of `sb_next`, the next stage's buffer - if NEXT), and `bq` holds it on return.
-template <int DT, int SPARSE, int TR, int TC, int NWC, int J0, int J1, bool NEXT>
-__device__ __forceinline__ void tile_multiply(TileState<SPARSE, TR, TC, NWC>& st, const TileRegs<SPARSE, TR>& r, TileB& bq,
+// multiplies of token tiles J0 .. J1 - 1 of stage k.  The B operands stream from LDS D token tiles ahead through a ring
+// of D register sets: on entry bq[(j + OFF) % D] holds the operand of tile j for j = J0 .. J0 + D - 1; while tile j is
+// multiplied the operand of tile j + D is read into the set it frees (from `sb` for tiles of this stage; past the stage's
+// last tile - if NEXT - tile j + D - TC of `sb_next`, the next stage's buffer).  The next stage therefore finds its tile t
+// in set (t + OFF + TC) % D: its OFF is (OFF + TC) % D.
+template <int DT, int SPARSE, int TR, int TC, int NWC, int J0, int J1, bool NEXT, int D, int OFF>
+__device__ __forceinline__ void tile_multiply(TileState<SPARSE, TR, TC, NWC>& st, const TileRegs<SPARSE, TR>& r, TileB (&bq)[D],
                                               const uint4* sb, const uint4* sb_next, unsigned k) {
   int idx[TR];
   if (SPARSE) {
@@ -753,24 +756,25 @@ __device__ __forceinline__ void tile_multiply(TileState<SPARSE, TR, TC, NWC>& st
   const uint4* bn = sb_next + (st.wc * TC) * 128 + st.lane;
 #pragma unroll
   for (int j = J0; j < J1; j++) {
-    TileB nx = bq;
-    if (j + 1 < TC) {
-      nx.b0 = b[(j + 1) * 128];
-      nx.b1 = b[(j + 1) * 128 + 64];
+    const TileB cur = bq[(j + OFF) % D];
+    TileB nx = cur;
+    if (j + D < TC) {
+      nx.b0 = b[(j + D) * 128];
+      nx.b1 = b[(j + D) * 128 + 64];
     } else if (NEXT) {
-      nx.b0 = bn[0];
-      nx.b1 = bn[64];
+      nx.b0 = bn[(j + D - TC) * 128];
+      nx.b1 = bn[(j + D - TC) * 128 + 64];
     }
 #pragma unroll
     for (int i = 0; i < TR; i++) {
       if (SPARSE) {
-        st.acc[i][j] = smfmac16<DT, 0>(r.a[i], bq.b0, bq.b1, st.acc[i][j], idx[i]);
+        st.acc[i][j] = smfmac16<DT, 0>(r.a[i], cur.b0, cur.b1, st.acc[i][j], idx[i]);
       } else {
-        st.acc[i][j] = mfma16<DT>(r.a[2 * i], bq.b0, st.acc[i][j]);
-        st.acc[i][j] = mfma16<DT>(r.a[2 * i + 1], bq.b1, st.acc[i][j]);
+        st.acc[i][j] = mfma16<DT>(r.a[2 * i], cur.b0, st.acc[i][j]);
+        st.acc[i][j] = mfma16<DT>(r.a[2 * i + 1], cur.b1, st.acc[i][j]);
       }
     }
-    bq = nx;
+    bq[(j + OFF) % D] = nx;
   }
 }
 
@@ -799,15 +803,18 @@ __device__ __forceinline__ void tile_arrive() {
 //     the matrix pipe has work across the barrier and the LDS latency behind it.
 // With fewer than four token tiles per wave holding one back leaves too little ahead of the barrier to spread the
 // DMA over (measured slower): all tiles are multiplied first and the next stage's operand is read after the barrier.
-template <int DT, int SPARSE, int TR, int TC, int NWC>
+// D = how many token tiles ahead the B operands are read (1 with two waves per SIMD, where the other wave covers the LDS
+// latency; more with one wave per SIMD); the last D token tiles of a stage are multiplied after the barrier.
+template <int DT, int SPARSE, int TR, int TC, int NWC, int D, int OFF>
 __device__ __forceinline__ void tile_stage(TileState<SPARSE, TR, TC, NWC>& st, const TileRegs<SPARSE, TR>& cur,
-                                           TileRegs<SPARSE, TR>& nxt, TileB& bq, const uint4* b_cur, const uint4* b_nxt,
+                                           TileRegs<SPARSE, TR>& nxt, TileB (&bq)[D], const uint4* b_cur, const uint4* b_nxt,
                                            const uint4* a_nxt, const uint32_t* m_nxt, uint4* b_pre, uint4* a_pre, uint32_t* m_pre,
                                            unsigned k) {
   using State = TileState<SPARSE, TR, TC, NWC>;
   constexpr int DMA = State::BCOPIES + (SPARSE ? 2 : 1) * State::ACOPIES;
   constexpr bool STRADDLE = TC >= 4;
-  constexpr int TH = STRADDLE ? TC - 1 : TC;                 // token tiles multiplied ahead of the barrier
+  static_assert(D == 1 || (STRADDLE && D < TC), "deeper operand streams exist for the straddling schedule only");
+  constexpr int TH = STRADDLE ? TC - D : TC;                 // token tiles multiplied ahead of the barrier
   constexpr int DPJ = (DMA + TH - 1) / TH;                   // DMA operations issued per token tile
   constexpr int AREADS = SPARSE ? 2 * TR : 2 * TR;           // LDS reads of tile_load_a
   constexpr int APJ = (AREADS + TH - 1) / TH;
@@ -815,14 +822,14 @@ __device__ __forceinline__ void tile_stage(TileState<SPARSE, TR, TC, NWC>& st, c
   const unsigned last = st.k1 - 1;                           // past the end: reload the last stage (never used)
   tile_prefetch_b<SPARSE, TR, TC, NWC>(st, b_pre, k + 2 < st.k1 ? k + 2 : last);
   tile_prefetch_a<SPARSE, TR, TC, NWC>(st, a_pre, m_pre, k + 3 < st.k1 ? k + 3 : last);
-  tile_multiply<DT, SPARSE, TR, TC, NWC, 0, TH, false>(st, cur, bq, b_cur, b_nxt, k);
+  tile_multiply<DT, SPARSE, TR, TC, NWC, 0, TH, false, D, OFF>(st, cur, bq, b_cur, b_nxt, k);
   tile_load_a<SPARSE, TR, TC, NWC>(st, a_nxt, m_nxt, nxt);
-  // the order wanted ahead of the barrier: per token tile "read the next B operand, multiply, issue a share of
+  // the order wanted ahead of the barrier: per token tile "read a coming B operand, multiply, issue a share of
   // the DMA, read a share of the next stage's A side".  A wave that issued its DMA in one burst would sit at the
   // (bandwidth-limited) vector-memory issue while the matrix pipe runs dry.
 #pragma unroll
   for (int j = 0; j < TH; j++) {
-    if (j + 1 < TC) sched_group<0x100, 2>();
+    if (j + D < TC) sched_group<0x100, 2>();
     sched_group<0x008, MM>();
     sched_group<0x010, DPJ>();
     sched_group<0x100, APJ>();
@@ -831,18 +838,21 @@ __device__ __forceinline__ void tile_stage(TileState<SPARSE, TR, TC, NWC>& st, c
   tile_arrive<DMA>();
   sched_fence();
   if (STRADDLE) {
-    tile_multiply<DT, SPARSE, TR, TC, NWC, TH, TC, true>(st, cur, bq, b_cur, b_nxt, k);
-    sched_group<0x100, 2>();
-    sched_group<0x008, MM>();
+    tile_multiply<DT, SPARSE, TR, TC, NWC, TH, TC, true, D, OFF>(st, cur, bq, b_cur, b_nxt, k);
+#pragma unroll
+    for (int j = TH; j < TC; j++) {
+      sched_group<0x100, 2>();
+      sched_group<0x008, MM>();
+    }
     sched_fence();
   } else {
-    const uint4* bn = b_nxt + (st.wc * TC) * 128 + st.lane;
-    bq.b0 = bn[0];
-    bq.b1 = bn[64];
+    const uint4* bn = b_nxt + (st.wc * TC) * 128 + st.lane;  // D == 1 here
+    bq[0].b0 = bn[0];
+    bq[0].b1 = bn[64];
   }
 }
 
-template <int DT, int SPARSE, int TR, int TC, int NWC>
+template <int DT, int SPARSE, int TR, int TC, int NWC, int D>
 __device__ __attribute__((always_inline)) void tile_pipeline(
     uint4* __restrict__ sa0, uint4* __restrict__ sa1, uint4* __restrict__ sa2, uint4* __restrict__ sb0, uint4* __restrict__ sb1,
     uint4* __restrict__ sb2, uint32_t* __restrict__ sm0, uint32_t* __restrict__ sm1, uint32_t* __restrict__ sm2,
@@ -905,18 +915,24 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
   tile_load_a<SPARSE, TR, TC, NWC>(st, sa0, sm0, r0);
   sched_fence();
   tile_arrive<0>();  // every wave has its first A side in registers before the first stage overwrites its buffer
-  TileB bq;          // the B operand of the coming stage's first token tile
-  bq.b0 = sb0[(st.wc * TC) * 128 + st.lane];
-  bq.b1 = sb0[(st.wc * TC) * 128 + 64 + st.lane];
+  TileB bq[D];       // the B operands of the coming stage's first D token tiles
+#pragma unroll
+  for (int d = 0; d < D; d++) {
+    bq[d].b0 = sb0[(st.wc * TC + d) * 128 + st.lane];
+    bq[d].b1 = sb0[(st.wc * TC + d) * 128 + 64 + st.lane];
+  }
+  // the register set a stage finds its first operand in moves by TC % D from stage to stage and is back after three
+  constexpr int O1 = TC % D, O2 = (2 * TC) % D;
+  static_assert((3 * TC) % D == 0, "the operand ring must be back in place after the three unrolled stages");
   unsigned k = kb;
   for (; k + 3 <= st.k1; k += 3) {
-    tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, bq, sb0, sb1, sa1, sm1, sb2, sa0, sm0, k);
-    tile_stage<DT, SPARSE, TR, TC, NWC>(st, r1, r0, bq, sb1, sb2, sa2, sm2, sb0, sa1, sm1, k + 1);
-    tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, bq, sb2, sb0, sa0, sm0, sb1, sa2, sm2, k + 2);
+    tile_stage<DT, SPARSE, TR, TC, NWC, D, 0>(st, r0, r1, bq, sb0, sb1, sa1, sm1, sb2, sa0, sm0, k);
+    tile_stage<DT, SPARSE, TR, TC, NWC, D, O1>(st, r1, r0, bq, sb1, sb2, sa2, sm2, sb0, sa1, sm1, k + 1);
+    tile_stage<DT, SPARSE, TR, TC, NWC, D, O2>(st, r0, r1, bq, sb2, sb0, sa0, sm0, sb1, sa2, sm2, k + 2);
     r0 = r1;
   }
-  if (k < st.k1) tile_stage<DT, SPARSE, TR, TC, NWC>(st, r0, r1, bq, sb0, sb1, sa1, sm1, sb2, sa0, sm0, k);
-  if (k + 1 < st.k1) tile_stage<DT, SPARSE, TR, TC, NWC>(st, r1, r0, bq, sb1, sb2, sa2, sm2, sb0, sa1, sm1, k + 1);
+  if (k < st.k1) tile_stage<DT, SPARSE, TR, TC, NWC, D, 0>(st, r0, r1, bq, sb0, sb1, sa1, sm1, sb2, sa0, sm0, k);
+  if (k + 1 < st.k1) tile_stage<DT, SPARSE, TR, TC, NWC, D, O1>(st, r1, r0, bq, sb1, sb2, sa2, sm2, sb0, sa1, sm1, k + 1);
 #if defined(__HIP_DEVICE_COMPILE__)
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no DMA into this workgroup's LDS is left in flight when the wave ends
 #endif
@@ -939,7 +955,7 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
 }
 
 // sparse: TR = 8 (macro tile of 16 row tiles) or 4; dense: half of that (operands twice as wide).
-template <int DT, int SPARSE, int TR, int TC, int NWC>
+template <int DT, int SPARSE, int TR, int TC, int NWC, int D = 1>
 __global__ void __launch_bounds__(128 * NWC) k_mm_tile(const uint4* __restrict__ A, const uint16_t* __restrict__ meta16,
                                                         const uint4* __restrict__ Xf, uint16_t* __restrict__ Y,
                                                         float* __restrict__ partial, long long M, long long N, long long Mp,
@@ -955,8 +971,283 @@ __global__ void __launch_bounds__(128 * NWC) k_mm_tile(const uint4* __restrict__
   __shared__ uint32_t s_m0[SPARSE ? ASLOTS : 1];  // one stage pair of index words each: [row tiles][64 lanes]
   __shared__ uint32_t s_m1[SPARSE ? ASLOTS : 1];
   __shared__ uint32_t s_m2[SPARSE ? ASLOTS : 1];
-  tile_pipeline<DT, SPARSE, TR, TC, NWC>(s_a0, s_a1, s_a2, s_b0, s_b1, s_b2, s_m0, s_m1, s_m2, A, meta16, Xf, Y, partial, M, N, Mp,
+  tile_pipeline<DT, SPARSE, TR, TC, NWC, D>(s_a0, s_a1, s_a2, s_b0, s_b1, s_b2, s_m0, s_m1, s_m2, A, meta16, Xf, Y, partial, M, N, Mp,
                                          Np, Kp, n_tiles, ntb, nsplit, sps);
+}
+
+// ------------------------------------------------------------------------------------------------
+// variant "tile32" (2:4 only): the same workgroup, LDS ring and DMA schedule as the 8-wave 256 x 256 tile
+// kernel above, but a wave's 128 rows x 64 tokens are 4 x 2 tiles of v_smfmac_f32_32x32x32 (half as many
+// matrix instructions for the same operand bytes; the instruction also peaks 10 % higher), and the outputs
+// leave through LDS: a wave transposes its tile 32 tokens at a time in a private LDS slice and stores 256-byte
+// runs of Y (128 output features of one token) instead of 32-byte pieces.
+// Operand layouts of v_smfmac_f32_32x32x32_{f16,bf16} (lane l, r = l % 32, h = l / 32), measured with one-hot
+// operands:  A: row r, the 8 kept values of channels [16 h, 16 h + 16) of the 32-channel step, value e at channel
+//            16 h + 4 (e / 2) + idx_e (idx_e = bits [2e+1 : 2e] of the low half of the lane's index register)
+//            B: column r, e < 8: k = 8 h + e;  e >= 8: k = 16 + 8 h + (e - 8)
+//            D: column r, register j holds row 8 (j / 4) + 4 h + j % 4
+// Both operands are read out of the LDS images the DMA leaves (the 16-byte units of the native weight layout and
+// of the fragment-major activations) by lane addressing alone: the A operand of the step's half q for rows
+// 32 i .. 32 i + 31 is unit 16 (2 q + h) + r % 16 of row tile 2 i + r / 16; the B operand for tokens 32 j .. + 31 is
+// units 16 h + r % 16 and 16 (2 + h) + r % 16 of half step q of token tile 2 j + r / 16.
+// ------------------------------------------------------------------------------------------------
+template <int DT>
+__device__ __forceinline__ floatx16_t smfmac32(uint4 a, uint4 b0, uint4 b1, floatx16_t c, int idx) {
+  struct B2 {
+    uint4 lo, hi;
+  } bb = {b0, b1};
+  if (DT == ESPARSE_F16) {
+    return __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half16_t, bb), c, idx, 0, 0);
+  } else {
+    return __builtin_amdgcn_smfmac_f32_32x32x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x16_t, bb), c, idx, 0, 0);
+  }
+}
+
+struct Tile32Regs {
+  uint4 a[2][4];     // [half of the 64-channel stage][32-row tile]
+  uint32_t m[2][4];  // raw index words (an even and an odd stage each)
+};
+struct Tile32Lane {
+  unsigned a_base;  // unit (and index-word) number of this lane's A operand for half 0, row tile 0
+  unsigned b_base;  // unit number of this lane's first B half for half 0, token tile 0
+};
+
+__device__ __forceinline__ void tile32_load_a(const Tile32Lane& ln, const uint4* sa, const uint32_t* sm, Tile32Regs& r) {
+#pragma unroll
+  for (int q = 0; q < 2; q++)
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      r.a[q][i] = sa[ln.a_base + i * 128 + q * 32];
+      r.m[q][i] = sm[ln.a_base + i * 128 + q * 32];
+    }
+}
+
+// multiplies of iterations IT0 .. IT1 - 1 of stage k; a wave owns TJ 32-token tiles and iteration it = (half q = it / TJ,
+// tile j = it % TJ).  On entry `bq` holds the B operand of iteration IT0; the next iteration's operand is read while one
+// is multiplied (after the stage's last iteration: the first operand of the next stage's buffer, if NEXT)
+template <int DT, int TJ, int IT0, int IT1, bool NEXT>
+__device__ __forceinline__ void tile32_multiply(const Tile32Lane& ln, const Tile32Regs& r, TileB& bq, const uint4* sb,
+                                                const uint4* sb_next, unsigned k, floatx16_t (&acc)[4][TJ]) {
+  const unsigned sh = (k & 1u) * 16u;
+#pragma unroll
+  for (int it = IT0; it < IT1; it++) {
+    const int q = it / TJ, j = it % TJ;
+    TileB nx = bq;
+    if (it + 1 < 2 * TJ) {
+      const int q2 = (it + 1) / TJ, j2 = (it + 1) % TJ;
+      nx.b0 = sb[ln.b_base + j2 * 256 + q2 * 64];
+      nx.b1 = sb[ln.b_base + j2 * 256 + q2 * 64 + 32];
+    } else if (NEXT) {
+      nx.b0 = sb_next[ln.b_base];
+      nx.b1 = sb_next[ln.b_base + 32];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) acc[i][j] = smfmac32<DT>(r.a[q][i], bq.b0, bq.b1, acc[i][j], (int)(r.m[q][i] >> sh));
+    bq = nx;
+  }
+}
+
+// one pipeline stage: the schedule of tile_stage (DMA of B(k+2) and A(k+3) issued, A(k+1) copied to registers, all
+// iterations but the last ahead of the barrier, the last across it)
+template <int DT, int TJ>
+__device__ __forceinline__ void tile32_stage(TileState<1, 8, 2 * TJ, 4>& st, const Tile32Lane& ln, const Tile32Regs& cur,
+                                             Tile32Regs& nxt, TileB& bq, const uint4* b_cur, const uint4* b_nxt, const uint4* a_nxt,
+                                             const uint32_t* m_nxt, uint4* b_pre, uint4* a_pre, uint32_t* m_pre, unsigned k,
+                                             floatx16_t (&acc)[4][TJ]) {
+  using State = TileState<1, 8, 2 * TJ, 4>;
+  constexpr int DMA = State::BCOPIES + 2 * State::ACOPIES;
+  constexpr int ITERS = 2 * TJ, TH = ITERS - 1;
+  constexpr int DPJ = (DMA + TH - 1) / TH;
+  constexpr int APJ = (16 + TH - 1) / TH;
+  const unsigned last = st.k1 - 1;
+  tile_prefetch_b<1, 8, 2 * TJ, 4>(st, b_pre, k + 2 < st.k1 ? k + 2 : last);
+  tile_prefetch_a<1, 8, 2 * TJ, 4>(st, a_pre, m_pre, k + 3 < st.k1 ? k + 3 : last);
+  tile32_multiply<DT, TJ, 0, TH, false>(ln, cur, bq, b_cur, b_nxt, k, acc);
+  tile32_load_a(ln, a_nxt, m_nxt, nxt);
+#pragma unroll
+  for (int j = 0; j < TH; j++) {
+    sched_group<0x100, 2>();
+    sched_group<0x008, 4>();
+    sched_group<0x010, DPJ>();
+    sched_group<0x100, APJ>();
+  }
+  sched_fence();
+  tile_arrive<DMA>();
+  sched_fence();
+  tile32_multiply<DT, TJ, TH, ITERS, true>(ln, cur, bq, b_cur, b_nxt, k, acc);
+  sched_group<0x100, 2>();
+  sched_group<0x008, 4>();
+  sched_fence();
+}
+
+// macro tile: 256 rows x 128 TJ tokens; waves 2 (rows) x 4 (tokens), a wave owns 128 rows x 32 TJ tokens.
+// nsplit > 1: K is split over workgroups and a workgroup stores an fp32 partial tile (k_reduce_splits adds them).
+template <int DT, int TJ>
+__global__ void __launch_bounds__(512) k_mm_tile32(const uint4* __restrict__ A, const uint16_t* __restrict__ meta16,
+                                                    const uint4* __restrict__ Xf, uint16_t* __restrict__ Y,
+                                                    float* __restrict__ partial, long long M, long long N, long long Mp,
+                                                    long long Np, long long Kp, long long n_tiles, long long ntb, int nsplit, int sps) {
+  using State = TileState<1, 8, 2 * TJ, 4>;
+  constexpr int ASLOTS = State::ASLOTS;
+  constexpr int NTT = 8 * TJ;  // token tiles of 16 in the macro tile
+  __shared__ uint4 s_a0[ASLOTS];
+  __shared__ uint4 s_a1[ASLOTS];
+  __shared__ uint4 s_a2[ASLOTS];
+  __shared__ uint4 s_b0[NTT * 128];
+  __shared__ uint4 s_b1[NTT * 128];
+  __shared__ uint4 s_b2[NTT * 128];
+  __shared__ uint32_t s_m0[ASLOTS];
+  __shared__ uint32_t s_m1[ASLOTS];
+  __shared__ uint32_t s_m2[ASLOTS];
+  uint4* __restrict__ sa0 = s_a0;
+  uint4* __restrict__ sa1 = s_a1;
+  uint4* __restrict__ sa2 = s_a2;
+  uint4* __restrict__ sb0 = s_b0;
+  uint4* __restrict__ sb1 = s_b1;
+  uint4* __restrict__ sb2 = s_b2;
+  uint32_t* __restrict__ sm0 = s_m0;
+  uint32_t* __restrict__ sm1 = s_m1;
+  uint32_t* __restrict__ sm2 = s_m2;
+  const int tid = threadIdx.x;
+  State st;
+  st.lane = (unsigned)(tid & 63);
+  st.wave = (unsigned)wave_uniform(tid >> 6);
+  st.wr = st.wave / 4;
+  st.wc = st.wave % 4;
+  const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
+  // XCD x (= blockIdx % 8) works through items [x * per, (x + 1) * per); an item is a macro tile and one of the
+  // nsplit ranges of K stages (the split varies fastest)
+  const long long n_items = n_tiles * nsplit;
+  const long long per = (n_items + 7) / 8;
+  const long long item = (long long)(blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if ((long long)(blockIdx.x >> 3) >= per || item >= n_items) return;
+  const long long tile = item / nsplit;
+  const int split = (int)(item % nsplit);
+  st.k0 = (unsigned)((long long)split * sps);
+  st.k1 = (unsigned)(((long long)(split + 1) * sps < nks) ? (long long)(split + 1) * sps : nks);
+  const long long rb = tile / ntb, tb = tile % ntb;
+  const long long rt_macro = rb * 16, tt_base = tb * NTT;
+#pragma unroll
+  for (int p = 0; p < State::ACOPIES; p++) {
+    const long long rtl = State::NW * p + st.wave;
+    const long long rt = (rt_macro + rtl < nrt) ? rt_macro + rtl : nrt - 1;
+    st.a_src[p] = A + rt * nks * 64;
+    st.m_src[p] = reinterpret_cast<const uint32_t*>(meta16) + rt * (nks / 4) * 128;
+  }
+#pragma unroll
+  for (int p = 0; p < State::BCOPIES; p++) {
+    const long long ttl = (State::NW / 2) * p + (st.wave >> 1);
+    const long long tt = (tt_base + ttl < ntt) ? tt_base + ttl : ntt - 1;
+    st.x_src[p] = Xf + tt * (2 * nks) * 64;
+  }
+  st.x_lane = (unsigned)(tid & 127);
+  Tile32Lane ln;
+  const unsigned r32 = st.lane & 31u, h = st.lane >> 5;
+  ln.a_base = (st.wr * 8u + (r32 >> 4)) * 64u + 16u * h + (r32 & 15u);
+  ln.b_base = (st.wc * (2u * TJ) + (r32 >> 4)) * 128u + 16u * h + (r32 & 15u);
+  floatx16_t acc[4][TJ];
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < TJ; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  const unsigned last = st.k1 - 1, kb = st.k0;
+  tile_prefetch_b<1, 8, 2 * TJ, 4>(st, sb0, kb);
+  tile_prefetch_a<1, 8, 2 * TJ, 4>(st, sa0, sm0, kb);
+  tile_prefetch_b<1, 8, 2 * TJ, 4>(st, sb1, kb + 1 < st.k1 ? kb + 1 : last);
+  tile_prefetch_a<1, 8, 2 * TJ, 4>(st, sa1, sm1, kb + 1 < st.k1 ? kb + 1 : last);
+  tile_prefetch_a<1, 8, 2 * TJ, 4>(st, sa2, sm2, kb + 2 < st.k1 ? kb + 2 : last);
+  sched_fence();
+  tile_arrive<0>();
+  Tile32Regs r0, r1;
+  tile32_load_a(ln, sa0, sm0, r0);
+  sched_fence();
+  tile_arrive<0>();
+  TileB bq;
+  bq.b0 = sb0[ln.b_base];
+  bq.b1 = sb0[ln.b_base + 32];
+  unsigned k = kb;
+  for (; k + 3 <= st.k1; k += 3) {
+    tile32_stage<DT, TJ>(st, ln, r0, r1, bq, sb0, sb1, sa1, sm1, sb2, sa0, sm0, k, acc);
+    tile32_stage<DT, TJ>(st, ln, r1, r0, bq, sb1, sb2, sa2, sm2, sb0, sa1, sm1, k + 1, acc);
+    tile32_stage<DT, TJ>(st, ln, r0, r1, bq, sb2, sb0, sa0, sm0, sb1, sa2, sm2, k + 2, acc);
+    r0 = r1;
+  }
+  if (k < st.k1) tile32_stage<DT, TJ>(st, ln, r0, r1, bq, sb0, sb1, sa1, sm1, sb2, sa0, sm0, k, acc);
+  if (k + 1 < st.k1) tile32_stage<DT, TJ>(st, ln, r1, r0, bq, sb1, sb2, sa2, sm2, sb0, sa1, sm1, k + 1, acc);
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): no DMA into this workgroup's LDS is left in flight
+#endif
+  __syncthreads();  // every wave is done with the ring: its buffers now carry the outputs
+
+  const long long t_wave = (tt_base + st.wc * (2 * TJ)) * 16;  // first token and first output feature of this wave's tile
+  const long long n_wave = (rt_macro + st.wr * 8) * 16;
+  // epilogue: wave w transposes its 128 rows x 32 TJ tokens, 32 tokens at a time, in a private LDS slice (32 tokens x
+  // (256 + 16) bytes, carved out of the weight and activation rings) and stores 256-byte runs of Y
+  constexpr unsigned EP_ROW = 272, EP_SLICE = 32 * EP_ROW;
+  // TJ = 2: eight slices at once (three in each of two activation buffers, one in each of two weight buffers);
+  // TJ = 1 (buffers half the size): four slices, waves 0-3 first, then waves 4-7
+  constexpr int PHASES = TJ == 1 ? 2 : 1;
+  static_assert((TJ == 2 ? 3 * EP_SLICE : EP_SLICE) <= NTT * 128 * 16 && EP_SLICE <= ASLOTS * 16, "the epilogue slices fit the rings");
+  unsigned char* ep;
+  if (TJ == 2)
+    ep = st.wave < 3 ? reinterpret_cast<unsigned char*>(s_b0) + st.wave * EP_SLICE
+                     : (st.wave < 6 ? reinterpret_cast<unsigned char*>(s_b1) + (st.wave - 3u) * EP_SLICE
+                                    : (st.wave == 6 ? reinterpret_cast<unsigned char*>(s_a0) : reinterpret_cast<unsigned char*>(s_a1)));
+  else
+    ep = (st.wave & 3u) == 0 ? reinterpret_cast<unsigned char*>(s_a0)
+                             : ((st.wave & 3u) == 1 ? reinterpret_cast<unsigned char*>(s_a1)
+                                                    : ((st.wave & 3u) == 2 ? reinterpret_cast<unsigned char*>(s_a2) : reinterpret_cast<unsigned char*>(s_b0)));
+  const bool wide = (N & 7) == 0 && nsplit == 1;  // 16-byte stores of 8 output features
+  if (wide) {
+#pragma unroll
+    for (int ph = 0; ph < PHASES; ph++)
+#pragma unroll
+      for (int j = 0; j < TJ; j++) {
+        const bool mine = PHASES == 1 || (int)(st.wave >> 2) == ph;  // wave-uniform
+        if (mine) {
+#pragma unroll
+          for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int a = 0; a < 4; a++) {
+              uint2 v;
+              v.x = esp_from_float<DT>(acc[i][j][4 * a]) | ((uint32_t)esp_from_float<DT>(acc[i][j][4 * a + 1]) << 16);
+              v.y = esp_from_float<DT>(acc[i][j][4 * a + 2]) | ((uint32_t)esp_from_float<DT>(acc[i][j][4 * a + 3]) << 16);
+              *reinterpret_cast<uint2*>(ep + r32 * EP_ROW + (32 * i + 8 * a + 4 * h) * 2) = v;
+            }
+        }
+        __syncthreads();
+        if (mine) {
+#pragma unroll
+          for (int p = 0; p < 8; p++) {
+            const unsigned tl = p * 4u + (st.lane >> 4), piece = st.lane & 15u;
+            const uint4 v = *reinterpret_cast<const uint4*>(ep + tl * EP_ROW + piece * 16u);
+            const long long t = t_wave + 32 * j + tl;
+            const long long n = n_wave + piece * 8;
+            if (t < M && n + 8 <= N) *reinterpret_cast<uint4*>(Y + t * N + n) = v;
+          }
+        }
+        __syncthreads();
+      }
+  } else {
+#pragma unroll
+    for (int j = 0; j < TJ; j++)
+#pragma unroll
+      for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int a = 0; a < 4; a++) {
+          const long long t = t_wave + 32 * j + r32;
+          const long long n = n_wave + 32 * i + 8 * a + 4 * h;
+          const floatx4_t v = {acc[i][j][4 * a], acc[i][j][4 * a + 1], acc[i][j][4 * a + 2], acc[i][j][4 * a + 3]};
+          if (nsplit > 1) {
+            if (t < Mp && n < Np) *reinterpret_cast<floatx4_t*>(partial + ((long long)split * Mp + t) * Np + n) = v;
+          } else {
+            store_y4<DT>(Y, M, N, t, n, v);
+          }
+        }
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1187,6 +1478,8 @@ struct Variant {
   int split_mode;  // wave and tile kinds: 0 = never split K, 1 = split K over workgroups to fill the chip
   int nw;          // ksplit kind: waves per workgroup; tile kind: waves along the tokens (the workgroup has 2 x nw waves)
   int quads;       // ksplit kind: 1 = a wave takes four consecutive steps with one index load (2:4, at most 16 tokens)
+  int x32;         // tile kind: 1 = the 32x32x32 form of the sparse instruction and the epilogue through LDS (2:4 only)
+  int depth;       // tile kind: token tiles the activation operands are read ahead (0 = 1)
 };
 static const Variant kVariants[] = {
     {"wave_r2_t1_splitk", KIND_WAVE, 2, 1, 1, 0},
@@ -1234,6 +1527,13 @@ static const Variant kVariants[] = {
     {"stream_w9_r1_d3", KIND_STREAM, 1, 4, 1, 9},
     // eleven waves (176 rows): 22016 rows are 126 row blocks, two aligned spans each
     {"stream_w11_r1_d3", KIND_STREAM, 1, 4, 1, 11},
+    // the 8-wave 256 x 256 tile with v_smfmac_f32_32x32x32 and outputs stored in 256-byte runs (2:4 only)
+    {"tile32_w8_t256", KIND_TILE, 8, 4, 0, 4, 0, 1},
+    {"tile32_w8_t128", KIND_TILE, 8, 2, 0, 4, 0, 1},         // ... 256 rows x 128 tokens
+    {"tile32_w8_t128_splitk", KIND_TILE, 8, 2, 1, 4, 0, 1},  // ... with K split over workgroups (M <= 512)
+    // the 4-wave 256 x 256 tile (one wave per SIMD, 256 accumulators each: fewer LDS reads per multiply) with the
+    // activation operands read three token tiles ahead, so that the wave's own multiplies cover the LDS latency
+    {"tile_t256_d3", KIND_TILE, 8, 8, 0, 2, 0, 0, 3},
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -1260,6 +1560,7 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
     if ((long long)var.nw * var.rt * mt * 1024 > 160 * 1024) return false;
   }
   if (var.kind == KIND_TILE && M < 64) return false;
+  if (var.x32 && sparse != 1) return false;
   if (var.kind == KIND_STREAM && M > 128) return false;
   return true;
 }
@@ -1298,7 +1599,7 @@ int esp_default_variant(long long M, long long N, long long K, int sparse) {
   // 8-wave tile kernels: the largest macro tile that still gives half of the 256 CUs a tile
   const long long rows = sparse ? 256 : 128;
   const long long nrb = (N + rows - 1) / rows;
-  if (nrb * ((M + 255) / 256) >= 128) return 12;  // tile_w8_t256
+  if (nrb * ((M + 255) / 256) >= 128) return sparse == 1 ? variant_index("tile32_w8_t256") : 12;  // tile_w8_t256 (dense)
   if (nrb * ((M + 127) / 128) >= 128) return 13;  // tile_w8_t128
   return 14;                                       // tile_w8_r128_t128
 }
@@ -1428,10 +1729,22 @@ static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const
   }
   const long long per = (n_tiles * nsplit + 7) / 8;
   dim3 grid((unsigned)(per * 8));
+  if (v.x32) {
+    if (SPARSE != 1) return esp_fail(ctx, ESPARSE_EINVAL, "the 32x32x32 tile kernel multiplies 2:4 weights only");
+    if (v.tt == 4)
+      hipLaunchKernelGGL((k_mm_tile32<DT, 2>), grid, dim3(512), 0, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, n_tiles, ntb, nsplit, (int)sps);
+    else
+      hipLaunchKernelGGL((k_mm_tile32<DT, 1>), grid, dim3(512), 0, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, n_tiles, ntb, nsplit, (int)sps);
+    ESP_HIP(ctx, hipGetLastError());
+  } else
+  {
 #define ESP_TILE(TRv, TCv, NWCv)                                                                                             \
   hipLaunchKernelGGL((k_mm_tile<DT, SPARSE, (SPARSE ? TRv : TRv / 2), TCv, NWCv>), grid, dim3(128 * NWCv), 0, st, A, meta16, Xf, Y, \
                      partial, M, N, Mp, Np, Kp, n_tiles, ntb, nsplit, (int)sps)
-  if (v.rt == 8 && v.nw == 2 && v.tt == 8) ESP_TILE(8, 8, 2);
+  if (v.rt == 8 && v.nw == 2 && v.tt == 8 && v.depth == 3)
+    hipLaunchKernelGGL((k_mm_tile<DT, SPARSE, (SPARSE ? 8 : 4), 8, 2, 3>), grid, dim3(256), 0, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp,
+                       n_tiles, ntb, nsplit, (int)sps);
+  else if (v.rt == 8 && v.nw == 2 && v.tt == 8) ESP_TILE(8, 8, 2);
   else if (v.rt == 8 && v.nw == 2 && v.tt == 4) ESP_TILE(8, 4, 2);
   else if (v.rt == 8 && v.nw == 4 && v.tt == 4) ESP_TILE(8, 4, 4);
   else if (v.rt == 8 && v.nw == 4 && v.tt == 2) ESP_TILE(8, 2, 4);
@@ -1442,6 +1755,7 @@ static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const
   else return esp_fail(ctx, ESPARSE_EINVAL, "unknown tile variant");
 #undef ESP_TILE
   ESP_HIP(ctx, hipGetLastError());
+  }
   if (nsplit > 1) {
     const long long e = M * (Np / 4);
     if (DT == ESPARSE_F16)
