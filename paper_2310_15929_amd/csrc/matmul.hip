@@ -150,6 +150,10 @@ struct KsplitArgs {
   uint16_t* Y[ESP_MAX_GROUP];
   float* partial;  // single products with K split over workgroups (gridDim.z > 1): fp32 partial tiles [split][Mp][Np]
   int sps;         // ... and the steps per split
+  // FOLD kernels (one or two tokens): the activations in original channel order and theta; the workgroup gathers them itself
+  const uint16_t* X[ESP_MAX_GROUP];
+  const int32_t* perm[ESP_MAX_GROUP];
+  long long K;
 };
 
 // mc > 0 (at most 16 tokens): a second, compact copy follows the fragment-major one (units [units, units + mc Kp / 8)):
@@ -445,14 +449,48 @@ __global__ void __launch_bounds__(256) k_mm_wave_tile(const uint4* __restrict__ 
 // the result does not depend on timing and no global synchronisation is needed.
 // grid = ceil(row tiles / RT), block = 64 * NW.
 // ------------------------------------------------------------------------------------------------
-template <int DT, int SPARSE, int MT, int RT, int NW, int IDXM>
+// FOLD (one or two tokens, MT = 1): there is no staged copy and no staging launch; the workgroup applies the channel
+// re-ordering of Section 3.3 itself: it gathers X[t, theta[p]] for all p into LDS (2 Kp bytes per token, the layout of the
+// compact copy) while its first weight loads are under way, and the waves read their activation operands from there.
+template <int DT, int SPARSE, int MT, int RT, int NW, int IDXM, bool FOLD = false>
 __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long long M, long long N, long long Mp, long long Np,
                                                         long long Kp, int mc) {
+  static_assert(!FOLD || MT == 1, "the fold exists for the compact activation layout only");
   const uint4* __restrict__ A = args.A[blockIdx.y];
   const uint16_t* __restrict__ meta16 = args.meta16[blockIdx.y];
   const uint4* __restrict__ Xf = args.Xf[blockIdx.y];
   uint16_t* __restrict__ Y = args.Y[blockIdx.y];
-  extern __shared__ floatx4_t s_red[];  // [NW][RT * MT][64]
+  extern __shared__ floatx4_t s_red[];  // [NW][RT * MT][64]; FOLD: followed by the gathered activations [Kp / 8][mc]
+  uint4* s_x = reinterpret_cast<uint4*>(s_red + NW * RT * MT * 64);
+  if (FOLD) {
+    const uint16_t* __restrict__ X = args.X[blockIdx.y];
+    const int32_t* __restrict__ perm = args.perm[blockIdx.y];
+    const long long K = args.K;
+    for (long long u = threadIdx.x; u < Kp / 8; u += NW * 64) {
+      const long long k0 = u * 8;
+      int p[8];
+      if (perm && k0 + 8 <= K) {
+        const int4 p0 = *reinterpret_cast<const int4*>(perm + k0);
+        const int4 p1 = *reinterpret_cast<const int4*>(perm + k0 + 4);
+        p[0] = p0.x, p[1] = p0.y, p[2] = p0.z, p[3] = p0.w, p[4] = p1.x, p[5] = p1.y, p[6] = p1.z, p[7] = p1.w;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; e++) p[e] = k0 + e < K ? (perm ? perm[k0 + e] : (int)(k0 + e)) : -1;
+      }
+      for (int c = 0; c < mc; c++) {
+        uint16_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) v[e] = (c < M && p[e] >= 0) ? X[(long long)c * K + p[e]] : (uint16_t)0;
+        uint4 o;
+        o.x = v[0] | ((uint32_t)v[1] << 16);
+        o.y = v[2] | ((uint32_t)v[3] << 16);
+        o.z = v[4] | ((uint32_t)v[5] << 16);
+        o.w = v[6] | ((uint32_t)v[7] << 16);
+        s_x[u * mc + c] = o;
+      }
+    }
+    __syncthreads();
+  }
   // SPARSE == 2 (4:8): byte-permute selectors that spread a group's 4 kept values over its 8 positions,
   // one 16-byte entry per bitmap: output half e takes value number popcount(bitmap below bit e) if
   // bit e is set and 0 otherwise (selector byte 0x0c yields 0x00)
@@ -537,8 +575,13 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long lon
 #pragma unroll
           for (int u = 0; u < 4; u++) {
             const long long k = ks + u;
-            b0[u][0] = Xc[((2 * k) * 4 + g) * mc + c];
-            b1[u][0] = Xc[((2 * k + 1) * 4 + g) * mc + c];
+            if (FOLD) {
+              b0[u][0] = s_x[((2 * k) * 4 + g) * mc + c];
+              b1[u][0] = s_x[((2 * k + 1) * 4 + g) * mc + c];
+            } else {
+              b0[u][0] = Xc[((2 * k) * 4 + g) * mc + c];
+              b1[u][0] = Xc[((2 * k + 1) * 4 + g) * mc + c];
+            }
           }
         }
       } else {
@@ -593,8 +636,13 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long lon
         const int c = lane & 15, g = lane >> 4;
         const bool live = c < mc;
         const uint4* Xc = Xf + Kp * 2;  // behind the 16 x Kp fragment-major copy
-        b0[u][0] = live ? Xc[((2 * kk[u]) * 4 + g) * mc + c] : zero;
-        b1[u][0] = live ? Xc[((2 * kk[u] + 1) * 4 + g) * mc + c] : zero;
+        if (FOLD) {
+          b0[u][0] = live ? s_x[((2 * kk[u]) * 4 + g) * mc + c] : zero;
+          b1[u][0] = live ? s_x[((2 * kk[u] + 1) * 4 + g) * mc + c] : zero;
+        } else {
+          b0[u][0] = live ? Xc[((2 * kk[u]) * 4 + g) * mc + c] : zero;
+          b1[u][0] = live ? Xc[((2 * kk[u] + 1) * 4 + g) * mc + c] : zero;
+        }
       } else {
 #pragma unroll
         for (int j = 0; j < MT; j++) {
@@ -1668,21 +1716,36 @@ static void launch_wave_tile(const Variant& v, dim3 grid, hipStream_t st, const 
 #undef LAUNCH
 }
 
+// Whether the decode kernel gathers the activations through theta itself (no staged copy, no staging launch): one or two
+// tokens, a variant that keeps K inside the workgroup, and the gathered copy (2 Kp bytes per token) fits beside the
+// reduction buffer in the 64 KiB of LDS a launch may ask for without further ado.
+static bool ksplit_folds(const Variant& v, long long M, long long Kp) {
+  if (v.kind != KIND_KSPLIT || v.split_mode != 0 || M > 2) return false;
+  const size_t red = (size_t)v.nw * v.rt * 64 * 16, gathered = (size_t)2 * Kp * compact_tokens(M);
+  return red + gathered <= 64 * 1024;
+}
+
 template <int DT, int SPARSE, int MT>
 static void launch_ksplit(const Variant& v, hipStream_t st, KsplitArgs args, int count, long long M, long long N, long long Mp,
-                          long long Np, long long Kp, int mc, int nsplit) {
+                          long long Np, long long Kp, int mc, int nsplit, bool fold) {
   const long long nrt = Np / 16, nks = Kp / 64;
   // K split over workgroups: single products only; splits of a multiple of four steps
   const long long sps = nsplit > 1 ? ((nks + nsplit - 1) / nsplit + 3) / 4 * 4 : nks;
   nsplit = (int)((nks + sps - 1) / sps);
   args.sps = (int)sps;
   dim3 grid((unsigned)((nrt + v.rt - 1) / v.rt), (unsigned)count, (unsigned)nsplit);
-  const size_t smem = (size_t)v.nw * v.rt * MT * 64 * 16;
+  fold = fold && MT == 1 && mc > 0 && nsplit == 1;
+  const size_t smem = (size_t)v.nw * v.rt * MT * 64 * 16 + (fold ? (size_t)2 * Kp * mc : 0);
   const bool pairs = SPARSE == 1 && MT >= 2 && ((sps / 2) % v.nw) == 0 && nks % sps == 0;
   const bool quads = v.quads != 0;
 #define LAUNCH(R, W)                                                                                                          \
   do {                                                                                                                        \
-    if (SPARSE == 1 && MT == 1 && quads && ((R == 1) || (W == 8 && (R == 2 || R == 4))))                                      \
+    if (MT == 1 && fold && SPARSE == 1 && quads && ((R == 1) || (W == 8 && (R == 2 || R == 4))))                              \
+      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, (SPARSE == 1 && MT == 1 && ((R == 1) || (W == 8 && (R == 2 || R == 4))) ? 2 : 0), MT == 1>), \
+                         grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp, mc);                                           \
+    else if (MT == 1 && fold)                                                                                                 \
+      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, 0, MT == 1>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp, mc); \
+    else if (SPARSE == 1 && MT == 1 && quads && ((R == 1) || (W == 8 && (R == 2 || R == 4))))                                 \
       hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, (SPARSE == 1 && MT == 1 && ((R == 1) || (W == 8 && (R == 2 || R == 4))) ? 2 : 0)>), \
                          grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp, mc);                                           \
     else if (SPARSE == 1 && MT >= 2 && pairs)                                                                                 \
@@ -1893,7 +1956,7 @@ static int stage_activations(esparse_ctx* ctx, const void* X, const int32_t* per
 
 // the decode kernels on `count` products of one shape: members share M, N, K; ka holds their operands
 static int launch_ksplit_any(esparse_ctx* ctx, const Variant& v, int sparse, int dtype, KsplitArgs ka, int count, long long M,
-                             long long N, long long Np, long long Kp) {
+                             long long N, long long Np, long long Kp, bool fold = false) {
   const int mc = compact_tokens(M);
   // variants with K split over workgroups (tt = splits): single products of at most 64 tokens with room for the partial tiles
   const int nsplit = (v.split_mode == 1 && count == 1 && M <= 64 && ka.partial) ? v.tt : 1;
@@ -1908,9 +1971,9 @@ static int launch_ksplit_any(esparse_ctx* ctx, const Variant& v, int sparse, int
     }
 #define ESP_KSPLIT(DTv, SPv)                                                          \
   do {                                                                                \
-    if (mcp == 16) launch_ksplit<DTv, SPv, 1>(v, st, kc, count, mcur, N, mcp, Np, Kp, mc, nsplit);  \
-    else if (mcp == 32) launch_ksplit<DTv, SPv, 2>(v, st, kc, count, mcur, N, mcp, Np, Kp, 0, nsplit); \
-    else launch_ksplit<DTv, SPv, 4>(v, st, kc, count, mcur, N, mcp, Np, Kp, 0, nsplit);            \
+    if (mcp == 16) launch_ksplit<DTv, SPv, 1>(v, st, kc, count, mcur, N, mcp, Np, Kp, mc, nsplit, fold);  \
+    else if (mcp == 32) launch_ksplit<DTv, SPv, 2>(v, st, kc, count, mcur, N, mcp, Np, Kp, 0, nsplit, false); \
+    else launch_ksplit<DTv, SPv, 4>(v, st, kc, count, mcur, N, mcp, Np, Kp, 0, nsplit, false);            \
   } while (0)
     if (dtype == ESPARSE_F16) {
       if (sparse == 2) ESP_KSPLIT(ESPARSE_F16, 2);
@@ -1941,7 +2004,9 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
   const Variant& v = kVariants[variant];
   const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
   int rc;
-  if ((phases & ESP_PHASE_STAGE) && (rc = stage_activations(ctx, X, perm, M, K, Mp, Kp, Xf, compact_tokens(M)))) return rc;
+  // one or two tokens through a decode kernel, both halves in one call: the kernel gathers through theta itself
+  const bool fold = phases == (ESP_PHASE_STAGE | ESP_PHASE_MULTIPLY) && ksplit_folds(v, M, Kp);
+  if ((phases & ESP_PHASE_STAGE) && !fold && (rc = stage_activations(ctx, X, perm, M, K, Mp, Kp, Xf, compact_tokens(M)))) return rc;
   if (!(phases & ESP_PHASE_MULTIPLY)) return ESPARSE_OK;
 
   if (v.kind == KIND_KSPLIT) {
@@ -1951,7 +2016,10 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
     ka.Xf[0] = Xf;
     ka.Y[0] = Y;
     ka.partial = partial;
-    return launch_ksplit_any(ctx, v, sparse, dtype, ka, 1, M, N, Np, Kp);
+    ka.X[0] = reinterpret_cast<const uint16_t*>(X);
+    ka.perm[0] = perm;
+    ka.K = K;
+    return launch_ksplit_any(ctx, v, sparse, dtype, ka, 1, M, N, Np, Kp, fold);
   }
 
   if (v.kind == KIND_TILE) {
@@ -2032,8 +2100,14 @@ int esp_matmul_group_device(esparse_ctx* ctx, int sparse, int count, const void*
   const size_t xbytes = staged_bytes(M, K);
   GatherArgs ga = {};
   KsplitArgs ka = {};
+  const bool fold = phases == (ESP_PHASE_STAGE | ESP_PHASE_MULTIPLY) && ksplit_folds(v, M, Kp);
+  ka.K = K;
   for (int i = 0; i < count; i++) {
     uint4* Xf = reinterpret_cast<uint4*>(ws + WS_HEADER_BYTES + (size_t)i * xbytes);
+    if (fold) {
+      ka.X[i] = reinterpret_cast<const uint16_t*>(X[i]);
+      ka.perm[i] = perm ? perm[i] : nullptr;
+    }
     if (phases & ESP_PHASE_STAGE) {
       ga.X[i] = reinterpret_cast<const uint16_t*>(X[i]);
       ga.perm[i] = perm ? perm[i] : nullptr;
@@ -2046,7 +2120,7 @@ int esp_matmul_group_device(esparse_ctx* ctx, int sparse, int count, const void*
       ka.Y[i] = reinterpret_cast<uint16_t*>(Y[i]);
     }
   }
-  if (phases & ESP_PHASE_STAGE) {
+  if ((phases & ESP_PHASE_STAGE) && !fold) {
     const int mc = compact_tokens(M);
     const long long units = Mp * Kp / 8, all = units + (long long)mc * (Kp / 8);
     hipLaunchKernelGGL(k_gather_x, dim3((unsigned)((all + 255) / 256), (unsigned)count), dim3(256), 0, ctx->stream, ga, M, K, Kp, units,
@@ -2054,7 +2128,7 @@ int esp_matmul_group_device(esparse_ctx* ctx, int sparse, int count, const void*
     ESP_HIP(ctx, hipGetLastError());
   }
   if (!(phases & ESP_PHASE_MULTIPLY)) return ESPARSE_OK;
-  return launch_ksplit_any(ctx, v, sparse, dtype, ka, count, M, N, Np, Kp);
+  return launch_ksplit_any(ctx, v, sparse, dtype, ka, count, M, N, Np, Kp, fold);
 }
 
 bool esp_variant_is_decode_kernel(int v) {

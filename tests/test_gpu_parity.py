@@ -373,6 +373,43 @@ def test_spmm_repeat_is_bitwise_identical_and_m0(esp, ctx):
     assert Y0.shape == (0, N)
 
 
+@pytest.mark.parametrize("M,K", [(1, 832), (2, 832), (1, 11008), (2, 4096), (1, 36864), (3, 832)])
+def test_spmm_theta_gathered_in_the_kernel_equals_staged(esp, ctx, M, K):
+    """With one or two tokens the decode kernels apply the channel re-ordering themselves (no staged copy, no staging
+    launch) where the gathered row fits the LDS; the result is bitwise the one of the two-step path (activations staged
+    through theta by a launch of their own, then multiplied) and within tolerance of the oracle.  K = 36864 at one token
+    and three tokens are beyond what is gathered in the kernel (both calls then take the staged path)."""
+    N = 80
+    rng = np.random.default_rng(M * 7 + K)
+    W = _rand((N, K), torch.float16, 61, scale=K ** -0.5)
+    X = _rand((M, K), torch.float16, 62, col_scale=wl.channel_scales("lognormal", K, wl.stream_id("xs", 62)))
+    theta = rng.permutation(K)
+    mask = orc.nm_mask_vectorised(_np(W), np.abs(rng.standard_normal(K)) + 0.1, theta, 2, 4)
+    th = torch.tensor(theta, dtype=torch.int32).cuda()
+    comp = ctx.compress(W.cuda(), torch.tensor(mask).cuda(), th, canonical=False)
+    Yref = orc.spmm_ref(_np(X), _np(W), theta, mask)
+    Xd = X.cuda()
+    ran = 0
+    for perm in (th, None):
+        ref = Yref if perm is not None else orc.spmm_ref(_np(X), _np(W[:, theta]), np.arange(K), mask)
+        comp_p = comp if perm is not None else ctx.compress(W[:, theta].contiguous().cuda(), torch.tensor(mask).cuda(), None, canonical=False)
+        for v in range(esp.num_variants()):
+            print(f"fold M={M} K={K} perm={'theta' if perm is not None else 'identity'} variant={esp.variant_name(v)}", flush=True)
+            try:
+                Y = ctx.spmm(Xd, comp_p, perm, variant=v)
+            except esp.EsparseError as e:
+                assert e.code == -2
+                continue
+            ws = ctx.stage_activations(Xd, perm, N)
+            Y2 = torch.empty_like(Y)
+            ctx.spmm_staged(M, comp_p, ws, Y2, variant=v)
+            torch.cuda.synchronize()
+            assert (_bits(Y) == _bits(Y2)).all(), esp.variant_name(v)
+            assert orc.rowwise_rel_error(_np(Y), ref).max() <= 2e-3
+            ran += 1
+    assert ran > 4
+
+
 @pytest.mark.parametrize("M", [8, 100, 300])
 def test_spmm_replayed_from_a_hip_graph(esp, ctx, M):
     """The calls enqueue kernels only (no allocation, no memset, no synchronisation), so a caller may capture them
