@@ -343,7 +343,8 @@ def main():
 
     def kernel_name(skey, M, cnt=1):
         v = tuned[f"{skey}/M={M}" + (f"/x{cnt}" if cnt > 1 else "")][0]
-        return {"ksplit": "k_mm_ksplit", "wave": "k_mm_wave_tile", "tile": "k_mm_tile", "stream": "k_mm_stream"}[v.split("_")[0]] + f" [{v}]"
+        return {"ksplit": "k_mm_ksplit", "wave": "k_mm_wave_tile", "tile": "k_mm_tile", "tile32": "k_mm_tile32",
+                "stream": "k_mm_stream"}[v.split("_")[0]] + f" [{v}]"
 
     per_shape = []
     seen = set()
@@ -502,7 +503,8 @@ def main():
             perr = float(orc.rowwise_rel_error(Yp[tt][:, ft].float().cpu().numpy(), Yref).max())
         pflops = 2.0 * pM * pN * pK
         pach = pflops / pts / 1e12
-        roofline_prefill = dict(bound="mfma", kernel=f"k_mm_tile [{esp.variant_name(pv)}] (2:4 sparse product, staged activations)",
+        roofline_prefill = dict(bound="mfma", kernel=("k_mm_tile32" if esp.variant_name(pv).startswith("tile32") else "k_mm_tile")
+                                + f" [{esp.variant_name(pv)}] (2:4 sparse product, staged activations)",
                                 workload="config 3 gate/up (LLaMA-13B-shaped), fp16, 2:4, GNS + LBS(64)",
                                 shape=f"M={pM} N={pN} K={pK}", achieved=round(pach, 1), peak=SPARSE_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
                                 frac=round(pach / SPARSE_MFMA_PEAK_TFLOPS, 4), flops_per_launch=pflops,
