@@ -986,6 +986,66 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
 #endif
 
   const int c = (int)(st.lane & 15), g = (int)(st.lane >> 4);
+  if (nsplit == 1 && (N & 7) == 0) {
+    // Outputs through LDS: a wave transposes its TR x TC tiles, CH tokens at a time, in a private slice of the (now idle)
+    // operand rings and stores runs of 32 TR bytes (the wave's 16 TR output features of one token) in 16-byte pieces;
+    // stored straight from the accumulators a lane would write 8 bytes of 16 different rows of Y per instruction.
+    constexpr int CHT = TC >= 2 ? 2 : 1;                   // token tiles per pass
+    constexpr unsigned ROWB = TR * 32 + 16;                // bytes per token in the slice (padded: the 16 tokens of a
+    constexpr unsigned SLICE = CHT * 16 * ROWB;            //   tile start in different banks)
+    constexpr unsigned ABYTES = State::ASLOTS * 16, BBYTES = NTT * 128 * 16;
+    constexpr int FA = ABYTES / SLICE, FB = BBYTES / SLICE;  // slices per weight / activation buffer
+    constexpr int SLOTS = 3 * (FA + FB) < State::NW ? 3 * (FA + FB) : State::NW;
+    static_assert(SLOTS >= 1, "no operand buffer holds an output slice");
+    constexpr int PHASES = (State::NW + SLOTS - 1) / SLOTS;  // waves take turns where the rings hold fewer slices than waves
+    constexpr int FAd = FA ? FA : 1, FBd = FB ? FB : 1;
+    const int slot = (int)st.wave % SLOTS, phase = (int)st.wave / SLOTS;
+    unsigned char* ep;
+    if (slot < 3 * FB) {
+      uint4* base = slot / FBd == 0 ? sb0 : (slot / FBd == 1 ? sb1 : sb2);
+      ep = reinterpret_cast<unsigned char*>(base) + (slot % FBd) * SLICE;
+    } else {
+      const int s2 = slot - 3 * FB;
+      uint4* base = s2 / FAd == 0 ? sa0 : (s2 / FAd == 1 ? sa1 : sa2);
+      ep = reinterpret_cast<unsigned char*>(base) + (s2 % FAd) * SLICE;
+    }
+    const long long t_wave = (tt_base + st.wc * TC) * 16, n_wave = (rt_macro + st.wr * TR) * 16;
+    __syncthreads();  // every wave is done with the rings
+#pragma unroll
+    for (int ph = 0; ph < PHASES; ph++)
+#pragma unroll
+      for (int j0 = 0; j0 < TC; j0 += CHT) {
+        const bool mine = PHASES == 1 || phase == ph;  // wave-uniform
+        if (mine) {
+#pragma unroll
+          for (int jj = 0; jj < CHT; jj++)
+#pragma unroll
+            for (int i = 0; i < TR; i++) {
+              const floatx4_t a = st.acc[i][j0 + jj];
+              uint2 v;
+              v.x = esp_from_float<DT>(a[0]) | ((uint32_t)esp_from_float<DT>(a[1]) << 16);
+              v.y = esp_from_float<DT>(a[2]) | ((uint32_t)esp_from_float<DT>(a[3]) << 16);
+              *reinterpret_cast<uint2*>(ep + (16 * jj + c) * ROWB + (16 * i + 4 * g) * 2) = v;
+            }
+        }
+        __syncthreads();
+        if (mine) {
+          constexpr int PIECES = CHT * 16 * TR * 2;  // 16-byte pieces of the pass
+#pragma unroll
+          for (int p = 0; p < (PIECES + 63) / 64; p++) {
+            const int pi = p * 64 + (int)st.lane;
+            const int tl = pi / (2 * TR), piece = pi % (2 * TR);
+            if (pi < PIECES) {
+              const uint4 v = *reinterpret_cast<const uint4*>(ep + tl * ROWB + piece * 16);
+              const long long t = t_wave + 16 * j0 + tl, n = n_wave + piece * 8;
+              if (t < M && n + 8 <= N) *reinterpret_cast<uint4*>(Y + t * N + n) = v;
+            }
+          }
+        }
+        __syncthreads();
+      }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < TR; i++) {
     const long long rt = rt_macro + st.wr * TR + i;
