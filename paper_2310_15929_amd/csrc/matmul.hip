@@ -1777,11 +1777,15 @@ static void launch_wave_tile(const Variant& v, dim3 grid, hipStream_t st, const 
 }
 
 // Whether the decode kernel gathers the activations through theta itself (no staged copy, no staging launch): one or two
-// tokens, a variant that keeps K inside the workgroup, and the gathered copy (2 Kp bytes per token) fits beside the
-// reduction buffer in the 64 KiB of LDS a launch may ask for without further ado.
-static bool ksplit_folds(const Variant& v, long long M, long long Kp) {
+// tokens, a variant that keeps K inside the workgroup, the gathered copy (2 Kp bytes per token) fits beside the reduction
+// buffer in the 64 KiB of LDS a launch may ask for without further ado - and the gather is cheap enough: every workgroup
+// repeats it, so it pays while workgroups x channels stays small (4096 x 4096: 7.0 us against 6.5 + 2.1 for the staging
+// launch; 36864 x 9216, 2304 workgroups: 77 us against 58 + 2.3, hence the limits).
+static bool ksplit_folds(const Variant& v, long long M, long long Np, long long Kp) {
   if (v.kind != KIND_KSPLIT || v.split_mode != 0 || M > 2) return false;
-  const size_t red = (size_t)v.nw * v.rt * 64 * 16, gathered = (size_t)2 * Kp * compact_tokens(M);
+  const long long mc = compact_tokens(M), groups = (Np / 16 + v.rt - 1) / v.rt;
+  if (Kp * mc > 10240 || groups * Kp * mc > 3000000) return false;
+  const size_t red = (size_t)v.nw * v.rt * 64 * 16, gathered = (size_t)2 * Kp * mc;
   return red + gathered <= 64 * 1024;
 }
 
@@ -2065,7 +2069,7 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
   const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
   int rc;
   // one or two tokens through a decode kernel, both halves in one call: the kernel gathers through theta itself
-  const bool fold = phases == (ESP_PHASE_STAGE | ESP_PHASE_MULTIPLY) && ksplit_folds(v, M, Kp);
+  const bool fold = phases == (ESP_PHASE_STAGE | ESP_PHASE_MULTIPLY) && ksplit_folds(v, M, Np, Kp);
   if ((phases & ESP_PHASE_STAGE) && !fold && (rc = stage_activations(ctx, X, perm, M, K, Mp, Kp, Xf, compact_tokens(M)))) return rc;
   if (!(phases & ESP_PHASE_MULTIPLY)) return ESPARSE_OK;
 
@@ -2160,7 +2164,7 @@ int esp_matmul_group_device(esparse_ctx* ctx, int sparse, int count, const void*
   const size_t xbytes = staged_bytes(M, K);
   GatherArgs ga = {};
   KsplitArgs ka = {};
-  const bool fold = phases == (ESP_PHASE_STAGE | ESP_PHASE_MULTIPLY) && ksplit_folds(v, M, Kp);
+  const bool fold = phases == (ESP_PHASE_STAGE | ESP_PHASE_MULTIPLY) && ksplit_folds(v, M, Np, Kp);
   ka.K = K;
   for (int i = 0; i < count; i++) {
     uint4* Xf = reinterpret_cast<uint4*>(ws + WS_HEADER_BYTES + (size_t)i * xbytes);

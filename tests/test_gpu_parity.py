@@ -378,7 +378,7 @@ def test_spmm_theta_gathered_in_the_kernel_equals_staged(esp, ctx, M, K):
     """With one or two tokens the decode kernels apply the channel re-ordering themselves (no staged copy, no staging
     launch) where the gathered row fits the LDS; the result is bitwise the one of the two-step path (activations staged
     through theta by a launch of their own, then multiplied) and within tolerance of the oracle.  K = 36864 at one token
-    and three tokens are beyond what is gathered in the kernel (both calls then take the staged path)."""
+     (and 11008) and three tokens are beyond what is gathered in the kernel (both calls then take the staged path)."""
     N = 80
     rng = np.random.default_rng(M * 7 + K)
     W = _rand((N, K), torch.float16, 61, scale=K ** -0.5)
