@@ -104,3 +104,20 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libesparse.so")
     with pytest.raises(FileNotFoundError):
         binding.load_library()
+
+
+def test_traffic_profile_rows_parse_and_name_existing_variants():
+    """bench.py looks roofline.traffic up in profiles/product_kernels_hbm_traffic.txt by shape and kernel variant: every
+    row must parse, name a variant the library has, and carry counter bytes of at least the algorithmic bytes."""
+    names = {esp.variant_name(v) for v in range(esp.num_variants())}
+    rows = [l for l in open(os.path.join(ROOT, "profiles", "product_kernels_hbm_traffic.txt")) if l.startswith("traffic ")]
+    assert len(rows) >= 10
+    seen = set()
+    for line in rows:
+        f = dict(kv.split("=", 1) for kv in line.split()[1:])
+        assert f["variant"] in names, f["variant"]
+        key = (f["members"], f["M"], f["N"], f["K"], f["variant"])
+        assert key not in seen
+        seen.add(key)
+        moved = int(f["fetch_bytes"]) + int(f["write_bytes"])
+        assert moved >= 0.98 * int(f["algorithmic_bytes"])
