@@ -74,3 +74,44 @@ def test_static_scratch_product_equals_workspace_product(capfd):
     # M = 0 is a no-op
     rc = lib.esparse_spmm_static(ctx._h, None, 0, None, None, 16, 16, 0, 2, 4, None, -1)
     assert rc == 0
+
+
+@pytest.mark.parametrize("M", [1, 2, 8, 70])
+def test_static_scratch_call_captured_in_a_hip_graph(M):
+    """The callers this entry point exists for: the whole call (theta gathered in the kernel for one or two tokens, the
+    staging launch into the library's scratch otherwise) is captured into a HIP graph once and replayed with new
+    activations, eager work of the same context between the replays; every replay reproduces the eager result of
+    esparse_spmm bit for bit."""
+    import paper_2310_15929_amd as esp
+    ctx = esp.Context(0)
+    N, K = 272, 2048
+    rng = np.random.default_rng(M)
+    W = wl.normal_matrix(N, K, wl.stream_id("nag-w", M), scale=K ** -0.5)
+    theta = rng.permutation(K)
+    mask = orc.nm_mask_vectorised(W.numpy(), np.ones(K), theta, 2, 4)
+    th = torch.tensor(theta, dtype=torch.int32).cuda()
+    comp = ctx.compress(W.cuda(), torch.tensor(mask).cuda(), th, canonical=False)
+    Xs = [wl.normal_matrix(M, K, wl.stream_id("nag-x", M, i)).cuda() for i in range(3)]
+    other = wl.normal_matrix(M + 3, K, wl.stream_id("nag-o", M)).cuda()
+    eager = [_bits(ctx.spmm(x, comp, th)) for x in Xs]
+    xin = Xs[0].clone()
+    yout = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    print(f"static scratch under graph capture M={M}", flush=True)
+    with torch.cuda.stream(side):
+        ctx.spmm_static(xin, comp, th, out=yout)                # warm-up on the side stream (looks the scratch address up)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            ctx.spmm_static(xin, comp, th, out=yout)
+    torch.cuda.synchronize()
+    for i in (1, 2, 0):
+        xin.copy_(Xs[i])
+        yout.zero_()
+        ctx.spmm(other, comp, th)                               # eager work between the replays (its own workspace)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert (_bits(yout) == eager[i]).all(), i
+    del g
