@@ -136,13 +136,17 @@ int esparse_compress(esparse_ctx* ctx, const void* W, const uint8_t* mask, const
  * esparse_compress.  workspace: DEVICE scratch of at least esparse_spmm_workspace bytes,
  * 256-byte aligned; it is overwritten.  variant: -1 = the one chosen by esparse_tune for this shape
  * (a built-in rule if never tuned), >= 0 = a specific kernel variant (EINVAL if out of range).
+ * esparse_spmm_workspace (host only, no context): variant -1 = the size that serves every variant of the
+ * shape - what a call with variant -1 requires, since tuning may change the choice after the caller has
+ * allocated; variant >= 0 = what that variant needs (the staged activations, plus fp32 partial tiles only
+ * for variants that split K over workgroups) - what a call naming that variant requires.
  * M = 0 is a no-op.  n:m = 2:4 runs on the sparse matrix instruction.  n:m = 4:8 (Section 4 lists it as a
  * format the hardware of the paper cannot multiply; there is no instruction for it here either): the
  * decode kernels expand each bitmap to a dense operand in registers and use the dense instruction, which
  * pays where the product is bound by reading the weights; inputs longer than 64 tokens are processed
  * 64 at a time; only decode-kernel variants apply (EUNSUPPORTED for the others).  Other n:m:
  * EUNSUPPORTED.  Does not synchronise. */
-int esparse_spmm_workspace(long long M, long long N, long long K, size_t* bytes);
+int esparse_spmm_workspace(long long M, long long N, long long K, int variant, size_t* bytes);
 int esparse_spmm(esparse_ctx* ctx, const void* X, long long M, const void* native_w,
                  const int32_t* perm, long long N, long long K, esparse_dtype dtype, int n_keep,
                  int m_group, void* Y, void* workspace, size_t workspace_bytes, int variant);

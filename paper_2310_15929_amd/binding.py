@@ -60,7 +60,7 @@ def load_library():
         "esparse_spmm_group_staged": (i32, [vp, i32, ll, P(vp), ll, ll, i32, i32, i32, P(vp), vp, sz, i32]),
         "esparse_compressed_size": (i32, [ll, ll, i32, i32, i32, P(sz), P(sz), P(sz)]),
         "esparse_compress": (i32, [vp, vp, vp, vp, ll, ll, i32, i32, i32, vp, vp, vp]),
-        "esparse_spmm_workspace": (i32, [ll, ll, ll, P(sz)]),
+        "esparse_spmm_workspace": (i32, [ll, ll, ll, i32, P(sz)]),
         "esparse_spmm": (i32, [vp, vp, ll, vp, vp, ll, ll, i32, i32, i32, vp, vp, sz, i32]),
         "esparse_spmm_static": (i32, [vp, vp, ll, vp, vp, ll, ll, i32, i32, i32, vp, i32]),
         "esparse_stage_activations": (i32, [vp, vp, ll, vp, ll, ll, i32, vp, sz]),
@@ -116,10 +116,10 @@ def compressed_size(N: int, K: int, n: int, m: int, dtype: int = F16):
     return a.value, b.value, c.value
 
 
-def spmm_workspace(M: int, N: int, K: int) -> int:
+def spmm_workspace(M: int, N: int, K: int, variant: int = -1) -> int:
     lib = load_library()
     a = C.c_size_t()
-    rc = lib.esparse_spmm_workspace(M, N, K, C.byref(a))
+    rc = lib.esparse_spmm_workspace(M, N, K, variant, C.byref(a))
     if rc:
         raise EsparseError(rc, "esparse_spmm_workspace")
     return a.value

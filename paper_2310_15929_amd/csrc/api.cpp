@@ -247,11 +247,12 @@ static int check_matmul(esparse_ctx* ctx, const void* X, long long M, const void
   ESP_REQUIRE(ctx, esp_aligned16(X) && esp_aligned16(w) && esp_aligned16(Y), ESPARSE_EINVAL,
               "X / weights / Y is not 16-byte aligned");
   ESP_REQUIRE(ctx, (reinterpret_cast<uintptr_t>(ws) & 255u) == 0, ESPARSE_EINVAL, "workspace is not 256-byte aligned");
-  ESP_REQUIRE(ctx, own_scratch || ws_bytes >= esp_workspace_bytes(M, N, K), ESPARSE_EWORKSPACE,
-              "workspace has %zu bytes, %zu needed", ws_bytes, esp_workspace_bytes(M, N, K));
   ESP_REQUIRE(ctx, variant >= -1 && variant < esp_num_variants(), ESPARSE_EINVAL, "variant %d does not exist", variant);
   ESP_REQUIRE(ctx, variant < 0 || esp_variant_applicable(variant, M, N, K, sparse), ESPARSE_EUNSUPPORTED,
               "variant %d (%s) cannot run M=%lld N=%lld K=%lld", variant, esp_variant_name(variant), M, N, K);
+  // a named variant needs what esparse_spmm_workspace reports for it; the tuned choice (-1) may be any variant
+  const size_t need = variant >= 0 ? esp_variant_workspace_bytes(variant, M, N, K) : esp_workspace_bytes(M, N, K);
+  ESP_REQUIRE(ctx, own_scratch || ws_bytes >= need, ESPARSE_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, need);
   return ESPARSE_OK;
 }
 
@@ -265,9 +266,9 @@ static int pick_variant(esparse_ctx* ctx, int sparse, int dtype, long long M, lo
   return esp_default_variant(M, N, K, sparse);
 }
 
-int esparse_spmm_workspace(long long M, long long N, long long K, size_t* bytes) {
-  if (!bytes || M < 0 || N < 1 || K < 4) return ESPARSE_EINVAL;
-  *bytes = esp_workspace_bytes(M, N, K);
+int esparse_spmm_workspace(long long M, long long N, long long K, int variant, size_t* bytes) {
+  if (!bytes || M < 0 || N < 1 || K < 4 || variant < -1 || variant >= esp_num_variants()) return ESPARSE_EINVAL;
+  *bytes = variant >= 0 ? esp_variant_workspace_bytes(variant, M, N, K) : esp_workspace_bytes(M, N, K);
   return ESPARSE_OK;
 }
 

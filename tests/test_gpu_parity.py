@@ -474,6 +474,39 @@ def test_workspace_too_small_and_bad_variant(esp, ctx):
     assert e.value.code == -1
 
 
+@pytest.mark.parametrize("M,N,K", [(33, 80, 2048), (130, 272, 1024), (600, 528, 768)])
+def test_named_variant_stays_inside_the_workspace_size_reported_for_it(esp, ctx, M, N, K):
+    # esparse_spmm_workspace(M, N, K, variant): a call naming that variant accepts exactly that many bytes, touches
+    # nothing behind them (a guard pattern follows the workspace) and gives the product of the full-size workspace
+    W = _rand((N, K), torch.float16, 81)
+    comp = ctx.compress(torch.tensor(_np(W) * np.tile([1, 0, 1, 0], (N, K // 4)), dtype=torch.float16).cuda(), None, None)
+    X = _rand((M, K), torch.float16, 82).cuda()
+    th = torch.tensor(np.random.default_rng(83).permutation(K), dtype=torch.int32).cuda()
+    lib = esp.load_library()
+    guard = 1 << 20
+    for v in range(esp.num_variants()):
+        try:
+            ref = _bits(ctx.spmm(X, comp, th, variant=v))
+        except esp.EsparseError as e:
+            assert e.code == -2
+            continue
+        need = esp.spmm_workspace(M, N, K, v)
+        assert need <= esp.spmm_workspace(M, N, K)
+        buf = torch.full((need + guard + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+        off = (-buf.data_ptr()) % 256
+        Y = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+        print(f"workspace of variant {esp.variant_name(v)}: {need} bytes", flush=True)
+        rc = lib.esparse_spmm(ctx._h, X.data_ptr(), M, comp.native.data_ptr(), th.data_ptr(), N, K, 0, 2, 4, Y.data_ptr(),
+                              buf.data_ptr() + off, need, v)
+        assert rc == 0, (esp.variant_name(v), lib.esparse_last_error(ctx._h).decode())
+        torch.cuda.synchronize()
+        assert (_bits(Y) == ref).all(), esp.variant_name(v)
+        assert bool((buf[off + need:] == 0xA5).all()), esp.variant_name(v)
+        rc = lib.esparse_spmm(ctx._h, X.data_ptr(), M, comp.native.data_ptr(), th.data_ptr(), N, K, 0, 2, 4, Y.data_ptr(),
+                              buf.data_ptr() + off, need - 256, v)
+        assert rc == -7
+
+
 def test_tune_picks_a_variant_and_persists(esp, ctx, tmp_path):
     best, ms = ctx.tune(16, 512, 1024, esp.F16, sparse=True)
     assert 0 <= best < esp.num_variants() and ms > 0

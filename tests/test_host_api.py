@@ -38,6 +38,20 @@ def test_size_queries_closed_form():
     assert (vb + mb) / (2 * 4096 * 4096) == 0.5625
     assert esp.dense_packed_size(24, 320) == 32 * 512 * 2
     assert esp.spmm_workspace(16, 512, 512) >= 16 * 512 * 2
+    # the size for a named variant never exceeds the size that serves every variant, covers the staged activations,
+    # and only variants that split K over workgroups ask for fp32 partial tiles
+    for M, N, K in [(1, 4096, 4096), (33, 80, 2048), (128, 22016, 8192), (2048, 13824, 5120)]:
+        every = esp.spmm_workspace(M, N, K)
+        assert every == esp.spmm_workspace(M, N, K, -1)
+        Mp = -(-M // 16) * 16
+        for v in range(esp.num_variants()):
+            one = esp.spmm_workspace(M, N, K, v)
+            assert Mp * K * 2 <= one <= every, esp.variant_name(v)
+            splits = "splitk" in esp.variant_name(v) or "stream" in esp.variant_name(v) or "_k" in esp.variant_name(v)
+            if not splits:
+                assert one < Mp * K * 2 * 2 + 4096, esp.variant_name(v)
+    with pytest.raises(esp.EsparseError):
+        esp.spmm_workspace(16, 512, 512, esp.num_variants())
     with pytest.raises(esp.EsparseError):
         esp.compressed_size(8, 8, 1, 4)
 
