@@ -721,12 +721,14 @@ template <int SPARSE, int TR, int TC, int NWC>
 struct TileState {
   static constexpr int NW = 2 * NWC;                        // waves: 2 along the rows x NWC along the tokens
   static constexpr int NT = 64 * NW;                        // threads
-  static constexpr int BCOPIES = (NWC * TC * 128) / NT;     // 16-byte units of activations per lane and stage
+  static constexpr bool HALF = SPARSE == 3;                 // dense, 32-channel stages (one half step per stage)
+  static constexpr int BSTEP = HALF ? 64 : 128;             // 16-byte units of activations per token tile and stage
+  static constexpr int BCOPIES = (NWC * TC * BSTEP) / NT;   // ... per lane and stage
   static constexpr int RTM = 2 * TR;                        // row tiles of 16 in the macro tile
   static constexpr int AUNITS = RTM * (SPARSE ? 64 : 128);  // 16-byte units of weights per stage
   static constexpr int ACOPIES = (AUNITS + NT - 1) / NT;    // ... per lane; when the chunks do not divide among the waves the
   static constexpr int ASLOTS = ACOPIES * NT;               //     last copies fetch a row tile past the macro tile into spare slots
-  static_assert((NWC * TC * 128) % NT == 0, "every wave copies whole 64-unit chunks");
+  static_assert((NWC * TC * BSTEP) % NT == 0, "every wave copies whole 64-unit chunks");
   floatx4_t acc[TR][TC];
   const uint4* a_src[ACOPIES];  // wave-uniform global bases of this wave's DMA copies
   const uint4* x_src[BCOPIES];
@@ -741,8 +743,12 @@ template <int SPARSE, int TR, int TC, int NWC>
 __device__ __forceinline__ void tile_prefetch_b(TileState<SPARSE, TR, TC, NWC>& st, uint4* sb, unsigned kn) {
   using State = TileState<SPARSE, TR, TC, NWC>;
 #pragma unroll
-  for (int p = 0; p < State::BCOPIES; p++)
-    global_to_lds_16(st.x_src[p] + (kn * 128u + st.x_lane), sb + State::NT * p + st.wave * 64);
+  for (int p = 0; p < State::BCOPIES; p++) {
+    if (State::HALF)  // chunk q = NW p + w: half step kn of token tile q
+      global_to_lds_16(st.x_src[p] + (kn * 64u + st.lane), sb + State::NT * p + st.wave * 64);
+    else
+      global_to_lds_16(st.x_src[p] + (kn * 128u + st.x_lane), sb + State::NT * p + st.wave * 64);
+  }
 }
 
 template <int SPARSE, int TR, int TC, int NWC>
@@ -750,11 +756,12 @@ __device__ __forceinline__ void tile_prefetch_a(TileState<SPARSE, TR, TC, NWC>& 
   using State = TileState<SPARSE, TR, TC, NWC>;
 #pragma unroll
   for (int p = 0; p < State::ACOPIES; p++) {
-    // chunk q = NW p + w of 64 units.  sparse: row tile q; dense: row tile q / 2, half q % 2 (NW is even: half w % 2)
+    // chunk q = NW p + w of 64 units.  sparse and dense half-step stages: row tile q; dense: row tile q / 2, half q % 2
+    // (NW is even: half w % 2)
     const unsigned off = SPARSE ? kn * 64u + st.lane : kn * 128u + (st.wave & 1u) * 64u + st.lane;
     global_to_lds_16(st.a_src[p] + off, sa + State::NT * p + st.wave * 64);
     // the lane's index word holding stage kn: 8 bytes per lane and group of 4 stages, word (kn % 4) / 2
-    if (SPARSE)
+    if (SPARSE == 1)
       global_to_lds_4(st.m_src[p] + ((kn >> 2) * 128u + st.lane * 2u + ((kn >> 1) & 1u)), sm + State::NT * p + st.wave * 64);
   }
 }
@@ -773,7 +780,7 @@ __device__ __forceinline__ void tile_load_a(TileState<SPARSE, TR, TC, NWC>& st, 
   for (int i = 0; i < TR; i++) {
     if (SPARSE) {
       r.a[i] = sa[(st.wr * TR + i) * 64 + st.lane];
-      r.m[i] = sm[(st.wr * TR + i) * 64 + st.lane];
+      if (SPARSE == 1) r.m[i] = sm[(st.wr * TR + i) * 64 + st.lane];
     } else {
       r.a[2 * i] = sa[(st.wr * TR + i) * 128 + st.lane];
       r.a[2 * i + 1] = sa[(st.wr * TR + i) * 128 + 64 + st.lane];
@@ -794,29 +801,33 @@ struct TileB {
 template <int DT, int SPARSE, int TR, int TC, int NWC, int J0, int J1, bool NEXT, int D, int OFF>
 __device__ __forceinline__ void tile_multiply(TileState<SPARSE, TR, TC, NWC>& st, const TileRegs<SPARSE, TR>& r, TileB (&bq)[D],
                                               const uint4* sb, const uint4* sb_next, unsigned k) {
+  using State = TileState<SPARSE, TR, TC, NWC>;
+  constexpr int BS = State::BSTEP;
   int idx[TR];
-  if (SPARSE) {
+  if (SPARSE == 1) {
     const unsigned sh = (k & 1u) * 16u;  // the word holds the index halves of an even and an odd stage
 #pragma unroll
     for (int i = 0; i < TR; i++) idx[i] = (int)(r.m[i] >> sh);
   }
-  const uint4* b = sb + (st.wc * TC) * 128 + st.lane;
-  const uint4* bn = sb_next + (st.wc * TC) * 128 + st.lane;
+  const uint4* b = sb + (st.wc * TC) * BS + st.lane;
+  const uint4* bn = sb_next + (st.wc * TC) * BS + st.lane;
 #pragma unroll
   for (int j = J0; j < J1; j++) {
     const TileB cur = bq[(j + OFF) % D];
     TileB nx = cur;
     if (j + D < TC) {
-      nx.b0 = b[(j + D) * 128];
-      nx.b1 = b[(j + D) * 128 + 64];
+      nx.b0 = b[(j + D) * BS];
+      if (!State::HALF) nx.b1 = b[(j + D) * BS + 64];
     } else if (NEXT) {
-      nx.b0 = bn[(j + D - TC) * 128];
-      nx.b1 = bn[(j + D - TC) * 128 + 64];
+      nx.b0 = bn[(j + D - TC) * BS];
+      if (!State::HALF) nx.b1 = bn[(j + D - TC) * BS + 64];
     }
 #pragma unroll
     for (int i = 0; i < TR; i++) {
-      if (SPARSE) {
+      if (SPARSE == 1) {
         st.acc[i][j] = smfmac16<DT, 0>(r.a[i], cur.b0, cur.b1, st.acc[i][j], idx[i]);
+      } else if (State::HALF) {
+        st.acc[i][j] = mfma16<DT>(r.a[i], cur.b0, st.acc[i][j]);
       } else {
         st.acc[i][j] = mfma16<DT>(r.a[2 * i], cur.b0, st.acc[i][j]);
         st.acc[i][j] = mfma16<DT>(r.a[2 * i + 1], cur.b1, st.acc[i][j]);
@@ -859,12 +870,13 @@ __device__ __forceinline__ void tile_stage(TileState<SPARSE, TR, TC, NWC>& st, c
                                            const uint4* a_nxt, const uint32_t* m_nxt, uint4* b_pre, uint4* a_pre, uint32_t* m_pre,
                                            unsigned k) {
   using State = TileState<SPARSE, TR, TC, NWC>;
-  constexpr int DMA = State::BCOPIES + (SPARSE ? 2 : 1) * State::ACOPIES;
+  constexpr int DMA = State::BCOPIES + (SPARSE == 1 ? 2 : 1) * State::ACOPIES;
+  constexpr int BR = State::HALF ? 1 : 2;                    // LDS reads per B operand
   constexpr bool STRADDLE = TC >= 4;
   static_assert(D == 1 || (STRADDLE && D < TC), "deeper operand streams exist for the straddling schedule only");
   constexpr int TH = STRADDLE ? TC - D : TC;                 // token tiles multiplied ahead of the barrier
   constexpr int DPJ = (DMA + TH - 1) / TH;                   // DMA operations issued per token tile
-  constexpr int AREADS = SPARSE ? 2 * TR : 2 * TR;           // LDS reads of tile_load_a
+  constexpr int AREADS = State::HALF ? TR : 2 * TR;          // LDS reads of tile_load_a
   constexpr int APJ = (AREADS + TH - 1) / TH;
   constexpr int MM = SPARSE ? TR : 2 * TR;                   // matrix instructions per token tile
   const unsigned last = st.k1 - 1;                           // past the end: reload the last stage (never used)
@@ -877,7 +889,7 @@ __device__ __forceinline__ void tile_stage(TileState<SPARSE, TR, TC, NWC>& st, c
   // (bandwidth-limited) vector-memory issue while the matrix pipe runs dry.
 #pragma unroll
   for (int j = 0; j < TH; j++) {
-    if (j + D < TC) sched_group<0x100, 2>();
+    if (j + D < TC) sched_group<0x100, BR>();
     sched_group<0x008, MM>();
     sched_group<0x010, DPJ>();
     sched_group<0x100, APJ>();
@@ -889,14 +901,14 @@ __device__ __forceinline__ void tile_stage(TileState<SPARSE, TR, TC, NWC>& st, c
     tile_multiply<DT, SPARSE, TR, TC, NWC, TH, TC, true, D, OFF>(st, cur, bq, b_cur, b_nxt, k);
 #pragma unroll
     for (int j = TH; j < TC; j++) {
-      sched_group<0x100, 2>();
+      sched_group<0x100, BR>();
       sched_group<0x008, MM>();
     }
     sched_fence();
   } else {
-    const uint4* bn = b_nxt + (st.wc * TC) * 128 + st.lane;  // D == 1 here
+    const uint4* bn = b_nxt + (st.wc * TC) * State::BSTEP + st.lane;  // D == 1 here
     bq[0].b0 = bn[0];
-    bq[0].b1 = bn[64];
+    if (!State::HALF) bq[0].b1 = bn[64];
   }
 }
 
@@ -917,6 +929,7 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
   st.wr = st.wave / NWC;
   st.wc = st.wave % NWC;
   const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
+  const long long nst = State::HALF ? 2 * nks : nks;  // stages of the K loop
   // XCD-aware numbering: XCD x (= blockIdx % 8) works through items [x * per, (x + 1) * per); an item is
   // a macro tile and one of the nsplit ranges of K stages (the split varies fastest)
   const long long n_items = n_tiles * nsplit;
@@ -926,7 +939,7 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
   const long long tile = item / nsplit;
   const int split = (int)(item % nsplit);
   st.k0 = (unsigned)((long long)split * sps);
-  st.k1 = (unsigned)(((long long)(split + 1) * sps < nks) ? (long long)(split + 1) * sps : nks);
+  st.k1 = (unsigned)(((long long)(split + 1) * sps < nst) ? (long long)(split + 1) * sps : nst);
   const long long rb = tile / ntb, tb = tile % ntb;
   const long long rt_macro = rb * RTM;  // first row tile of the macro tile
   const long long tt_base = tb * NTT;   // first token tile of the macro tile
@@ -934,12 +947,13 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
   for (int p = 0; p < State::ACOPIES; p++) {
     const long long rtl = SPARSE ? State::NW * p + st.wave : (State::NW / 2) * p + (st.wave >> 1);  // row tile this wave copies
     const long long rt = (rt_macro + rtl < nrt) ? rt_macro + rtl : nrt - 1;
-    st.a_src[p] = A + (SPARSE ? rt * nks : rt * (2 * nks)) * 64;
+    st.a_src[p] = A + (SPARSE == 1 ? rt * nks : rt * (2 * nks)) * 64;
     st.m_src[p] = reinterpret_cast<const uint32_t*>(meta16) + rt * (nks / 4) * 128;
   }
 #pragma unroll
   for (int p = 0; p < State::BCOPIES; p++) {
-    const long long ttl = (State::NW / 2) * p + (st.wave >> 1);  // token tile (within the macro tile) of this wave's p-th copy
+    // token tile (within the macro tile) of this wave's p-th copy
+    const long long ttl = State::HALF ? State::NW * p + st.wave : (State::NW / 2) * p + (st.wave >> 1);
     const long long tt = (tt_base + ttl < ntt) ? tt_base + ttl : ntt - 1;
     st.x_src[p] = Xf + tt * (2 * nks) * 64;
   }
@@ -966,8 +980,8 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
   TileB bq[D];       // the B operands of the coming stage's first D token tiles
 #pragma unroll
   for (int d = 0; d < D; d++) {
-    bq[d].b0 = sb0[(st.wc * TC + d) * 128 + st.lane];
-    bq[d].b1 = sb0[(st.wc * TC + d) * 128 + 64 + st.lane];
+    bq[d].b0 = sb0[(st.wc * TC + d) * State::BSTEP + st.lane];
+    if (!State::HALF) bq[d].b1 = sb0[(st.wc * TC + d) * State::BSTEP + 64 + st.lane];
   }
   // the register set a stage finds its first operand in moves by TC % D from stage to stage and is back after three
   constexpr int O1 = TC % D, O2 = (2 * TC) % D;
@@ -993,7 +1007,7 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
     constexpr int CHT = TC >= 2 ? 2 : 1;                   // token tiles per pass
     constexpr unsigned ROWB = TR * 32 + 16;                // bytes per token in the slice (padded: the 16 tokens of a
     constexpr unsigned SLICE = CHT * 16 * ROWB;            //   tile start in different banks)
-    constexpr unsigned ABYTES = State::ASLOTS * 16, BBYTES = NTT * 128 * 16;
+    constexpr unsigned ABYTES = State::ASLOTS * 16, BBYTES = NTT * State::BSTEP * 16;
     constexpr int FA = ABYTES / SLICE, FB = BBYTES / SLICE;  // slices per weight / activation buffer
     constexpr int SLOTS = 3 * (FA + FB) < State::NW ? 3 * (FA + FB) : State::NW;
     static_assert(SLOTS >= 1, "no operand buffer holds an output slice");
@@ -1062,7 +1076,9 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
   }
 }
 
-// sparse: TR = 8 (macro tile of 16 row tiles) or 4; dense: half of that (operands twice as wide).
+// sparse: TR = 8 (macro tile of 16 row tiles) or 4; dense: half of that (operands twice as wide), or (SPARSE = 3) the
+// sparse shape with stages of 32 channels: 256 x 256 outputs per workgroup for 32 KiB of operands per stage - half the
+// operand bytes per multiply of the 128-row dense form, which is what the matrix pipe waits for.
 template <int DT, int SPARSE, int TR, int TC, int NWC, int D = 1>
 __global__ void __launch_bounds__(128 * NWC) k_mm_tile(const uint4* __restrict__ A, const uint16_t* __restrict__ meta16,
                                                         const uint4* __restrict__ Xf, uint16_t* __restrict__ Y,
@@ -1073,12 +1089,13 @@ __global__ void __launch_bounds__(128 * NWC) k_mm_tile(const uint4* __restrict__
   __shared__ uint4 s_a0[ASLOTS];  // one stage of weights each
   __shared__ uint4 s_a1[ASLOTS];
   __shared__ uint4 s_a2[ASLOTS];
-  __shared__ uint4 s_b0[NWC * TC * 128];  // one stage of activations each: [NWC TC token tiles][2 half steps][64 lanes]
-  __shared__ uint4 s_b1[NWC * TC * 128];
-  __shared__ uint4 s_b2[NWC * TC * 128];
-  __shared__ uint32_t s_m0[SPARSE ? ASLOTS : 1];  // one stage pair of index words each: [row tiles][64 lanes]
-  __shared__ uint32_t s_m1[SPARSE ? ASLOTS : 1];
-  __shared__ uint32_t s_m2[SPARSE ? ASLOTS : 1];
+  constexpr int BSTEP = TileState<SPARSE, TR, TC, NWC>::BSTEP;
+  __shared__ uint4 s_b0[NWC * TC * BSTEP];  // one stage of activations each: [NWC TC token tiles][2 half steps (or 1)][64 lanes]
+  __shared__ uint4 s_b1[NWC * TC * BSTEP];
+  __shared__ uint4 s_b2[NWC * TC * BSTEP];
+  __shared__ uint32_t s_m0[SPARSE == 1 ? ASLOTS : 1];  // one stage pair of index words each: [row tiles][64 lanes]
+  __shared__ uint32_t s_m1[SPARSE == 1 ? ASLOTS : 1];
+  __shared__ uint32_t s_m2[SPARSE == 1 ? ASLOTS : 1];
   tile_pipeline<DT, SPARSE, TR, TC, NWC, D>(s_a0, s_a1, s_a2, s_b0, s_b1, s_b2, s_m0, s_m1, s_m2, A, meta16, Xf, Y, partial, M, N, Mp,
                                          Np, Kp, n_tiles, ntb, nsplit, sps);
 }
@@ -1588,6 +1605,7 @@ struct Variant {
   int quads;       // ksplit kind: 1 = a wave takes four consecutive steps with one index load (2:4, at most 16 tokens)
   int x32;         // tile kind: 1 = the 32x32x32 form of the sparse instruction and the epilogue through LDS (2:4 only)
   int depth;       // tile kind: token tiles the activation operands are read ahead (0 = 1)
+  int half;        // tile kind: 1 = dense only, stages of 32 channels and the macro tile of the sparse form
 };
 static const Variant kVariants[] = {
     {"wave_r2_t1_splitk", KIND_WAVE, 2, 1, 1, 0},
@@ -1642,6 +1660,12 @@ static const Variant kVariants[] = {
     // the 4-wave 256 x 256 tile (one wave per SIMD, 256 accumulators each: fewer LDS reads per multiply) with the
     // activation operands read three token tiles ahead, so that the wave's own multiplies cover the LDS latency
     {"tile_t256_d3", KIND_TILE, 8, 8, 0, 2, 0, 0, 3},
+    // dense only: 256 rows x 256 (128) tokens per workgroup in stages of 32 channels - the operand bytes per multiply of
+    // the sparse macro tile, half those of the 128-row dense forms above
+    {"tile_w8_t256_h", KIND_TILE, 8, 4, 0, 4, 0, 0, 0, 1},
+    {"tile_w8_t128_h", KIND_TILE, 8, 2, 0, 4, 0, 0, 0, 1},
+    {"tile_w8_t256_h_splitk", KIND_TILE, 8, 4, 1, 4, 0, 0, 0, 1},  // ... with K split over workgroups (M <= 512)
+    {"tile_w8_t128_h_splitk", KIND_TILE, 8, 2, 1, 4, 0, 0, 0, 1},
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -1669,6 +1693,7 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
   }
   if (var.kind == KIND_TILE && M < 64) return false;
   if (var.x32 && sparse != 1) return false;
+  if (var.half && sparse != 0) return false;
   if (var.kind == KIND_STREAM && M > 128) return false;
   return true;
 }
@@ -1707,7 +1732,11 @@ int esp_default_variant(long long M, long long N, long long K, int sparse) {
   // 8-wave tile kernels: the largest macro tile that still gives half of the 256 CUs a tile
   const long long rows = sparse ? 256 : 128;
   const long long nrb = (N + rows - 1) / rows;
-  if (nrb * ((M + 255) / 256) >= 128) return sparse == 1 ? variant_index("tile32_w8_t256") : 12;  // tile_w8_t256 (dense)
+  if (nrb * ((M + 255) / 256) >= 128) {
+    if (sparse == 1) return variant_index("tile32_w8_t256");
+    // dense: the 256-row form with 32-channel stages once its macro tiles alone give half of the CUs a tile
+    return ((N + 255) / 256) * ((M + 255) / 256) >= 128 ? variant_index("tile_w8_t256_h") : 12;  // else tile_w8_t256
+  }
   if (nrb * ((M + 127) / 128) >= 128) return 13;  // tile_w8_t128
   return 14;                                       // tile_w8_r128_t128
 }
@@ -1838,8 +1867,8 @@ template <int DT, int SPARSE>
 static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const uint4* A, const uint16_t* meta16, const uint4* Xf,
                        uint16_t* Y, float* partial, long long M, long long N, long long Mp, long long Np, long long Kp) {
   // the dense operand is twice as wide: half the row tiles per wave
-  const long long rtm = SPARSE ? 2 * v.rt : 2 * (v.rt / 2);  // row tiles per macro tile
-  const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
+  const long long rtm = (SPARSE || v.half) ? 2 * v.rt : 2 * (v.rt / 2);  // row tiles per macro tile
+  const long long nrt = Np / 16, ntt = Mp / 16, nks = (v.half ? 2 : 1) * (Kp / 64);  // nks: stages of the K loop
   const long long cols = (long long)v.nw * v.tt;  // token tiles per macro tile
   const long long nrb = (nrt + rtm - 1) / rtm, ntb = (ntt + cols - 1) / cols;
   const long long n_tiles = nrb * ntb;
@@ -1856,7 +1885,14 @@ static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const
   }
   const long long per = (n_tiles * nsplit + 7) / 8;
   dim3 grid((unsigned)(per * 8));
-  if (v.x32) {
+  if (v.half) {
+    if (SPARSE != 0) return esp_fail(ctx, ESPARSE_EINVAL, "the half-step tile kernel multiplies dense weights only");
+    if (v.tt == 4)
+      hipLaunchKernelGGL((k_mm_tile<DT, 3, 8, 4, 4>), grid, dim3(512), 0, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, n_tiles, ntb, nsplit, (int)sps);
+    else
+      hipLaunchKernelGGL((k_mm_tile<DT, 3, 8, 2, 4>), grid, dim3(512), 0, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, n_tiles, ntb, nsplit, (int)sps);
+    ESP_HIP(ctx, hipGetLastError());
+  } else if (v.x32) {
     if (SPARSE != 1) return esp_fail(ctx, ESPARSE_EINVAL, "the 32x32x32 tile kernel multiplies 2:4 weights only");
     if (v.tt == 4)
       hipLaunchKernelGGL((k_mm_tile32<DT, 2>), grid, dim3(512), 0, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, n_tiles, ntb, nsplit, (int)sps);
