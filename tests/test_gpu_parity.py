@@ -308,6 +308,13 @@ def test_spmm_many_tokens_row_staging(esp, ctx):
     _spmm_case(esp, ctx, 8200, 32, 320, torch.bfloat16, 55)
 
 
+def test_spmm_banded_tile_order(esp, ctx):
+    """More than 8 token blocks per row block: the tile kernels number their macro tiles in bands of 8 row blocks
+    (token blocks outermost within a band).  11 row blocks of 256 (22 of 128) leave a ragged last band; 2400 tokens are
+    10 blocks of 256 (19 of 128), the last one ragged."""
+    _spmm_case(esp, ctx, 2400, 2816, 256, torch.float16, 56)
+
+
 def test_stacked_matrices_share_one_theta(esp, ctx):
     """Matrices that read the same input (q/k/v, gate/up) pruned as one stacked matrix: one theta, one mask;
     the product of the stack is the concatenation of the products of its slices (bitwise: rows are independent)
