@@ -461,6 +461,31 @@ def main():
     for r in per_shape + per_group:
         del r["flops"]
 
+    # what the matrix pipes sustain on this chip with nothing else to do (register-resident operands, no LDS, no memory):
+    # with operands of random signs and mantissas - the case of real data - and with zeros, on which the chip holds a
+    # higher clock.  The roofline objects keep the published peak; these figures say how much of it a kernel could see.
+    matrix_rate = None
+
+    def measured_matrix_rate():
+        nonlocal matrix_rate
+        if matrix_rate is None and not args.counter_probe:
+            dt = dcode
+            matrix_rate = dict(unit="TFLOP/s", instruction="v_smfmac_f32_32x32x32 (2:4), effective flops",
+                               random_operands=round(ctx.matrix_rate(True, dt, True), 1),
+                               zero_operands=round(ctx.matrix_rate(True, dt, False), 1),
+                               dense_random_operands=round(ctx.matrix_rate(False, dt, True), 1),
+                               with_stage_lds_reads=round(ctx.matrix_rate(True, dt, True, 1), 1),
+                               with_stage_lds_reads_dma_wait_barrier=round(ctx.matrix_rate(True, dt, True, 2), 1),
+                               what="8 waves per CU issue the matrix instruction back to back: on operands held in registers "
+                                    "(random / zero / dense), and with what one 64-channel stage of the prefill kernel does beside its "
+                                    "16 multiplies per wave (operand reads out of LDS; + DMA from an L2-resident region, counted wait, barrier)")
+        return matrix_rate
+
+    if roofline["bound"] == "mfma" and measured_matrix_rate():
+        roofline["matrix_rate_measured"] = matrix_rate
+        roofline["frac_of_measured_rate"] = round(roofline["achieved"] / matrix_rate["random_operands"], 4)
+        roofline["frac_of_measured_stage_rate"] = round(roofline["achieved"] / matrix_rate["with_stage_lds_reads_dma_wait_barrier"], 4)
+
     # ------------------------------------------------------------------ the prefill kernel beside the decode headline
     # The default workload is decode-sized (HBM-bound).  So that one run also times the MFMA-bound kernel, the
     # largest product of config 3 (gate/up 13824 x 5120 at M = 2048, fp16) is pruned, compressed, tuned and timed
@@ -512,6 +537,10 @@ def main():
                                 note="dense-equivalent flops 2 M N K against twice the dense 16-bit MFMA peak",
                                 traffic=measured_traffic(pM, pN, pK, 1, esp.variant_name(pv)),
                                 parity_max_row_rel_err=perr, parity_tol=2e-3)
+        if measured_matrix_rate():
+            roofline_prefill["matrix_rate_measured"] = matrix_rate
+            roofline_prefill["frac_of_measured_rate"] = round(pach / matrix_rate["random_operands"], 4)
+            roofline_prefill["frac_of_measured_stage_rate"] = round(pach / matrix_rate["with_stage_lds_reads_dma_wait_barrier"], 4)
         del pmats, pX, pY, pws, pW0, pmask0
         torch.cuda.empty_cache()
 

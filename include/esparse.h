@@ -254,6 +254,21 @@ int esparse_tune_load(esparse_ctx* ctx, const char* path);
 int esparse_output_error(esparse_ctx* ctx, const void* Yref, const void* Y, long long M, long long N,
                          esparse_dtype dtype, double* err_num, double* err_den);
 
+/* ---- Measurement aid: what the matrix pipes sustain on this chip -------------------------------
+ * Not a step of the method: the ceiling its product kernels (Section 4) are compared with, beside the published
+ * peak.  One workgroup of 8 waves per compute unit issues the matrix instruction of the tile kernels back to back for
+ * about 40 ms; *tflops (HOST) receives the rate in effective TFLOP/s: 2 x 32 x 32 x 32 flops per 2:4 instruction
+ * (sparse = 1, v_smfmac_f32_32x32x32), 2 x 32 x 32 x 16 per dense one (sparse = 0, v_mfma_f32_32x32x16), fp16 or bf16.
+ * random_operands = 1: values with random signs and mantissas, the case of real data; 0: zeros, on which the chip holds
+ * a higher clock.  mix = 0: operands held in registers (no LDS, no memory traffic).  mix = 1 / 2 (2:4 on random
+ * operands only, else EUNSUPPORTED): per 16 multiplies - one 64-channel stage of the 8-wave prefill kernel - also that
+ * stage's operand reads out of LDS (1), and the DMA of a coming stage's operands from an L2-resident region of global
+ * memory into LDS with the stage's counted wait and barrier (2): what the kernel's instruction mix reaches when
+ * nothing waits for data.  Synchronises the context's stream; allocates small scratch buffers.
+ * Errors: ESPARSE_EINVAL (null pointer, sparse / random_operands not 0 / 1, mix outside 0..2), ESPARSE_EUNSUPPORTED
+ * (dtype, mix), ESPARSE_ENOMEM, ESPARSE_EHIP. */
+int esparse_matrix_rate(esparse_ctx* ctx, int sparse, esparse_dtype dtype, int random_operands, int mix, double* tflops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -53,6 +53,7 @@ def load_library():
         "esparse_prune": (i32, [vp, vp, ll, vp, ll, ll, i32, P(_Opts), vp, vp, vp, vp, vp]),
         "esparse_prune_with_scores": (i32, [vp, vp, vp, ll, ll, i32, P(_Opts), vp, vp, vp, vp]),
         "esparse_output_error": (i32, [vp, vp, vp, ll, ll, i32, vp, vp]),
+        "esparse_matrix_rate": (i32, [vp, i32, i32, i32, i32, P(C.c_double)]),
         "esparse_spmm_group_workspace": (i32, [i32, ll, ll, ll, P(sz)]),
         "esparse_spmm_group": (i32, [vp, i32, P(vp), ll, P(vp), P(vp), ll, ll, i32, i32, i32, P(vp), vp, sz, i32]),
         "esparse_dense_gemm_group": (i32, [vp, i32, P(vp), ll, P(vp), ll, ll, i32, P(vp), vp, sz, i32]),
@@ -86,6 +87,7 @@ def load_library():
 
 EXPORTED = ["esparse_create", "esparse_destroy", "esparse_set_stream", "esparse_last_error",
             "esparse_version", "esparse_channel_stats", "esparse_prune", "esparse_prune_with_scores", "esparse_output_error",
+            "esparse_matrix_rate",
             "esparse_spmm_group_workspace", "esparse_spmm_group", "esparse_dense_gemm_group",
             "esparse_stage_activations_group", "esparse_spmm_group_staged",
             "esparse_compressed_size", "esparse_compress", "esparse_spmm_workspace", "esparse_spmm", "esparse_spmm_static",
@@ -410,6 +412,15 @@ class Context:
         self._check(self._lib.esparse_output_error(self._h, _ptr(Yref), _ptr(Y), M, N, _dtype_code(Y),
                                                    C.cast(C.byref(num), C.c_void_p), C.cast(C.byref(den), C.c_void_p)))
         return num.value, den.value
+
+    # -- measurement aid ------------------------------------------------------------------------
+    def matrix_rate(self, sparse: bool = True, dtype: int = F16, random_operands: bool = True, mix: int = 0) -> float:
+        """Effective TFLOP/s the matrix pipes sustain: mix 0 = operands held in registers, 1 = + a prefill stage's operand
+        reads out of LDS, 2 = + its DMA, counted wait and barrier (L2-resident source)."""
+        t = C.c_double(0.0)
+        self._sync_stream()
+        self._check(self._lib.esparse_matrix_rate(self._h, int(bool(sparse)), dtype, int(bool(random_operands)), mix, C.byref(t)))
+        return t.value
 
     def tune(self, M: int, N: int, K: int, dtype: int = F16, sparse=True):
         """sparse: False / 0 = dense, True / 1 = 2:4, 2 = 4:8."""

@@ -483,14 +483,12 @@ static int tune_impl(esparse_ctx* ctx, int count, long long M, long long N, long
   ESP_HIP(ctx, hipEventCreate(&events.e[0]));
   ESP_HIP(ctx, hipEventCreate(&events.e[1]));
   const hipEvent_t e0 = events.e[0], e1 = events.e[1];
-  int best = -1;
-  float best_t = 0.f;
   const int reps = 20;
-  for (int v = 0; v < esp_num_variants(); v++) {
-    if (!esp_variant_applicable(v, M, N, K, sparse)) continue;
-    const unsigned char* wbase = reinterpret_cast<const unsigned char*>(w.p);
-    unsigned char* ybase = reinterpret_cast<unsigned char*>(y.p);
-    // launch i reads the weight copies i count, i count + 1, ... (mod ncopies)
+  const unsigned char* wbase = reinterpret_cast<const unsigned char*>(w.p);
+  unsigned char* ybase = reinterpret_cast<unsigned char*>(y.p);
+  // average duration of `reps` launches of variant v after three untimed ones; launch i reads the weight copies
+  // i count, i count + 1, ... (mod ncopies)
+  auto time_variant = [&](int v, float* ms_out) -> int {
     auto launch = [&](int i) {
       const void* Xs[4];
       const void* Ws[4];
@@ -503,24 +501,50 @@ static int tune_impl(esparse_ctx* ctx, int count, long long M, long long N, long
       if (count == 1) return esp_matmul_device(ctx, sparse, Xs[0], M, Ws[0], nullptr, N, K, dtype, Ys[0], ws.p, v, 3);
       return esp_matmul_group_device(ctx, sparse, count, Xs, M, Ws, nullptr, N, K, dtype, Ys, ws.p, v, 3);
     };
+    int r = 0;
     for (int i = 0; i < 3; i++)
-      if ((rc = launch(i))) break;
-    if (rc) break;
+      if ((r = launch(i))) return r;
     (void)hipEventRecord(e0, ctx->stream);
     for (int i = 0; i < reps; i++)
-      if ((rc = launch(i + 3))) break;
+      if ((r = launch(i + 3))) break;
     (void)hipEventRecord(e1, ctx->stream);
-    if (rc) break;
-    if (hipEventSynchronize(e1) != hipSuccess) {
-      rc = esp_fail(ctx, ESPARSE_EHIP, "event synchronize failed while tuning");
-      break;
-    }
+    if (r) return r;
+    if (hipEventSynchronize(e1) != hipSuccess) return esp_fail(ctx, ESPARSE_EHIP, "event synchronize failed while tuning");
     float ms = 0.f;
     (void)hipEventElapsedTime(&ms, e0, e1);
-    ms /= reps;
-    if (best < 0 || ms < best_t) {
-      best = v;
-      best_t = ms;
+    *ms_out = ms / reps;
+    return ESPARSE_OK;
+  };
+  std::vector<std::pair<float, int>> timed;  // (ms, variant)
+  for (int v = 0; v < esp_num_variants() && !rc; v++) {
+    if (!esp_variant_applicable(v, M, N, K, sparse)) continue;
+    float ms = 0.f;
+    if (!(rc = time_variant(v, &ms))) timed.emplace_back(ms, v);
+  }
+  int best = -1;
+  float best_t = 0.f;
+  if (!rc && !timed.empty()) {
+    // The first pass times every variant once, one after the other, while the clocks still move with the load: variants
+    // within a few percent of each other come out in an order that changes from run to run.  The (at most four) variants
+    // within 6 % of the fastest are therefore timed twice more, in alternating order, and ranked by their mean.
+    std::sort(timed.begin(), timed.end());
+    size_t nclose = 1;
+    while (nclose < timed.size() && nclose < 4 && timed[nclose].first <= timed[0].first * 1.06f) nclose++;
+    std::vector<float> sum(nclose);
+    for (size_t i = 0; i < nclose; i++) sum[i] = timed[i].first;
+    if (nclose > 1)
+      for (int round = 0; round < 2 && !rc; round++)
+        for (size_t q = 0; q < nclose && !rc; q++) {
+          const size_t i = round == 0 ? nclose - 1 - q : q;
+          float ms = 0.f;
+          if (!(rc = time_variant(timed[i].second, &ms))) sum[i] += ms;
+        }
+    if (!rc) {
+      size_t pick = 0;
+      for (size_t i = 1; i < nclose; i++)
+        if (sum[i] < sum[pick]) pick = i;
+      best = timed[pick].second;
+      best_t = nclose > 1 ? sum[pick] / 3.f : sum[pick];
     }
   }
   if (rc) return rc;
@@ -554,6 +578,20 @@ int esparse_output_error(esparse_ctx* ctx, const void* Yref, const void* Y, long
   ESP_REQUIRE(ctx, Yref && Y, ESPARSE_EINVAL, "Yref / Y is null");
   ESP_HIP(ctx, hipSetDevice(ctx->device));
   return esp_output_error_device(ctx, Yref, Y, M * N, dtype, err_num, err_den);
+}
+
+int esparse_matrix_rate(esparse_ctx* ctx, int sparse, esparse_dtype dtype, int random_operands, int mix, double* tflops) {
+  if (!ctx) return ESPARSE_EINVAL;
+  int rc = check_dtype(ctx, dtype);
+  if (rc) return rc;
+  ESP_REQUIRE(ctx, tflops != nullptr, ESPARSE_EINVAL, "tflops is null");
+  ESP_REQUIRE(ctx, (sparse == 0 || sparse == 1) && (random_operands == 0 || random_operands == 1) && mix >= 0 && mix <= 2,
+              ESPARSE_EINVAL, "sparse and random_operands are 0 or 1, mix is 0, 1 or 2");
+  ESP_REQUIRE(ctx, mix == 0 || (sparse == 1 && random_operands == 1), ESPARSE_EUNSUPPORTED,
+              "the stage mixes exist for the 2:4 instruction on random operands");
+  *tflops = 0.0;
+  ESP_HIP(ctx, hipSetDevice(ctx->device));
+  return esp_matrix_rate_device(ctx, sparse, dtype, random_operands, mix, tflops);
 }
 
 int esparse_tune_save(const esparse_ctx* ctx, const char* path) {

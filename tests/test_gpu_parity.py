@@ -512,6 +512,23 @@ def test_named_variant_stays_inside_the_workspace_size_reported_for_it(esp, ctx,
         assert rc == -7
 
 
+def test_matrix_rate_is_plausible(esp, ctx):
+    # register-resident operands: below the published peaks (5.0 PFLOP/s effective for 2:4, 2.5 dense; 3 % for the
+    # clock's tolerance), well above what any product kernel reaches, zeros not slower than random data, and the 2:4
+    # instruction about twice the dense one
+    sr = ctx.matrix_rate(True, esp.F16, True)
+    sz = ctx.matrix_rate(True, esp.F16, False)
+    dr = ctx.matrix_rate(False, esp.F16, True)
+    br = ctx.matrix_rate(True, esp.BF16, True)
+    m1 = ctx.matrix_rate(True, esp.F16, True, mix=1)
+    m2 = ctx.matrix_rate(True, esp.F16, True, mix=2)
+    print(f"matrix rate TFLOP/s: 2:4 fp16 random {sr:.0f}, zeros {sz:.0f}, bf16 random {br:.0f}, dense fp16 random {dr:.0f}; "
+          f"with a stage's LDS reads {m1:.0f}, and its DMA, wait and barrier {m2:.0f}", flush=True)
+    assert 1500 < sr <= 5150 and 1500 < br <= 5150 and sr * 0.95 <= sz <= 5150
+    assert 750 < dr <= 2575 and 1.6 < sr / dr < 2.4
+    assert 1000 < m2 <= m1 * 1.05 and m1 <= sr * 1.05
+
+
 def test_tune_picks_a_variant_and_persists(esp, ctx, tmp_path):
     best, ms = ctx.tune(16, 512, 1024, esp.F16, sparse=True)
     assert 0 <= best < esp.num_variants() and ms > 0

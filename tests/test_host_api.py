@@ -94,6 +94,12 @@ def test_argument_errors_need_no_gpu():
     assert lib.esparse_output_error(None, None, None, 4, 4, 0, None, None) == -1        # null context
     assert lib.esparse_tune_group(ctx._h, 0, 16, 512, 512, 0, 1, None, None) == -1       # count outside 1..4
     assert lib.esparse_tune_group(ctx._h, 5, 16, 512, 512, 0, 1, None, None) == -1
+    assert lib.esparse_matrix_rate(ctx._h, 1, 0, 1, 0, None) == -1                       # null result pointer
+    rate = C.c_double(0.0)
+    assert lib.esparse_matrix_rate(ctx._h, 2, 0, 1, 0, C.byref(rate)) == -1              # sparse is 0 or 1
+    assert lib.esparse_matrix_rate(ctx._h, 1, 7, 1, 0, C.byref(rate)) == -2              # no such dtype
+    assert lib.esparse_matrix_rate(ctx._h, 1, 0, 1, 3, C.byref(rate)) == -1              # mix is 0, 1 or 2
+    assert lib.esparse_matrix_rate(ctx._h, 0, 0, 1, 2, C.byref(rate)) == -2              # the stage mixes are 2:4 only
 
 
 def test_tune_table_text_roundtrip(tmp_path):
