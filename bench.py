@@ -481,6 +481,13 @@ def main():
                                     "16 multiplies per wave (operand reads out of LDS; + DMA from an L2-resident region, counted wait, barrier)")
         return matrix_rate
 
+    if roofline["bound"] == "hbm" and not args.counter_probe:
+        # what the memory system gives a plain read of the launch's bytes, cold, in one launch: the ceiling for its size
+        pr = ctx.read_rate(int(roofline["alg_bytes_per_launch"]))
+        roofline["plain_read_measured"] = dict(value=round(pr, 1), unit="GB/s", bytes_per_launch=int(roofline["alg_bytes_per_launch"]),
+                                               what="streaming read of the same number of bytes per launch, 16 bytes per lane, "
+                                                    "launches walking through more than the last-level cache holds")
+        roofline["frac_of_plain_read"] = round(roofline["achieved"] / pr, 4)
     if roofline["bound"] == "mfma" and measured_matrix_rate():
         roofline["matrix_rate_measured"] = matrix_rate
         roofline["frac_of_measured_rate"] = round(roofline["achieved"] / matrix_rate["random_operands"], 4)

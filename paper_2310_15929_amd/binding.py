@@ -54,6 +54,7 @@ def load_library():
         "esparse_prune_with_scores": (i32, [vp, vp, vp, ll, ll, i32, P(_Opts), vp, vp, vp, vp]),
         "esparse_output_error": (i32, [vp, vp, vp, ll, ll, i32, vp, vp]),
         "esparse_matrix_rate": (i32, [vp, i32, i32, i32, i32, P(C.c_double)]),
+        "esparse_read_rate": (i32, [vp, sz, P(C.c_double)]),
         "esparse_spmm_group_workspace": (i32, [i32, ll, ll, ll, P(sz)]),
         "esparse_spmm_group": (i32, [vp, i32, P(vp), ll, P(vp), P(vp), ll, ll, i32, i32, i32, P(vp), vp, sz, i32]),
         "esparse_dense_gemm_group": (i32, [vp, i32, P(vp), ll, P(vp), ll, ll, i32, P(vp), vp, sz, i32]),
@@ -87,7 +88,7 @@ def load_library():
 
 EXPORTED = ["esparse_create", "esparse_destroy", "esparse_set_stream", "esparse_last_error",
             "esparse_version", "esparse_channel_stats", "esparse_prune", "esparse_prune_with_scores", "esparse_output_error",
-            "esparse_matrix_rate",
+            "esparse_matrix_rate", "esparse_read_rate",
             "esparse_spmm_group_workspace", "esparse_spmm_group", "esparse_dense_gemm_group",
             "esparse_stage_activations_group", "esparse_spmm_group_staged",
             "esparse_compressed_size", "esparse_compress", "esparse_spmm_workspace", "esparse_spmm", "esparse_spmm_static",
@@ -420,6 +421,13 @@ class Context:
         t = C.c_double(0.0)
         self._sync_stream()
         self._check(self._lib.esparse_matrix_rate(self._h, int(bool(sparse)), dtype, int(bool(random_operands)), mix, C.byref(t)))
+        return t.value
+
+    def read_rate(self, nbytes: int) -> float:
+        """GB/s of a plain streaming read of nbytes per launch, cold (the launches walk through more than the caches hold)."""
+        t = C.c_double(0.0)
+        self._sync_stream()
+        self._check(self._lib.esparse_read_rate(self._h, int(nbytes), C.byref(t)))
         return t.value
 
     def tune(self, M: int, N: int, K: int, dtype: int = F16, sparse=True):

@@ -594,6 +594,15 @@ int esparse_matrix_rate(esparse_ctx* ctx, int sparse, esparse_dtype dtype, int r
   return esp_matrix_rate_device(ctx, sparse, dtype, random_operands, mix, tflops);
 }
 
+int esparse_read_rate(esparse_ctx* ctx, size_t bytes, double* gbs) {
+  if (!ctx) return ESPARSE_EINVAL;
+  ESP_REQUIRE(ctx, gbs != nullptr, ESPARSE_EINVAL, "gbs is null");
+  ESP_REQUIRE(ctx, bytes >= 4096 && bytes <= ((size_t)8 << 30), ESPARSE_EINVAL, "bytes outside 4 KiB .. 8 GiB");
+  *gbs = 0.0;
+  ESP_HIP(ctx, hipSetDevice(ctx->device));
+  return esp_read_rate_device(ctx, bytes, gbs);
+}
+
 int esparse_tune_save(const esparse_ctx* ctx, const char* path) {
   if (!ctx || !path) return ESPARSE_EINVAL;
   FILE* f = fopen(path, "w");

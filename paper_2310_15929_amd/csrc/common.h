@@ -104,6 +104,7 @@ int esp_fill_pattern_device(esparse_ctx* ctx, void* dst, size_t bytes);
 int esp_output_error_device(esparse_ctx* ctx, const void* Yref, const void* Y, long long count, int dtype, double* num_out,
                             double* den_out);
 int esp_matrix_rate_device(esparse_ctx* ctx, int sparse, int dtype, int random_operands, int mix, double* tflops);
+int esp_read_rate_device(esparse_ctx* ctx, size_t bytes, double* gbs);
 
 int esp_num_variants();
 const char* esp_variant_name(int v);

@@ -17,9 +17,13 @@
 // mix 0 is not.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "common.h"
 
 namespace {
+
+typedef unsigned int esp_read4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint32_t rate_hash(uint32_t x) {
   x ^= x >> 16;
@@ -183,6 +187,27 @@ __global__ void __launch_bounds__(512) k_stage_rate(int trips, const uint4* __re
   sink[id] = s;
 }
 
+
+// plain streaming read: a workgroup reads a contiguous share of the buffer, 16 bytes per lane and load, four loads under
+// way per thread; the values are folded into one word per thread so that the loads cannot be dropped
+__global__ void __launch_bounds__(256) k_read_rate(const uint4* __restrict__ src, size_t units_per_wg, uint32_t* __restrict__ sink) {
+  const uint4* p = src + (size_t)blockIdx.x * units_per_wg;
+  uint32_t f = 0u;
+  size_t u = threadIdx.x;
+  for (; u + 768 < units_per_wg; u += 1024) {
+    const esp_read4 a = __builtin_nontemporal_load(reinterpret_cast<const esp_read4*>(p + u));
+    const esp_read4 b = __builtin_nontemporal_load(reinterpret_cast<const esp_read4*>(p + u + 256));
+    const esp_read4 c = __builtin_nontemporal_load(reinterpret_cast<const esp_read4*>(p + u + 512));
+    const esp_read4 d = __builtin_nontemporal_load(reinterpret_cast<const esp_read4*>(p + u + 768));
+    f ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  }
+  for (; u < units_per_wg; u += 256) {
+    const esp_read4 a = __builtin_nontemporal_load(reinterpret_cast<const esp_read4*>(p + u));
+    f ^= a.x ^ a.y ^ a.z ^ a.w;
+  }
+  sink[blockIdx.x * 256 + threadIdx.x] = f;
+}
+
 }  // namespace
 
 int esp_matrix_rate_device(esparse_ctx* ctx, int sparse, int dtype, int random_operands, int mix, double* tflops) {
@@ -240,5 +265,41 @@ int esp_matrix_rate_device(esparse_ctx* ctx, int sparse, int dtype, int random_o
   const double per_instr = sparse ? 65536.0 : 32768.0;
   const double flops = 3.0 * (double)cus * 8.0 * (double)trips * 16.0 * per_instr;
   *tflops = ms > 0.f ? flops / ((double)ms * 1e-3) / 1e12 : 0.0;
+  return ESPARSE_OK;
+}
+
+// What the memory system gives a plain read of `bytes` bytes in one launch, cold: the launches walk through a buffer
+// larger than the last-level cache, so every launch reads from HBM.  The decode kernels read 1.125 N K bytes per launch
+// and can be no faster than this for their size (launch, ramp-up and drain are a fixed few microseconds).
+int esp_read_rate_device(esparse_ctx* ctx, size_t bytes, double* gbs) {
+  const size_t wgs = std::min<size_t>(2048, std::max<size_t>(1, bytes / 16384));  // at least 16 KiB per workgroup
+  const size_t units_per_wg = (bytes / 16 + wgs - 1) / wgs;
+  const size_t span = wgs * units_per_wg * 16;                                    // bytes one launch reads
+  const size_t ncopies = std::max<size_t>(2, ((size_t)640 << 20) / span + 1);
+  DevBuf buf, sink;
+  if (buf.alloc(span * ncopies) != hipSuccess || sink.alloc(wgs * 256 * 4) != hipSuccess)
+    return esp_fail(ctx, ESPARSE_ENOMEM, "scratch allocation failed");
+  int rc = esp_fill_pattern_device(ctx, buf.p, span * ncopies);
+  if (rc) return rc;
+  hipEvent_t e0, e1;
+  ESP_HIP(ctx, hipEventCreate(&e0));
+  ESP_HIP(ctx, hipEventCreate(&e1));
+  const int reps = 24;
+  auto launch = [&](int i) {
+    const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(buf.p) + (size_t)(i % ncopies) * span);
+    hipLaunchKernelGGL(k_read_rate, dim3((unsigned)wgs), dim3(256), 0, ctx->stream, src, units_per_wg, sink.as<uint32_t>());
+  };
+  for (int i = 0; i < 4; i++) launch(i);
+  hipError_t e = hipEventRecord(e0, ctx->stream);
+  for (int i = 0; i < reps && e == hipSuccess; i++) launch(i + 4);
+  if (e == hipSuccess) e = hipGetLastError();
+  if (e == hipSuccess) e = hipEventRecord(e1, ctx->stream);
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  ESP_HIP(ctx, e);
+  *gbs = ms > 0.f ? (double)span * reps / ((double)ms * 1e-3) / 1e9 : 0.0;
   return ESPARSE_OK;
 }

@@ -529,6 +529,13 @@ def test_matrix_rate_is_plausible(esp, ctx):
     assert 1000 < m2 <= m1 * 1.05 and m1 <= sr * 1.05
 
 
+def test_read_rate_is_plausible(esp, ctx):
+    # cold plain reads: below the published 8 TB/s, rising with the bytes per launch (launch, ramp-up and drain are fixed)
+    small, mid, big = ctx.read_rate(16 << 20), ctx.read_rate(100 << 20), ctx.read_rate(1 << 30)
+    print(f"plain read GB/s: 16 MiB {small:.0f}, 100 MiB {mid:.0f}, 1 GiB {big:.0f}", flush=True)
+    assert 1000 < small < mid < big * 1.05 and big < 8000
+
+
 def test_tune_picks_a_variant_and_persists(esp, ctx, tmp_path):
     best, ms = ctx.tune(16, 512, 1024, esp.F16, sparse=True)
     assert 0 <= best < esp.num_variants() and ms > 0

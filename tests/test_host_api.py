@@ -100,6 +100,8 @@ def test_argument_errors_need_no_gpu():
     assert lib.esparse_matrix_rate(ctx._h, 1, 7, 1, 0, C.byref(rate)) == -2              # no such dtype
     assert lib.esparse_matrix_rate(ctx._h, 1, 0, 1, 3, C.byref(rate)) == -1              # mix is 0, 1 or 2
     assert lib.esparse_matrix_rate(ctx._h, 0, 0, 1, 2, C.byref(rate)) == -2              # the stage mixes are 2:4 only
+    assert lib.esparse_read_rate(ctx._h, 1 << 20, None) == -1                             # null result pointer
+    assert lib.esparse_read_rate(ctx._h, 16, C.byref(rate)) == -1                         # fewer than 4 KiB
 
 
 def test_tune_table_text_roundtrip(tmp_path):
