@@ -270,7 +270,7 @@ int esparse_output_error(esparse_ctx* ctx, const void* Yref, const void* Y, long
 int esparse_matrix_rate(esparse_ctx* ctx, int sparse, esparse_dtype dtype, int random_operands, int mix, double* tflops);
 
 /* The same for the memory system: *gbs (HOST) receives the rate, in GB/s, of a plain streaming read of `bytes` bytes
- * per launch (16 bytes per lane, up to 2048 workgroups), averaged over 24 launches that walk through a buffer larger
+ * per launch (16 bytes per lane, one workgroup of 1024 threads per compute unit), averaged over 24 launches that walk through a buffer larger
  * than the last-level cache, so that every launch reads from HBM.  The decode kernels (Section 4, Table 5 decoder rows)
  * read 1.125 N K bytes per launch and cannot be faster than this for their size: launch, ramp-up and drain are a fixed
  * few microseconds.  Synchronises the context's stream; allocates max(2 bytes, 640 MiB) of scratch.

@@ -188,24 +188,24 @@ __global__ void __launch_bounds__(512) k_stage_rate(int trips, const uint4* __re
 }
 
 
-// plain streaming read: a workgroup reads a contiguous share of the buffer, 16 bytes per lane and load, four loads under
-// way per thread; the values are folded into one word per thread so that the loads cannot be dropped
-__global__ void __launch_bounds__(256) k_read_rate(const uint4* __restrict__ src, size_t units_per_wg, uint32_t* __restrict__ sink) {
+// plain streaming read: a workgroup of 16 waves reads a contiguous share of the buffer, 16 bytes per lane and load, four
+// loads under way per thread; the values are folded into one word per thread so that the loads cannot be dropped
+__global__ void __launch_bounds__(1024) k_read_rate(const uint4* __restrict__ src, size_t units_per_wg, uint32_t* __restrict__ sink) {
   const uint4* p = src + (size_t)blockIdx.x * units_per_wg;
   uint32_t f = 0u;
   size_t u = threadIdx.x;
-  for (; u + 768 < units_per_wg; u += 1024) {
+  for (; u + 3072 < units_per_wg; u += 4096) {
     const esp_read4 a = __builtin_nontemporal_load(reinterpret_cast<const esp_read4*>(p + u));
-    const esp_read4 b = __builtin_nontemporal_load(reinterpret_cast<const esp_read4*>(p + u + 256));
-    const esp_read4 c = __builtin_nontemporal_load(reinterpret_cast<const esp_read4*>(p + u + 512));
-    const esp_read4 d = __builtin_nontemporal_load(reinterpret_cast<const esp_read4*>(p + u + 768));
+    const esp_read4 b = __builtin_nontemporal_load(reinterpret_cast<const esp_read4*>(p + u + 1024));
+    const esp_read4 c = __builtin_nontemporal_load(reinterpret_cast<const esp_read4*>(p + u + 2048));
+    const esp_read4 d = __builtin_nontemporal_load(reinterpret_cast<const esp_read4*>(p + u + 3072));
     f ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
   }
-  for (; u < units_per_wg; u += 256) {
+  for (; u < units_per_wg; u += 1024) {
     const esp_read4 a = __builtin_nontemporal_load(reinterpret_cast<const esp_read4*>(p + u));
     f ^= a.x ^ a.y ^ a.z ^ a.w;
   }
-  sink[blockIdx.x * 256 + threadIdx.x] = f;
+  sink[blockIdx.x * 1024 + threadIdx.x] = f;
 }
 
 }  // namespace
@@ -272,12 +272,17 @@ int esp_matrix_rate_device(esparse_ctx* ctx, int sparse, int dtype, int random_o
 // larger than the last-level cache, so every launch reads from HBM.  The decode kernels read 1.125 N K bytes per launch
 // and can be no faster than this for their size (launch, ramp-up and drain are a fixed few microseconds).
 int esp_read_rate_device(esparse_ctx* ctx, size_t bytes, double* gbs) {
-  const size_t wgs = std::min<size_t>(2048, std::max<size_t>(1, bytes / 16384));  // at least 16 KiB per workgroup
+  // one workgroup of 1024 threads per compute unit: the fastest of the grids tried (103 MB per launch: 17.0 us against
+  // 18.6 with 2048 workgroups of 256 threads and 20.5 with 8192; 19 MB: 5.0 against 5.1 and 6.8)
+  int cus = 0;
+  ESP_HIP(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device));
+  if (cus < 1) return esp_fail(ctx, ESPARSE_EHIP, "the device reports no compute units");
+  const size_t wgs = std::min<size_t>((size_t)cus, std::max<size_t>(1, bytes / 16384));  // at least 16 KiB per workgroup
   const size_t units_per_wg = (bytes / 16 + wgs - 1) / wgs;
   const size_t span = wgs * units_per_wg * 16;                                    // bytes one launch reads
   const size_t ncopies = std::max<size_t>(2, ((size_t)640 << 20) / span + 1);
   DevBuf buf, sink;
-  if (buf.alloc(span * ncopies) != hipSuccess || sink.alloc(wgs * 256 * 4) != hipSuccess)
+  if (buf.alloc(span * ncopies) != hipSuccess || sink.alloc(wgs * 1024 * 4) != hipSuccess)
     return esp_fail(ctx, ESPARSE_ENOMEM, "scratch allocation failed");
   int rc = esp_fill_pattern_device(ctx, buf.p, span * ncopies);
   if (rc) return rc;
@@ -287,7 +292,7 @@ int esp_read_rate_device(esparse_ctx* ctx, size_t bytes, double* gbs) {
   const int reps = 24;
   auto launch = [&](int i) {
     const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(buf.p) + (size_t)(i % ncopies) * span);
-    hipLaunchKernelGGL(k_read_rate, dim3((unsigned)wgs), dim3(256), 0, ctx->stream, src, units_per_wg, sink.as<uint32_t>());
+    hipLaunchKernelGGL(k_read_rate, dim3((unsigned)wgs), dim3(1024), 0, ctx->stream, src, units_per_wg, sink.as<uint32_t>());
   };
   for (int i = 0; i < 4; i++) launch(i);
   hipError_t e = hipEventRecord(e0, ctx->stream);
