@@ -95,6 +95,21 @@ __device__ __forceinline__ void sched_fence() {
   __builtin_amdgcn_sched_barrier(0);
 #endif
 }
+// NM matrix instructions with ND copies into LDS and NA LDS reads spread evenly among them: after each multiply one copy
+// and a share of the reads.  A matrix instruction occupies its pipe for 16 or 32 clocks, during which the wave can issue
+// other work; issued in bursts (all multiplies, then all copies, then all reads) the copies queue up at the
+// vector-memory issue while the matrix pipe runs dry - measured 5-6 % slower on the prefill shapes.
+template <int NM, int ND, int NA>
+__device__ __forceinline__ void sched_spread() {
+  constexpr int AP = (NA + NM - 1) / NM;
+#pragma unroll
+  for (int p = 0; p < NM; p++) {
+    sched_group<0x008, 1>();
+    if (p < ND) sched_group<0x010, 1>();
+    if (AP > 0) sched_group<0x100, AP>();
+  }
+  if (ND > NM) sched_group<0x010, ND - NM>();
+}
 
 // ------------------------------------------------------------------------------------------------
 // instruction wrappers
@@ -896,15 +911,12 @@ __device__ __forceinline__ void tile_stage(TileState<SPARSE, TR, TC, NWC>& st, c
   tile_prefetch_a<SPARSE, TR, TC, NWC>(st, a_pre, m_pre, k + 3 < st.k1 ? k + 3 : last);
   tile_multiply<DT, SPARSE, TR, TC, NWC, 0, TH, false, D, OFF>(st, cur, bq, b_cur, b_nxt, k);
   tile_load_a<SPARSE, TR, TC, NWC>(st, a_nxt, m_nxt, nxt);
-  // the order wanted ahead of the barrier: per token tile "read a coming B operand, multiply, issue a share of
-  // the DMA, read a share of the next stage's A side".  A wave that issued its DMA in one burst would sit at the
-  // (bandwidth-limited) vector-memory issue while the matrix pipe runs dry.
+  // the order wanted ahead of the barrier: per token tile "read a coming B operand; then multiplies, each followed by
+  // one copy of the DMA's share and a share of the reads of the next stage's A side" (sched_spread).
 #pragma unroll
   for (int j = 0; j < TH; j++) {
     if (j + D < TC) sched_group<0x100, BR>();
-    sched_group<0x008, MM>();
-    sched_group<0x010, DPJ>();
-    sched_group<0x100, APJ>();
+    sched_spread<MM, DPJ, APJ>();
   }
   sched_fence();
   tile_arrive<DMA>();
@@ -1205,9 +1217,7 @@ __device__ __forceinline__ void tile32_stage(TileState<1, 8, 2 * TJ, 4>& st, con
 #pragma unroll
   for (int j = 0; j < TH; j++) {
     sched_group<0x100, 2>();
-    sched_group<0x008, 4>();
-    sched_group<0x010, DPJ>();
-    sched_group<0x100, APJ>();
+    sched_spread<4, DPJ, APJ>();
   }
   sched_fence();
   tile_arrive<DMA>();
