@@ -10,8 +10,8 @@
 //   mix 1: the stage's operand reads out of LDS (8 weight + 8 activation operands of 16 bytes per lane and 8 index
 //          words per wave: 144 KiB per workgroup) feeding the multiplies;
 //   mix 2: ... and the DMA of a coming stage's operands from an L2-resident region of global memory into LDS (6 copies
-//          of 16 bytes per lane + 2 of 4 bytes per wave: 52 KiB per workgroup, one copy after every second multiply), the
-//          stage's counted wait and its barrier.
+//          of 16 bytes per lane + 2 of 4 bytes per wave: 52 KiB per workgroup, each copy behind one multiply, none behind
+//          the stage's last four), the stage's counted wait and its barrier.
 // The rate of mix 2 is what this instruction mix can reach on the chip when every global access hits the L2 and nothing
 // waits for data: the distance between it and a product kernel is the kernel's to close, the distance between it and
 // mix 0 is not.
@@ -154,7 +154,8 @@ __global__ void __launch_bounds__(512) k_stage_rate(int trips, const uint4* __re
       for (int m = 0; m < 4; m++) {
         o.idx = (int)ix[m];
         acc[(g & 1) * 4 + m] = rate_multiply<DT, 1>(o, m, acc[(g & 1) * 4 + m]);
-        if (MIX >= 2 && (m & 1) && issued < ND) {
+        if (MIX >= 2 && g < 3 && m < 3 && issued < ND) {  // the order of the tile kernel: a copy after each of the first three
+                                                            // multiplies of the first three groups of four
           const int q = issued++;
 #if defined(__HIP_DEVICE_COMPILE__)
           if (q < ND16)
