@@ -98,15 +98,18 @@ __device__ __forceinline__ void sched_fence() {
 // NM matrix instructions with ND copies into LDS and NA LDS reads spread evenly among them: after each multiply one copy
 // and a share of the reads.  A matrix instruction occupies its pipe for 16 or 32 clocks, during which the wave can issue
 // other work; issued in bursts (all multiplies, then all copies, then all reads) the copies queue up at the
-// vector-memory issue while the matrix pipe runs dry - measured 5-6 % slower on the prefill shapes.
-template <int NM, int ND, int NA>
+// vector-memory issue while the matrix pipe runs dry - measured 5-6 % slower on the prefill shapes.  READS_FIRST: the
+// reads ahead of the copy in each slot (same-box comparisons: 2 % faster for the 8-wave 32x32x32 kernel, 4-8 % slower
+// for the 4-wave kernel with its deeper operand read-ahead, no difference for the other 8-wave kernels).
+template <int NM, int ND, int NA, bool READS_FIRST = false>
 __device__ __forceinline__ void sched_spread() {
   constexpr int AP = (NA + NM - 1) / NM;
 #pragma unroll
   for (int p = 0; p < NM; p++) {
     sched_group<0x008, 1>();
+    if (READS_FIRST && AP > 0) sched_group<0x100, AP>();
     if (p < ND) sched_group<0x010, 1>();
-    if (AP > 0) sched_group<0x100, AP>();
+    if (!READS_FIRST && AP > 0) sched_group<0x100, AP>();
   }
   if (ND > NM) sched_group<0x010, ND - NM>();
 }
@@ -1217,7 +1220,7 @@ __device__ __forceinline__ void tile32_stage(TileState<1, 8, 2 * TJ, 4>& st, con
 #pragma unroll
   for (int j = 0; j < TH; j++) {
     sched_group<0x100, 2>();
-    sched_spread<4, DPJ, APJ>();
+    sched_spread<4, DPJ, APJ, true>();
   }
   sched_fence();
   tile_arrive<DMA>();
