@@ -690,13 +690,14 @@ def main():
         del r, cmp_
     del calib0, Xh, Yd0
 
-    # ------------------------------------------------------------------ extra: 4:8 against 2:4 at the decode sizes
-    # 4:8 has no matrix instruction: the decode kernel expands the bitmaps in registers and uses the dense one;
-    # same bytes per weight as 2:4, so where the product is bound by reading the weights it runs at the same rate
+    # ------------------------------------------------------------------ extra: 4:8 against 2:4 (and dense) at every size
+    # 4:8 has no matrix instruction: the kernels expand each group to a dense operand in registers and use the dense
+    # one; same bytes per weight as 2:4, so where the product is bound by reading the weights it runs at the same
+    # rate, and at prefill sizes it is bound by the dense instruction
     four_eight = []
     seen48 = set()
     for name, skey, stream in MATS:
-        if skey in seen48 or not any(M <= 64 for M in M_LIST):
+        if skey in seen48:
             continue
         seen48.add(skey)
         N, K = shapes[skey]
@@ -711,14 +712,15 @@ def main():
                 r24 = ctx.prune(None, layers[li][n2]["W"], opts, score=layers[li][n2]["score"], want_retained=True).retained
             comps48.append(ctx.compress(layers[li][n2]["W"], r.mask, r.perm, 4, 8, canonical=False))
             del r
-        for M in [m_ for m_ in M_LIST if m_ <= 64]:
-            ctx.tune(M, N, K, dcode, 2)
+        for M in M_LIST:
+            v48, _ = ctx.tune(M, N, K, dcode, 2)
             Y = outs[(name, M)]
             ctx.stage_activations(acts[(stream, M)], layers[0][name]["perm"], N, ws)
             P = len(pool)
             t48 = kernel_time(lambda i, M=M, Y=Y: ctx.spmm_staged(M, comps48[i % P], ws, Y), 48)
-            t24 = [r_["spmm_kernel_us"] for r_ in per_shape if r_["layer"] == skey and r_["M"] == M][0]
-            four_eight.append(dict(layer=skey, N=N, K=K, M=M, spmm_4_8_kernel_us=round(t48 * 1e6, 2), spmm_2_4_kernel_us=t24,
+            t24, tdn = [(r_["spmm_kernel_us"], r_["dense_kernel_us"]) for r_ in per_shape if r_["layer"] == skey and r_["M"] == M][0]
+            four_eight.append(dict(layer=skey, N=N, K=K, M=M, variant_4_8=esp.variant_name(v48),
+                                   spmm_4_8_kernel_us=round(t48 * 1e6, 2), spmm_2_4_kernel_us=t24, dense_kernel_us=tdn,
                                    retained_metric_4_8_over_2_4=round(retained48 / r24, 5)))
         del comps48
     torch.cuda.empty_cache()

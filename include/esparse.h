@@ -122,8 +122,10 @@ int esparse_compressed_size(long long N, long long K, int n_keep, int m_group, e
  *              offset Np*Kp the uint16 units ordered [row/16][chunk/16][chunk%4][row%16][(chunk/4)%4].
  *              4:8: the group of row 16 rt + r covering re-ordered channels 64 ks + 32 h + 8 g .. + 8
  *              belongs to lane 16 g + r: its 4 kept values are half h (8 B) of the 16-byte unit
- *              (rt * Kp/64 + ks) * 64 + lane, its bitmap byte h of the uint16 unit at the place the
- *              2:4 form keeps that lane's indices for step ks.
+ *              (rt * Kp/64 + ks) * 64 + lane, its pattern code byte h of the uint16 unit at the place the
+ *              2:4 form keeps that lane's indices for step ks.  Pattern code = the index of the group's
+ *              occupancy bitmap among the 70 bitmaps with four bits set, in ascending order (0x0f -> 0,
+ *              0x17 -> 1, ..., 0xf0 -> 69); padding groups hold zero values and code 0.
  * Errors: EBADMASK (a group keeping != n, or > n non-zeros with mask NULL), EBADPERM.
  * Synchronises (it reports those two errors). */
 int esparse_compress(esparse_ctx* ctx, const void* W, const uint8_t* mask, const int32_t* perm,
@@ -142,10 +144,12 @@ int esparse_compress(esparse_ctx* ctx, const void* W, const uint8_t* mask, const
  * for variants that split K over workgroups) - what a call naming that variant requires.
  * M = 0 is a no-op.  n:m = 2:4 runs on the sparse matrix instruction.  n:m = 4:8 (Section 4 lists it as a
  * format the hardware of the paper cannot multiply; there is no instruction for it here either): the
- * decode kernels expand each bitmap to a dense operand in registers and use the dense instruction, which
- * pays where the product is bound by reading the weights; inputs longer than 64 tokens are processed
- * 64 at a time; only decode-kernel variants apply (EUNSUPPORTED for the others).  Other n:m:
- * EUNSUPPORTED.  Does not synchronise. */
+ * kernels expand each group to a dense operand in registers (byte-permute selectors looked up by the
+ * group's pattern code) and use the dense instruction, which pays where the product is bound by reading
+ * the weights; at prefill sizes (the tile48 variants, 64 tokens and more; the default beyond 128) it runs
+ * at 0.7-0.9 of the dense product's speed on 56 % of its weight bytes.  Only decode-kernel variants
+ * (inputs longer than 64 tokens: 64 at a time) and the tile48 variants apply (EUNSUPPORTED for the
+ * others).  Other n:m: EUNSUPPORTED.  Does not synchronise. */
 int esparse_spmm_workspace(long long M, long long N, long long K, int variant, size_t* bytes);
 int esparse_spmm(esparse_ctx* ctx, const void* X, long long M, const void* native_w,
                  const int32_t* perm, long long N, long long K, esparse_dtype dtype, int n_keep,

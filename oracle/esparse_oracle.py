@@ -411,17 +411,23 @@ def native_tiling_4_8(values: np.ndarray, meta: np.ndarray, N: int, K: int):
     A pure index map (documented in include/esparse.h), same size and unit numbering as the
     2:4 one.  The group of row 16 rt + r that covers re-ordered channels 64 ks + 32 h + 8 g ..
     + 8 belongs to lane 16 g + r: its 4 kept values (8 bytes) are the half h of the 16-byte
-    value unit (rt * nks + ks) * 64 + lane, its bitmap the byte h of the 16-bit metadata unit
-    ordered [rt][ks // 4][g][r][ks % 4].  Padding (rows to 16, K to 256) is zero.
+    value unit (rt * nks + ks) * 64 + lane, its pattern code the byte h of the 16-bit metadata unit
+    ordered [rt][ks // 4][g][r][ks % 4].  The pattern code of a group is the index of its occupancy
+    bitmap in the ascending list of the 70 bitmaps with four bits set.  Padding (rows to 16, K to
+    256) is zero: zero values, code 0.
     Returns (native_values[Np*Kp/2] of the value dtype, native_meta[Np*Kp/8] uint8).
     """
+    patterns = [b for b in range(256) if bin(b).count("1") == 4]        # ascending; 70 of them
+    code_of = np.zeros(256, dtype=np.uint8)
+    for code, b in enumerate(patterns):
+        code_of[b] = code
     Np = -(-N // 16) * 16
     Kp = -(-K // 256) * 256
     nks = Kp // 64
     v = np.zeros((Np, Kp // 8, 4), dtype=values.dtype)
     v.reshape(Np, Kp // 2)[:N, :K // 2] = values
     mb = np.zeros((Np, Kp // 8), dtype=np.uint8)
-    mb[:N, :K // 8] = np.asarray(meta, dtype=np.uint8).reshape(N, K // 8)
+    mb[:N, :K // 8] = code_of[np.asarray(meta, dtype=np.uint8).reshape(N, K // 8)]
     nv = np.zeros((Np // 16, nks, 64, 2, 4), dtype=values.dtype)
     nm = np.zeros((Np // 16, nks // 4, 64, 4, 2), dtype=np.uint8)
     for row in range(Np):

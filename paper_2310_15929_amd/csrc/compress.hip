@@ -184,8 +184,26 @@ __global__ void __launch_bounds__(512) k_compress_2_4_rows(const uint16_t* __res
 // Native form (what the 4:8 product streams; same size and unit numbering as the 2:4 one): the group
 // of row 16 rt + r that covers channels 64 ks + 32 h + 8 g .. + 8 is the A operand of lane 16 g + r of
 // the dense 16x16x32 instruction for half-step h of step ks.  Its 4 kept values (8 bytes) sit at byte
-// 8 h of the 16-byte unit (rt nks + ks) 64 + lane; its bitmap is byte h of the 16-bit word at the place
-// where the 2:4 form keeps that lane's index half for step ks.  Padding rows and channels hold zeros.
+// 8 h of the 16-byte unit (rt nks + ks) 64 + lane; its pattern code is byte h of the 16-bit word at the place
+// where the 2:4 form keeps that lane's index half for step ks.  The pattern code of a group is the index of its
+// bitmap among the 70 bitmaps with four bits set, in ascending order (the product kernels look their byte-permute
+// selectors up by it, and 70 entries can be replicated in LDS where 256 cannot).  Padding rows and channels hold
+// zero values and code 0.
+__device__ __forceinline__ uint32_t pattern_code_4_8(uint32_t bm) {
+  // sum over the set positions p_1 < p_2 < ... of C(p_j, j): the bitmaps below bm that first differ from it at p_j
+  uint32_t code = 0;
+  int j = 0;
+#pragma unroll
+  for (int e = 0; e < 8; e++)
+    if ((bm >> e) & 1u) {
+      j++;
+      int c = 1;
+      for (int t = 0; t < j; t++) c = c * (e - t) / (t + 1);
+      code += (uint32_t)c;
+    }
+  return code;
+}
+
 __global__ void __launch_bounds__(256) k_compress_4_8(const uint16_t* __restrict__ W, const uint8_t* __restrict__ mask,
                                                        const int32_t* __restrict__ perm, long long N, long long K, long long Np,
                                                        long long Kp, uint16_t* __restrict__ values, uint8_t* __restrict__ meta,
@@ -243,7 +261,7 @@ __global__ void __launch_bounds__(256) k_compress_4_8(const uint16_t* __restrict
     v.x = kept[0] | ((uint32_t)kept[1] << 16);
     v.y = kept[2] | ((uint32_t)kept[3] << 16);
     *reinterpret_cast<uint2*>(nvalues + ((rt * nks + ks) * 64 + lane) * 16 + 8 * h) = v;
-    nmeta[(((rt * (nks / 4) + ks / 4) * 64 + lane) * 4 + (ks & 3)) * 2 + h] = (uint8_t)bm;
+    nmeta[(((rt * (nks / 4) + ks / 4) * 64 + lane) * 4 + (ks & 3)) * 2 + h] = (uint8_t)pattern_code_4_8(bm);
   }
 }
 

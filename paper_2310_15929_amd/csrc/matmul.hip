@@ -141,6 +141,44 @@ __device__ __forceinline__ uint32_t byte_perm(uint32_t hi, uint32_t lo, uint32_t
 #endif
 }
 
+// 4:8: byte-permute selectors that spread a group's 4 kept values over its 8 positions, one 16-byte entry per pattern
+// code (the index of the group's bitmap among the 70 bitmaps with four bits set, in ascending order - what the native
+// form stores per group): output half e takes value number popcount(bitmap below bit e) if bit e is set and 0 otherwise
+// (selector byte 0x0c yields 0x00).  COPIES copies of the table stand side by side, entry code * COPIES + c: with
+// COPIES = 16 and c = lane % 16 the 16 lanes that one pass of a 16-byte LDS read serves fall into 16 different groups of
+// four banks whatever their codes are (measured: the rate of a conflict-free read; one copy: half of it).
+// Threads 0 .. 255 of the workgroup take one bitmap each; the caller synchronises.
+constexpr int LUT48_CODES = 70;
+template <int COPIES>
+__device__ __forceinline__ void fill_expand_lut(uint4* s_lut, int tid) {
+  if (tid < 256 && __builtin_popcount(tid) == 4) {
+    uint32_t sel[4] = {0x0c0c0c0cu, 0x0c0c0c0cu, 0x0c0c0c0cu, 0x0c0c0c0cu};
+    int code = 0, r = 0;
+#pragma unroll
+    for (int e = 0; e < 8; e++)
+      if ((tid >> e) & 1) {
+        const int sh = 16 * (e & 1);
+        sel[e >> 1] = (sel[e >> 1] & ~(0xffffu << sh)) | (((2u * r) | ((2u * r + 1u) << 8)) << sh);
+        r++;
+        int c = 1;  // C(e, r): bitmaps below this one that agree with it above bit e and have a zero at bit e
+        for (int t = 0; t < r; t++) c = c * (e - t) / (t + 1);
+        code += c;
+      }
+    for (int c = 0; c < COPIES; c++) s_lut[code * COPIES + c] = uint4{sel[0], sel[1], sel[2], sel[3]};
+  }
+}
+
+// the dense operands of the two half steps of a 4:8 unit: v.x, v.y hold the 4 kept values of the first group of 8, v.z, v.w
+// those of the second; codes = the two pattern codes (bits 0-7, 8-15); copy = the lane's copy of the table
+template <int COPIES>
+__device__ __forceinline__ void expand_4_8(const uint4 v, uint32_t codes, const uint4* s_lut, unsigned copy, uint4& e0, uint4& e1) {
+  const unsigned c0 = codes & 0xffu, c1 = (codes >> 8) & 0xffu;  // a code past the table (corrupt input) reads the last entry
+  const uint4 s0 = s_lut[(c0 < LUT48_CODES ? c0 : LUT48_CODES - 1) * COPIES + copy];
+  const uint4 s1 = s_lut[(c1 < LUT48_CODES ? c1 : LUT48_CODES - 1) * COPIES + copy];
+  e0 = uint4{byte_perm(v.y, v.x, s0.x), byte_perm(v.y, v.x, s0.y), byte_perm(v.y, v.x, s0.z), byte_perm(v.y, v.x, s0.w)};
+  e1 = uint4{byte_perm(v.w, v.z, s1.x), byte_perm(v.w, v.z, s1.y), byte_perm(v.w, v.z, s1.z), byte_perm(v.w, v.z, s1.w)};
+}
+
 template <int DT>
 __device__ __forceinline__ floatx4_t mfma16(uint4 a, uint4 b, floatx4_t c) {
   if (DT == ESPARSE_F16) {
@@ -509,25 +547,10 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long lon
     }
     __syncthreads();
   }
-  // SPARSE == 2 (4:8): byte-permute selectors that spread a group's 4 kept values over its 8 positions,
-  // one 16-byte entry per bitmap: output half e takes value number popcount(bitmap below bit e) if
-  // bit e is set and 0 otherwise (selector byte 0x0c yields 0x00)
-  __shared__ uint4 s_lut[SPARSE == 2 ? 256 : 1];
+  __shared__ uint4 s_lut[SPARSE == 2 ? LUT48_CODES : 1];  // 4:8: the byte-permute selectors of every pattern code
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (SPARSE == 2) {
-    if (tid < 256) {
-      uint32_t sel[4] = {0x0c0c0c0cu, 0x0c0c0c0cu, 0x0c0c0c0cu, 0x0c0c0c0cu};
-#pragma unroll
-      for (int e = 0; e < 8; e++)
-        if ((tid >> e) & 1) {
-          const uint32_t r = (uint32_t)__builtin_popcount(tid & ((1 << e) - 1));
-          if (r < 4) {
-            const int sh = 16 * (e & 1);
-            sel[e >> 1] = (sel[e >> 1] & ~(0xffffu << sh)) | (((2u * r) | ((2u * r + 1u) << 8)) << sh);
-          }
-        }
-      s_lut[tid] = uint4{sel[0], sel[1], sel[2], sel[3]};
-    }
+    fill_expand_lut<1>(s_lut, tid);
     __syncthreads();
   }
   const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
@@ -676,11 +699,7 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long lon
 #pragma unroll
         for (int i = 0; i < RT; i++) {
           const uint4 v = a[u][i];
-          const uint4 s0 = s_lut[idx[u][i] & 0xff], s1 = s_lut[(idx[u][i] >> 8) & 0xff];
-          a[u][i] = uint4{byte_perm(v.y, v.x, s0.x), byte_perm(v.y, v.x, s0.y),
-                          byte_perm(v.y, v.x, s0.z), byte_perm(v.y, v.x, s0.w)};
-          a2[u][i] = uint4{byte_perm(v.w, v.z, s1.x), byte_perm(v.w, v.z, s1.y),
-                           byte_perm(v.w, v.z, s1.z), byte_perm(v.w, v.z, s1.w)};
+          expand_4_8<1>(v, (uint32_t)idx[u][i], s_lut, 0u, a[u][i], a2[u][i]);
         }
     }
 #pragma unroll
@@ -752,6 +771,7 @@ struct TileState {
   static constexpr int NW = 2 * NWC;                        // waves: 2 along the rows x NWC along the tokens
   static constexpr int NT = 64 * NW;                        // threads
   static constexpr bool HALF = SPARSE == 3;                 // dense, 32-channel stages (one half step per stage)
+  static constexpr bool META = SPARSE == 1 || SPARSE == 2;  // index words (2:4) or bitmaps (4:8) travel beside the weights
   static constexpr int BSTEP = HALF ? 64 : 128;             // 16-byte units of activations per token tile and stage
   static constexpr int BCOPIES = (NWC * TC * BSTEP) / NT;   // ... per lane and stage
   static constexpr int RTM = 2 * TR;                        // row tiles of 16 in the macro tile
@@ -765,6 +785,7 @@ struct TileState {
   const uint32_t* m_src[ACOPIES];  // index words (two stages of index halves per lane) of the copied row tiles
   unsigned lane, x_lane, wave, wr, wc;
   unsigned k0, k1;  // this workgroup's stages [k0, k1) of the K loop (all of them unless K is split)
+  const uint4* lut;  // 4:8: the byte-permute selectors of every pattern code, 16 copies (LDS)
 };
 
 // every vector-memory operation of the pipeline is a DMA into LDS: they keep their program order,
@@ -791,26 +812,42 @@ __device__ __forceinline__ void tile_prefetch_a(TileState<SPARSE, TR, TC, NWC>& 
     const unsigned off = SPARSE ? kn * 64u + st.lane : kn * 128u + (st.wave & 1u) * 64u + st.lane;
     global_to_lds_16(st.a_src[p] + off, sa + State::NT * p + st.wave * 64);
     // the lane's index word holding stage kn: 8 bytes per lane and group of 4 stages, word (kn % 4) / 2
-    if (SPARSE == 1)
+    if (State::META)
       global_to_lds_4(st.m_src[p] + ((kn >> 2) * 128u + st.lane * 2u + ((kn >> 1) & 1u)), sm + State::NT * p + st.wave * 64);
   }
 }
 
-// the A side of one stage in registers: the wave's TR weight operands and their raw index words
+// the A side of one stage in registers: the wave's TR weight operands and their raw index words; 4:8: the dense operands
+// of the stage's two half steps, expanded from the kept values and the bitmaps as they are read
 template <int SPARSE, int TR>
 struct TileRegs {
-  uint4 a[SPARSE ? TR : 2 * TR];
-  uint32_t m[SPARSE ? TR : 1];
+  uint4 a[(SPARSE == 1 || SPARSE == 3) ? TR : 2 * TR];
+  uint32_t m[SPARSE == 1 ? TR : 1];
 };
 
 template <int SPARSE, int TR, int TC, int NWC>
 __device__ __forceinline__ void tile_load_a(TileState<SPARSE, TR, TC, NWC>& st, const uint4* sa, const uint32_t* sm,
-                                            TileRegs<SPARSE, TR>& r) {
+                                            TileRegs<SPARSE, TR>& r, unsigned k) {
+  if constexpr (SPARSE == 2) {
+    // all pattern codes first, then the kept values, then the selectors: the selector reads depend on the codes, and
+    // with the reads issued in this order (spread one by one among the multiplies) a code is back long before its
+    // selector read comes up.  The word holds the codes of an even and an odd stage; k = the stage of these operands.
+    uint32_t codes[TR];
+    uint4 raw[TR];
+#pragma unroll
+    for (int i = 0; i < TR; i++) codes[i] = sm[(st.wr * TR + i) * 64 + st.lane] >> ((k & 1u) * 16u);
+#pragma unroll
+    for (int i = 0; i < TR; i++) raw[i] = sa[(st.wr * TR + i) * 64 + st.lane];
+#pragma unroll
+    for (int i = 0; i < TR; i++) expand_4_8<16>(raw[i], codes[i], st.lut, st.lane & 15u, r.a[2 * i], r.a[2 * i + 1]);
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < TR; i++) {
-    if (SPARSE) {
+    if constexpr (SPARSE == 2) {
+    } else if constexpr (SPARSE != 0) {
       r.a[i] = sa[(st.wr * TR + i) * 64 + st.lane];
-      if (SPARSE == 1) r.m[i] = sm[(st.wr * TR + i) * 64 + st.lane];
+      if constexpr (SPARSE == 1) r.m[i] = sm[(st.wr * TR + i) * 64 + st.lane];
     } else {
       r.a[2 * i] = sa[(st.wr * TR + i) * 128 + st.lane];
       r.a[2 * i + 1] = sa[(st.wr * TR + i) * 128 + 64 + st.lane];
@@ -834,7 +871,7 @@ __device__ __forceinline__ void tile_multiply(TileState<SPARSE, TR, TC, NWC>& st
   using State = TileState<SPARSE, TR, TC, NWC>;
   constexpr int BS = State::BSTEP;
   int idx[TR];
-  if (SPARSE == 1) {
+  if constexpr (SPARSE == 1) {
     const unsigned sh = (k & 1u) * 16u;  // the word holds the index halves of an even and an odd stage
 #pragma unroll
     for (int i = 0; i < TR; i++) idx[i] = (int)(r.m[i] >> sh);
@@ -854,11 +891,11 @@ __device__ __forceinline__ void tile_multiply(TileState<SPARSE, TR, TC, NWC>& st
     }
 #pragma unroll
     for (int i = 0; i < TR; i++) {
-      if (SPARSE == 1) {
+      if constexpr (SPARSE == 1) {
         st.acc[i][j] = smfmac16<DT, 0>(r.a[i], cur.b0, cur.b1, st.acc[i][j], idx[i]);
-      } else if (State::HALF) {
+      } else if constexpr (State::HALF) {
         st.acc[i][j] = mfma16<DT>(r.a[i], cur.b0, st.acc[i][j]);
-      } else {
+      } else {  // dense, or 4:8 expanded to dense operands
         st.acc[i][j] = mfma16<DT>(r.a[2 * i], cur.b0, st.acc[i][j]);
         st.acc[i][j] = mfma16<DT>(r.a[2 * i + 1], cur.b1, st.acc[i][j]);
       }
@@ -900,20 +937,20 @@ __device__ __forceinline__ void tile_stage(TileState<SPARSE, TR, TC, NWC>& st, c
                                            const uint4* a_nxt, const uint32_t* m_nxt, uint4* b_pre, uint4* a_pre, uint32_t* m_pre,
                                            unsigned k) {
   using State = TileState<SPARSE, TR, TC, NWC>;
-  constexpr int DMA = State::BCOPIES + (SPARSE == 1 ? 2 : 1) * State::ACOPIES;
+  constexpr int DMA = State::BCOPIES + (State::META ? 2 : 1) * State::ACOPIES;
   constexpr int BR = State::HALF ? 1 : 2;                    // LDS reads per B operand
   constexpr bool STRADDLE = TC >= 4;
   static_assert(D == 1 || (STRADDLE && D < TC), "deeper operand streams exist for the straddling schedule only");
   constexpr int TH = STRADDLE ? TC - D : TC;                 // token tiles multiplied ahead of the barrier
   constexpr int DPJ = (DMA + TH - 1) / TH;                   // DMA operations issued per token tile
-  constexpr int AREADS = State::HALF ? TR : 2 * TR;          // LDS reads of tile_load_a
+  constexpr int AREADS = State::HALF ? TR : (SPARSE == 2 ? 4 : 2) * TR;  // LDS reads of tile_load_a (4:8: + two selector reads)
   constexpr int APJ = (AREADS + TH - 1) / TH;
-  constexpr int MM = SPARSE ? TR : 2 * TR;                   // matrix instructions per token tile
+  constexpr int MM = (SPARSE == 1 || SPARSE == 3) ? TR : 2 * TR;  // matrix instructions per token tile
   const unsigned last = st.k1 - 1;                           // past the end: reload the last stage (never used)
   tile_prefetch_b<SPARSE, TR, TC, NWC>(st, b_pre, k + 2 < st.k1 ? k + 2 : last);
   tile_prefetch_a<SPARSE, TR, TC, NWC>(st, a_pre, m_pre, k + 3 < st.k1 ? k + 3 : last);
   tile_multiply<DT, SPARSE, TR, TC, NWC, 0, TH, false, D, OFF>(st, cur, bq, b_cur, b_nxt, k);
-  tile_load_a<SPARSE, TR, TC, NWC>(st, a_nxt, m_nxt, nxt);
+  tile_load_a<SPARSE, TR, TC, NWC>(st, a_nxt, m_nxt, nxt, k + 1);
   // the order wanted ahead of the barrier: per token tile "read a coming B operand; then multiplies, each followed by
   // one copy of the DMA's share and a share of the reads of the next stage's A side" (sched_spread).
 #pragma unroll
@@ -945,7 +982,7 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
     uint4* __restrict__ sb2, uint32_t* __restrict__ sm0, uint32_t* __restrict__ sm1, uint32_t* __restrict__ sm2,
     const uint4* __restrict__ A, const uint16_t* __restrict__ meta16, const uint4* __restrict__ Xf,
     uint16_t* __restrict__ Y, float* __restrict__ partial, long long M, long long N, long long Mp, long long Np, long long Kp,
-    long long n_tiles, long long ntb, int nsplit, int sps, int band) {
+    long long n_tiles, long long ntb, int nsplit, int sps, int band, const uint4* lut = nullptr) {
   constexpr int NTT = NWC * TC;               // token tiles of 16 in the macro tile
   constexpr int RTM = 2 * TR;                 // row tiles of 16 in the macro tile
   using State = TileState<SPARSE, TR, TC, NWC>;
@@ -955,6 +992,7 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
   st.wave = (unsigned)wave_uniform(tid >> 6);  // wave-uniform: keeps the operand bases in SGPRs
   st.wr = st.wave / NWC;
   st.wc = st.wave % NWC;
+  st.lut = lut;
   const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
   const long long nst = State::HALF ? 2 * nks : nks;  // stages of the K loop
   // XCD-aware numbering: XCD x (= blockIdx % 8) works through items [x * per, (x + 1) * per); an item is
@@ -975,7 +1013,7 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
   for (int p = 0; p < State::ACOPIES; p++) {
     const long long rtl = SPARSE ? State::NW * p + st.wave : (State::NW / 2) * p + (st.wave >> 1);  // row tile this wave copies
     const long long rt = (rt_macro + rtl < nrt) ? rt_macro + rtl : nrt - 1;
-    st.a_src[p] = A + (SPARSE == 1 ? rt * nks : rt * (2 * nks)) * 64;
+    st.a_src[p] = A + (State::META ? rt * nks : rt * (2 * nks)) * 64;
     st.m_src[p] = reinterpret_cast<const uint32_t*>(meta16) + rt * (nks / 4) * 128;
   }
 #pragma unroll
@@ -1002,7 +1040,7 @@ __device__ __attribute__((always_inline)) void tile_pipeline(
   sched_fence();
   tile_arrive<0>();
   TileRegs<SPARSE, TR> r0, r1;
-  tile_load_a<SPARSE, TR, TC, NWC>(st, sa0, sm0, r0);
+  tile_load_a<SPARSE, TR, TC, NWC>(st, sa0, sm0, r0, kb);
   sched_fence();
   tile_arrive<0>();  // every wave has its first A side in registers before the first stage overwrites its buffer
   TileB bq[D];       // the B operands of the coming stage's first D token tiles
@@ -1121,11 +1159,17 @@ __global__ void __launch_bounds__(128 * NWC) k_mm_tile(const uint4* __restrict__
   __shared__ uint4 s_b0[NWC * TC * BSTEP];  // one stage of activations each: [NWC TC token tiles][2 half steps (or 1)][64 lanes]
   __shared__ uint4 s_b1[NWC * TC * BSTEP];
   __shared__ uint4 s_b2[NWC * TC * BSTEP];
-  __shared__ uint32_t s_m0[SPARSE == 1 ? ASLOTS : 1];  // one stage pair of index words each: [row tiles][64 lanes]
-  __shared__ uint32_t s_m1[SPARSE == 1 ? ASLOTS : 1];
-  __shared__ uint32_t s_m2[SPARSE == 1 ? ASLOTS : 1];
+  constexpr bool META = TileState<SPARSE, TR, TC, NWC>::META;
+  __shared__ uint32_t s_m0[META ? ASLOTS : 1];  // one stage pair of index words (4:8: bitmaps) each: [row tiles][64 lanes]
+  __shared__ uint32_t s_m1[META ? ASLOTS : 1];
+  __shared__ uint32_t s_m2[META ? ASLOTS : 1];
+  __shared__ uint4 s_lut[SPARSE == 2 ? LUT48_CODES * 16 : 1];
+  if (SPARSE == 2) {
+    fill_expand_lut<16>(s_lut, (int)threadIdx.x);
+    __syncthreads();
+  }
   tile_pipeline<DT, SPARSE, TR, TC, NWC, D>(s_a0, s_a1, s_a2, s_b0, s_b1, s_b2, s_m0, s_m1, s_m2, A, meta16, Xf, Y, partial, M, N, Mp,
-                                         Np, Kp, n_tiles, ntb, nsplit, sps, band);
+                                         Np, Kp, n_tiles, ntb, nsplit, sps, band, s_lut);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1634,6 +1678,7 @@ struct Variant {
   int x32;         // tile kind: 1 = the 32x32x32 form of the sparse instruction and the epilogue through LDS (2:4 only)
   int depth;       // tile kind: token tiles the activation operands are read ahead (0 = 1)
   int half;        // tile kind: 1 = dense only, stages of 32 channels and the macro tile of the sparse form
+  int four8;       // tile kind: 1 = 4:8 only, bitmaps expanded to dense operands in registers, dense instruction
 };
 static const Variant kVariants[] = {
     {"wave_r2_t1_splitk", KIND_WAVE, 2, 1, 1, 0},
@@ -1694,6 +1739,13 @@ static const Variant kVariants[] = {
     {"tile_w8_t128_h", KIND_TILE, 8, 2, 0, 4, 0, 0, 0, 1},
     {"tile_w8_t256_h_splitk", KIND_TILE, 8, 4, 1, 4, 0, 0, 0, 1},  // ... with K split over workgroups (M <= 512)
     {"tile_w8_t128_h_splitk", KIND_TILE, 8, 2, 1, 4, 0, 0, 0, 1},
+    // 4:8 only: the 2:4 kernel's copies, rings and 64-channel stages; while a wave reads the next stage's weight units out
+    // of LDS it expands each unit and its two pattern codes into the dense operands of two 16x16x32 multiplies (selectors
+    // from a table in LDS, replicated so that the lookups are free of bank conflicts).  128 rows x 256 tokens per
+    // workgroup (a wave expands 4 row tiles for 4 token tiles) or 256 rows x 128 tokens
+    {"tile48_w8_r128_t256", KIND_TILE, 4, 4, 0, 4, 0, 0, 0, 0, 1},
+    {"tile48_w8_t128", KIND_TILE, 8, 2, 0, 4, 0, 0, 0, 0, 1},
+    {"tile48_w8_t128_splitk", KIND_TILE, 8, 2, 1, 4, 0, 0, 0, 0, 1},  // ... with K split over workgroups (M <= 512)
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
@@ -1705,8 +1757,9 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
   (void)K;
   if (v < 0 || v >= kNumVariants) return false;
   const Variant& var = kVariants[v];
-  if (sparse == 2) {
-    // 4:8: decode kernels only; longer inputs go through them 64 tokens at a time
+  if (var.four8 && (sparse != 2 || M < 64)) return false;
+  if (sparse == 2 && !var.four8) {
+    // 4:8: otherwise decode kernels only; longer inputs go through them 64 tokens at a time
     if (var.kind != KIND_KSPLIT || var.quads) return false;
     const long long mc = M < 64 ? M : 64;
     const long long mt = mc <= 16 ? 1 : (mc <= 32 ? 2 : 4);
@@ -1733,6 +1786,11 @@ static int variant_index(const char* name) {
 }
 
 int esp_default_variant(long long M, long long N, long long K, int sparse) {
+  if (sparse == 2 && M > 128)  // 4:8 at prefill sizes; few macro tiles (and room for partial tiles): K split over workgroups
+  {
+    if (((N + 127) / 128) * ((M + 255) / 256) >= 128 || esp_split_capacity(M) == 1) return variant_index("tile48_w8_r128_t256");
+    return variant_index("tile48_w8_t128_splitk");
+  }
   if (M <= 32 || sparse == 2) {
     const long long nrt = esp_round_up(N, 16) / 16;
     return nrt <= 320 ? 4 : 5;  // ksplit_w16_r1 / ksplit_w16_r2
@@ -1917,7 +1975,16 @@ static int launch_tile(esparse_ctx* ctx, const Variant& v, hipStream_t st, const
   // and 4 activation panels in its L2 instead of 1 and 32 (16384 tokens: 12-14 % faster); up to 8 token blocks the plain
   // order already gives each XCD a patch of 4 x 8
   const int band = ntb > 8 ? 8 : 1;
-  if (v.half) {
+  if constexpr (SPARSE == 2) {
+    if (!v.four8) return esp_fail(ctx, ESPARSE_EINVAL, "4:8 weights at prefill sizes go through the tile48 variants");
+    if (v.tt == 4)
+      hipLaunchKernelGGL((k_mm_tile<DT, 2, 4, 4, 4>), grid, dim3(512), 0, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, n_tiles, ntb, nsplit, (int)sps, band);
+    else
+      hipLaunchKernelGGL((k_mm_tile<DT, 2, 8, 2, 4>), grid, dim3(512), 0, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, n_tiles, ntb, nsplit, (int)sps, band);
+    ESP_HIP(ctx, hipGetLastError());
+  } else if (v.four8) {
+    return esp_fail(ctx, ESPARSE_EINVAL, "the tile48 variants multiply 4:8 weights only");
+  } else if (v.half) {
     if (SPARSE != 0) return esp_fail(ctx, ESPARSE_EINVAL, "the half-step tile kernel multiplies dense weights only");
     if (v.tt == 4)
       hipLaunchKernelGGL((k_mm_tile<DT, 3, 8, 4, 4>), grid, dim3(512), 0, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, n_tiles, ntb, nsplit, (int)sps, band);
@@ -2156,6 +2223,9 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
 
   if (v.kind == KIND_TILE) {
     const uint16_t* meta16 = reinterpret_cast<const uint16_t*>(meta_bytes);
+    if (sparse == 2)
+      return dtype == ESPARSE_F16 ? launch_tile<ESPARSE_F16, 2>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp)
+                                  : launch_tile<ESPARSE_BF16, 2>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp);
     if (dtype == ESPARSE_F16)
       return sparse ? launch_tile<ESPARSE_F16, 1>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp)
                     : launch_tile<ESPARSE_F16, 0>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp);

@@ -338,10 +338,10 @@ def test_config5_block_size_sweep_and_4_8(esp, ctx):
             assert (vb, mb) == orc.compressed_bytes(N, K, n, m) and mb * 8 == N * K      # 1 bit of metadata per weight
             retained[(n, m, B)] = res.retained
             if B == 64:
-                # the product at the decode sizes of the configuration, sampled tokens x sampled output features
+                # the product at the sizes of the configuration, sampled tokens x sampled output features
                 feat = np.sort(rng.choice(N, 512, replace=False))
                 mask_feat = orc.nm_mask_vectorised(Wf[feat], s, theta, n, m)
-                for M in (1, 64):
+                for M in (1, 64, 1024):
                     X = wl.activations(cfg, layer, M, device="cuda")
                     Y = ctx.spmm(X, comp, res.perm)
                     tok = np.sort(rng.choice(M, min(M, 4), replace=False))

@@ -339,9 +339,10 @@ def test_native_tiling_is_bijection_and_matches_instruction_layout():
 
 
 def test_native_tiling_4_8_is_bijection_and_matches_dense_instruction_layout():
-    """The 4:8 native form, expanded the way the kernel does it (value number = popcount of the bitmap below the
-    position) and multiplied with the measured operand layout of the dense 16x16x32 instruction (A lane l: row
-    l % 16, channels 8 (l // 16) .. + 8), gives the plain masked product."""
+    """The 4:8 native form, decoded from its definition (pattern code c = the c-th smallest 8-bit number with four
+    bits set; value number = popcount of that bitmap below the position) and multiplied with the measured operand
+    layout of the dense 16x16x32 instruction (A lane l: row l % 16, channels 8 (l // 16) .. + 8), gives the plain
+    masked product."""
     N, K, M = 24, 320, 3
     W = _f16(RNG.standard_normal((N, K)))
     s = np.abs(RNG.standard_normal(K)) + 0.1
@@ -367,12 +368,39 @@ def test_native_tiling_4_8_is_bijection_and_matches_dense_instruction_layout():
             for lane in range(64):
                 r, g = lane % 16, lane // 16
                 for h in range(2):
-                    bm = int(maps[rt, ks // 4, lane, ks % 4, h])
+                    code = int(maps[rt, ks // 4, lane, ks % 4, h])
+                    assert code < 70
+                    bm, seen = 0, -1                                   # the code-th smallest number with four bits set
+                    while seen < code:
+                        bm += 1
+                        if bin(bm).count("1") == 4:
+                            seen += 1
                     for e in range(8):
                         if (bm >> e) & 1:
                             rank = bin(bm & ((1 << e) - 1)).count("1")
                             Y[:, 16 * rt + r] += vals[rt, ks, lane, h, rank] * Xp[:, 64 * ks + 32 * h + 8 * g + e]
     assert np.allclose(Y[:, :N], orc.spmm_ref(X, W, theta, mk), rtol=1e-12, atol=1e-12)
+
+
+def test_native_tiling_4_8_pattern_codes_at_their_places():
+    """Pattern codes written out by hand (0x0f is the smallest bitmap with four bits set, 0x17 the next, 0x1b, 0x1d,
+    0x1e, 0x27 follow, 0xf0 is the largest = code 69), at the metadata byte the index map names: row r of row tile 0,
+    group q = 8 ks + 4 h + g -> byte ((lane * 4 + ks % 4) * 2 + h) of the tile's first block, lane = 16 g + r."""
+    bitmaps = [0x0F, 0x17, 0x1B, 0x1D, 0x1E, 0x27, 0xF0, 0xE8]
+    codes = [0, 1, 2, 3, 4, 5, 69, 68]
+    meta = np.array([bitmaps], dtype=np.uint8)                      # one row, K = 64: groups q = 0 .. 7 of step ks = 0
+    values = np.zeros((1, 32), dtype=np.float16)
+    _, nm = orc.native_tiling_4_8(values, meta, 1, 64)
+    assert nm.size == 16 * 256 // 8
+    for q, code in enumerate(codes):
+        h, g = divmod(q, 4)
+        lane = 16 * g + 0
+        assert nm[(lane * 4 + 0) * 2 + h] == code, (q, nm[(lane * 4 + 0) * 2 + h], code)
+    expect = np.zeros_like(nm)
+    for q, code in enumerate(codes):
+        h, g = divmod(q, 4)
+        expect[(16 * g * 4) * 2 + h] = code
+    assert (nm == expect).all()                                      # everything else is padding: code 0
 
 
 # ---------------------------------------------------------------- products
