@@ -579,7 +579,7 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long lon
   const long long kb = gridDim.z > 1 ? (long long)blockIdx.z * args.sps : 0;
   const long long ke = gridDim.z > 1 && kb + args.sps < nks ? kb + args.sps : nks;
   if constexpr (IDXM == 2) {
-    // quads (2:4): wave w takes the four steps 4 w .. 4 w + 3, then 4 (w + NW) .., whose index halves are one 8-byte
+    // quads (2:4 and 4:8): wave w takes the four steps 4 w .. 4 w + 3, then 4 (w + NW) .., whose index halves are one 8-byte
     // unit per lane: one index load per row tile and quad instead of four.  The vector-memory path of a CU works
     // through a load lane by lane whatever its width, so a 2-byte index load costs what a 16-byte weight load costs.
     const uint2* meta64 = reinterpret_cast<const uint2*>(meta16);
@@ -640,10 +640,21 @@ __global__ void __launch_bounds__(NW * 64) k_mm_ksplit(KsplitArgs args, long lon
 #pragma unroll
       for (int u = 0; u < 4; u++)
 #pragma unroll
-        for (int i = 0; i < RT; i++)
+        for (int i = 0; i < RT; i++) {
+          const uint32_t half = (u & 1) ? iw[u >> 1][i] >> 16 : iw[u >> 1][i];  // index half (2:4) or two pattern codes (4:8)
+          if constexpr (SPARSE == 2) {
+            uint4 e0, e1;
+            expand_4_8<1>(a[u][i], half, s_lut, 0u, e0, e1);
 #pragma unroll
-          for (int j = 0; j < MT; j++)
-            acc[i][j] = smfmac16<DT, 0>(a[u][i], b0[u][j], b1[u][j], acc[i][j], (int)((u & 1) ? iw[u >> 1][i] >> 16 : iw[u >> 1][i]));
+            for (int j = 0; j < MT; j++) {
+              acc[i][j] = mfma16<DT>(e0, b0[u][j], acc[i][j]);
+              acc[i][j] = mfma16<DT>(e1, b1[u][j], acc[i][j]);
+            }
+          } else {
+#pragma unroll
+            for (int j = 0; j < MT; j++) acc[i][j] = smfmac16<DT, 0>(a[u][i], b0[u][j], b1[u][j], acc[i][j], (int)half);
+          }
+        }
     }
   } else
   for (long long ks = kb + (pairs ? 2 * wave : wave); ks < ke; ks += 2 * NW) {
@@ -1674,7 +1685,7 @@ struct Variant {
   int rt, tt;      // row tiles / token tiles per wave (ksplit: row tiles per workgroup, tt unused: MT follows M)
   int split_mode;  // wave and tile kinds: 0 = never split K, 1 = split K over workgroups to fill the chip
   int nw;          // ksplit kind: waves per workgroup; tile kind: waves along the tokens (the workgroup has 2 x nw waves)
-  int quads;       // ksplit kind: 1 = a wave takes four consecutive steps with one index load (2:4, at most 16 tokens)
+  int quads;       // ksplit kind: 1 = a wave takes four consecutive steps with one index load (2:4 and 4:8, at most 16 tokens)
   int x32;         // tile kind: 1 = the 32x32x32 form of the sparse instruction and the epilogue through LDS (2:4 only)
   int depth;       // tile kind: token tiles the activation operands are read ahead (0 = 1)
   int half;        // tile kind: 1 = dense only, stages of 32 channels and the macro tile of the sparse form
@@ -1716,7 +1727,7 @@ static const Variant kVariants[] = {
     {"tile_w8_r288_t128", KIND_TILE, 9, 2, 0, 4},
     {"tile_w8_r320_t128", KIND_TILE, 10, 2, 0, 4},
     // decode kernels for at most 16 tokens whose waves take four consecutive steps and read their index halves with
-    // one 8-byte load (2:4 only): 7-13 % on 4096 x 11008, 2-5 % on q/k/v in one launch, level or behind elsewhere
+    // one 8-byte load (2:4: 7-13 % on 4096 x 11008, 2-5 % on q/k/v in one launch, level or behind elsewhere; 4:8: two pattern codes per step)
     {"ksplit_w8_r1_q", KIND_KSPLIT, 1, 0, 0, 8, 1},
     {"ksplit_w16_r1_q", KIND_KSPLIT, 1, 0, 0, 16, 1},
     {"ksplit_w8_r2_q", KIND_KSPLIT, 2, 0, 0, 8, 1},
@@ -1760,7 +1771,7 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
   if (var.four8 && (sparse != 2 || M < 64)) return false;
   if (sparse == 2 && !var.four8) {
     // 4:8: otherwise decode kernels only; longer inputs go through them 64 tokens at a time
-    if (var.kind != KIND_KSPLIT || var.quads) return false;
+    if (var.kind != KIND_KSPLIT || (var.quads && M > 16)) return false;
     const long long mc = M < 64 ? M : 64;
     const long long mt = mc <= 16 ? 1 : (mc <= 32 ? 2 : 4);
     return (long long)var.nw * var.rt * mt * 1024 <= 160 * 1024;
@@ -1768,7 +1779,7 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
   if (var.split_mode == 1 && esp_split_capacity(M) == 1) return false;  // no room for partial tiles beyond 512 tokens
   if (var.kind == KIND_KSPLIT) {
     if (M > 64) return false;
-    if (var.quads && (sparse != 1 || M > 16)) return false;
+    if (var.quads && (sparse == 0 || M > 16)) return false;
     const long long mt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);  // token tiles; the waves' partial tiles must fit the LDS
     if ((long long)var.nw * var.rt * mt * 1024 > 160 * 1024) return false;
   }
@@ -1915,20 +1926,20 @@ static void launch_ksplit(const Variant& v, hipStream_t st, KsplitArgs args, int
   dim3 grid((unsigned)((nrt + v.rt - 1) / v.rt), (unsigned)count, (unsigned)nsplit);
   fold = fold && MT == 1 && mc > 0 && nsplit == 1;
   const size_t smem = (size_t)v.nw * v.rt * MT * 64 * 16 + (fold ? (size_t)2 * Kp * mc : 0);
-  const bool pairs = SPARSE == 1 && MT >= 2 && ((sps / 2) % v.nw) == 0 && nks % sps == 0;
+  const bool pairs = SPARSE != 0 && MT >= 2 && ((sps / 2) % v.nw) == 0 && nks % sps == 0;
   const bool quads = v.quads != 0;
 #define LAUNCH(R, W)                                                                                                          \
   do {                                                                                                                        \
-    if (MT == 1 && fold && SPARSE == 1 && quads && ((R == 1) || (W == 8 && (R == 2 || R == 4))))                              \
-      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, (SPARSE == 1 && MT == 1 && ((R == 1) || (W == 8 && (R == 2 || R == 4))) ? 2 : 0), MT == 1>), \
+    if (MT == 1 && fold && SPARSE != 0 && quads && ((R == 1) || (W == 8 && (R == 2 || R == 4))))                              \
+      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, (SPARSE != 0 && MT == 1 && ((R == 1) || (W == 8 && (R == 2 || R == 4))) ? 2 : 0), MT == 1>), \
                          grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp, mc);                                           \
     else if (MT == 1 && fold)                                                                                                 \
       hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, 0, MT == 1>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp, mc); \
-    else if (SPARSE == 1 && MT == 1 && quads && ((R == 1) || (W == 8 && (R == 2 || R == 4))))                                 \
-      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, (SPARSE == 1 && MT == 1 && ((R == 1) || (W == 8 && (R == 2 || R == 4))) ? 2 : 0)>), \
+    else if (SPARSE != 0 && MT == 1 && quads && ((R == 1) || (W == 8 && (R == 2 || R == 4))))                                 \
+      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, (SPARSE != 0 && MT == 1 && ((R == 1) || (W == 8 && (R == 2 || R == 4))) ? 2 : 0)>), \
                          grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp, mc);                                           \
-    else if (SPARSE == 1 && MT >= 2 && pairs)                                                                                 \
-      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, (SPARSE == 1 && MT >= 2 ? 1 : 0)>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, \
+    else if (SPARSE != 0 && MT >= 2 && pairs)                                                                                 \
+      hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, (SPARSE != 0 && MT >= 2 ? 1 : 0)>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, \
                          Kp, mc);                                                                                             \
     else                                                                                                                      \
       hipLaunchKernelGGL((k_mm_ksplit<DT, SPARSE, MT, R, W, 0>), grid, dim3(W * 64), smem, st, args, M, N, Mp, Np, Kp, mc); \
