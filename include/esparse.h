@@ -148,8 +148,9 @@ int esparse_compress(esparse_ctx* ctx, const void* W, const uint8_t* mask, const
  * group's pattern code) and use the dense instruction, which pays where the product is bound by reading
  * the weights; at prefill sizes (the tile48 variants, 64 tokens and more; the default beyond 128) it runs
  * at 0.7-0.9 of the dense product's speed on 56 % of its weight bytes.  Only decode-kernel variants
- * (inputs longer than 64 tokens: 64 at a time) and the tile48 variants apply (EUNSUPPORTED for the
- * others).  Other n:m: EUNSUPPORTED.  Does not synchronise. */
+ * (inputs longer than 64 tokens: 64 at a time), the stream variants with a ring of four slots (at most
+ * 128 tokens) and the tile48 variants apply (EUNSUPPORTED for the others).  Other n:m: EUNSUPPORTED.
+ * Does not synchronise. */
 int esparse_spmm_workspace(long long M, long long N, long long K, int variant, size_t* bytes);
 int esparse_spmm(esparse_ctx* ctx, const void* X, long long M, const void* native_w,
                  const int32_t* perm, long long N, long long K, esparse_dtype dtype, int n_keep,
@@ -202,7 +203,7 @@ int esparse_dense_gemm_staged(esparse_ctx* ctx, long long M, const void* packed_
  * ramp-up; the linear layers that read the same hidden state (q/k/v, gate/up) have the same shape.  This
  * call runs count (1..4) products Y[i] = X[i][:, perm[i]] . W'_i^T, all with the same M, N, K, dtype
  * and n:m, through one staging launch and one multiply launch when a decode kernel serves the shape
- * (M <= 64, or 4:8), and one after the other otherwise.  X, native_w, perm, Y: HOST arrays of count
+ * (the default up to 32 tokens), and one after the other otherwise.  X, native_w, perm, Y: HOST arrays of count
  * DEVICE pointers (perm may be NULL = identity for all, or hold NULL entries); members may share X.
  * workspace: DEVICE, 256-byte aligned, at least esparse_spmm_group_workspace bytes.  Results are
  * bitwise those of esparse_spmm with the same variant.  Errors as esparse_spmm; count outside 1..4:

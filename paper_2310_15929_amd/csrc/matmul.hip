@@ -1492,6 +1492,7 @@ struct StreamState {
   const uint4* x_src[BC];     // wave-uniform bases of this wave's DMA copies (token tile q / 2, half q % 2)
   unsigned x_dst[BC];         // ... and where they land in a ring buffer, in units
   unsigned lane, wave;
+  const uint4* lut;           // 4:8: the byte-permute selectors of every pattern code (LDS)
 };
 
 template <int SPARSE, int MT, int RT, int NW>
@@ -1523,6 +1524,13 @@ __device__ __forceinline__ void stream_multiply(const StreamState<SPARSE, MT, RT
     a[i] = uint4{r.a[i].x & keep, r.a[i].y & keep, r.a[i].z & keep, r.a[i].w & keep};
     if (!SPARSE) a2[i] = uint4{r.a2[i].x & keep, r.a2[i].y & keep, r.a2[i].z & keep, r.a2[i].w & keep};
   }
+  // 4:8: the dense operands of the two half steps, from the unit's kept values and the step's two pattern codes
+  uint4 e0[SPARSE == 2 ? RT : 1], e1[SPARSE == 2 ? RT : 1];
+  if constexpr (SPARSE == 2) {
+#pragma unroll
+    for (int i = 0; i < RT; i++) expand_4_8<1>(a[i], (uint32_t)r.idx[i] >> (16 * PAR), st.lut, 0u, e0[i], e1[i]);
+    sched_fence();  // the selector reads stay out of the read / multiply order set below
+  }
   // the activations of token tile j + 1 are read while tile j is multiplied
   uint4 b0[2], b1[2];
   b0[0] = sb[st.lane];
@@ -1535,8 +1543,11 @@ __device__ __forceinline__ void stream_multiply(const StreamState<SPARSE, MT, RT
     }
 #pragma unroll
     for (int i = 0; i < RT; i++) {
-      if (SPARSE) {
+      if constexpr (SPARSE == 1) {
         acc[i][j] = smfmac16<DT, PAR>(a[i], b0[j & 1], b1[j & 1], acc[i][j], r.idx[i]);
+      } else if constexpr (SPARSE == 2) {
+        acc[i][j] = mfma16<DT>(e0[i], b0[j & 1], acc[i][j]);
+        acc[i][j] = mfma16<DT>(e1[i], b1[j & 1], acc[i][j]);
       } else {
         acc[i][j] = mfma16<DT>(a[i], b0[j & 1], acc[i][j]);
         acc[i][j] = mfma16<DT>(a2[i], b1[j & 1], acc[i][j]);
@@ -1544,7 +1555,7 @@ __device__ __forceinline__ void stream_multiply(const StreamState<SPARSE, MT, RT
     }
   }
   // issue order: reads of tile 0, then per tile the reads of the next one ahead of its multiplies
-  constexpr int MM = (SPARSE ? 1 : 2) * RT;
+  constexpr int MM = (SPARSE == 1 ? 1 : 2) * RT;
   sched_group<0x100, 2>();
 #pragma unroll
   for (int j = 0; j + 1 < MT; j++) {
@@ -1578,7 +1589,8 @@ template <int DT, int SPARSE, int MT, int RT, int NW, int NB>
 __device__ __attribute__((always_inline)) void stream_pipeline(uint4* __restrict__ sb, const uint4* __restrict__ A,
                                                                const uint16_t* __restrict__ meta16, const uint4* __restrict__ Xf,
                                                                uint16_t* __restrict__ Y, float* __restrict__ partial, long long M,
-                                                               long long N, long long Mp, long long Np, long long Kp, long long span) {
+                                                               long long N, long long Mp, long long Np, long long Kp, long long span,
+                                                               const uint4* lut) {
   static_assert(NB % 2 == 0, "the parity of a step is that of its ring slot");
   using State = StreamState<SPARSE, MT, RT, NW>;
   constexpr int BUF = MT * 128;  // units per ring buffer: [MT token tiles][2 half steps][64 lanes]
@@ -1586,6 +1598,7 @@ __device__ __attribute__((always_inline)) void stream_pipeline(uint4* __restrict
   const int tid = threadIdx.x;
   st.lane = (unsigned)(tid & 63);
   st.wave = (unsigned)wave_uniform(tid >> 6);
+  st.lut = lut;
   const long long nrt = Np / 16, ntt = Mp / 16, nks = Kp / 64;
   const long long nrb = (nrt + NW * RT - 1) / (NW * RT);
   const long long s_begin = (long long)blockIdx.x * span;
@@ -1672,7 +1685,12 @@ __global__ void __launch_bounds__(NW * 64) k_mm_stream(const uint4* __restrict__
                                                         float* __restrict__ partial, long long M, long long N, long long Mp,
                                                         long long Np, long long Kp, long long span) {
   extern __shared__ uint4 s_stream[];  // NB ring buffers of MT * 128 units
-  stream_pipeline<DT, SPARSE, MT, RT, NW, NB>(s_stream, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span);
+  __shared__ uint4 s_lut[SPARSE == 2 ? LUT48_CODES : 1];
+  if (SPARSE == 2) {
+    fill_expand_lut<1>(s_lut, (int)threadIdx.x);
+    __syncthreads();
+  }
+  stream_pipeline<DT, SPARSE, MT, RT, NW, NB>(s_stream, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span, s_lut);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1769,6 +1787,7 @@ bool esp_variant_applicable(int v, long long M, long long N, long long K, int sp
   if (v < 0 || v >= kNumVariants) return false;
   const Variant& var = kVariants[v];
   if (var.four8 && (sparse != 2 || M < 64)) return false;
+  if (sparse == 2 && var.kind == KIND_STREAM) return M <= 128 && var.tt == 4;  // the stream kernels with a ring of four slots
   if (sparse == 2 && !var.four8) {
     // 4:8: otherwise decode kernels only; longer inputs go through them 64 tokens at a time
     if (var.kind != KIND_KSPLIT || (var.quads && M > 16)) return false;
@@ -1802,7 +1821,7 @@ int esp_default_variant(long long M, long long N, long long K, int sparse) {
     if (((N + 127) / 128) * ((M + 255) / 256) >= 128 || esp_split_capacity(M) == 1) return variant_index("tile48_w8_r128_t256");
     return variant_index("tile48_w8_t128_splitk");
   }
-  if (M <= 32 || sparse == 2) {
+  if (M <= 32) {
     const long long nrt = esp_round_up(N, 16) / 16;
     return nrt <= 320 ? 4 : 5;  // ksplit_w16_r1 / ksplit_w16_r2
   }
@@ -2088,11 +2107,13 @@ static int launch_stream(esparse_ctx* ctx, const Variant& v, hipStream_t st, con
       : (mt == 4) ? launch_stream_kernel<DT, SPARSE, 4, RTv, NWv, NBv>(ctx->device, grid, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span) \
                   : launch_stream_kernel<DT, SPARSE, 8, RTv, NWv, NBv>(ctx->device, grid, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp, span)
   ESP_STREAM(1, 8, 4);
-  ESP_STREAM(1, 8, 8);
   ESP_STREAM(2, 8, 4);
-  ESP_STREAM(2, 8, 6);
   ESP_STREAM(1, 9, 4);
   ESP_STREAM(1, 11, 4);
+  if constexpr (SPARSE != 2) {  // 4:8: the rings of four slots only
+    ESP_STREAM(1, 8, 8);
+    ESP_STREAM(2, 8, 6);
+  }
 #undef ESP_STREAM
   ESP_HIP(ctx, e);
   if (span % nks != 0) {  // some row block is cut
@@ -2246,11 +2267,15 @@ int esp_matmul_device(esparse_ctx* ctx, int sparse, const void* X, long long M, 
 
   if (v.kind == KIND_STREAM) {
     const uint16_t* meta16 = reinterpret_cast<const uint16_t*>(meta_bytes);
+    if (sparse == 2)
+      return dtype == ESPARSE_F16 ? launch_stream<ESPARSE_F16, 2>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp)
+                                  : launch_stream<ESPARSE_BF16, 2>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp);
     if (dtype == ESPARSE_F16)
       return sparse ? launch_stream<ESPARSE_F16, 1>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp)
                     : launch_stream<ESPARSE_F16, 0>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp);
     return sparse ? launch_stream<ESPARSE_BF16, 1>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp)
                   : launch_stream<ESPARSE_BF16, 0>(ctx, v, st, A, meta16, Xf, Y, partial, M, N, Mp, Np, Kp);
+
   }
 
   // ---- wave-tile kinds

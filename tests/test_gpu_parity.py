@@ -612,7 +612,7 @@ def test_spmm_4_8(esp, ctx, M, N, K, dtype):
         try:
             Y = ctx.spmm(X.cuda(), comp, th, variant=v)
         except esp.EsparseError as e:
-            assert e.code == -2 and v >= 0          # neither a decode nor a 4:8 tile kernel, or not for this M
+            assert e.code == -2 and v >= 0          # not a decode, four-slot stream or 4:8 tile kernel, or not for this M
             continue
         torch.cuda.synchronize()
         err = orc.rowwise_rel_error(_np(Y), Yref)
@@ -667,8 +667,8 @@ def test_spmm_group_equals_single_products(esp, ctx, M, n, m):
         for i in range(3):
             assert (_bits(Yd[i]) == _bits(ctx.dense_gemm(Xs[i], packed[i], N))).all()
             assert orc.rowwise_rel_error(_np(Yd[i]), orc.dense_ref(_np(Xs[i]), _np(Ws[i]))).max() <= 2e-3
-    if M <= 32 or m == 8:
-        # the two halves as separate calls (they exist where a decode kernel is the default: M <= 32, or 4:8)
+    if M <= 32:
+        # the two halves as separate calls (they exist where a decode kernel is the default: M <= 32)
         ws = ctx.workspace(4 * esp.spmm_workspace(M, N, K))
         ctx.stage_activations_group(Xs, perms, comps[0], ws)
         outs = [torch.empty_like(y) for y in Ys]
