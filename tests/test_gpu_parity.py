@@ -590,7 +590,7 @@ def test_output_error_report_for_the_ablation_settings(esp, ctx):
 # ---------------------------------------------------------------- 4:8 product (bitmaps expanded in registers)
 @pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
 @pytest.mark.parametrize("M,N,K", [(1, 72, 576), (8, 40, 256), (33, 72, 576), (40, 72, 1024), (64, 144, 2304), (150, 48, 512),
-                                   (300, 520, 768)])
+                                   (300, 520, 768), (200, 100, 264)])
 def test_spmm_4_8(esp, ctx, M, N, K, dtype):
     rng = np.random.default_rng(M * N + K)
     scales = wl.channel_scales("lognormal", K, wl.stream_id("x48", M))
