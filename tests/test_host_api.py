@@ -100,6 +100,21 @@ def test_argument_errors_need_no_gpu():
     assert lib.esparse_matrix_rate(ctx._h, 1, 7, 1, 0, C.byref(rate)) == -2              # no such dtype
     assert lib.esparse_matrix_rate(ctx._h, 1, 0, 1, 3, C.byref(rate)) == -1              # mix is 0, 1 or 2
     assert lib.esparse_matrix_rate(ctx._h, 0, 0, 1, 2, C.byref(rate)) == -2              # the stage mixes are 2:4 only
+    # which kernel variants serve which weights is decided on the host, before any GPU call (the pointers are never used)
+    vs = {esp.variant_name(v): v for v in range(esp.num_variants())}
+    fake = C.c_void_p(1 << 20)
+
+    def spmm_code(M, n, m, name):
+        return lib.esparse_spmm(ctx._h, fake, M, fake, None, 512, 512, 0, n, m, fake, fake, 1 << 30, vs[name])
+
+    assert spmm_code(256, 4, 8, "tile32_w8_t256") == -2       # the 32x32x32 kernel multiplies 2:4 weights only
+    assert spmm_code(256, 2, 4, "tile48_w8_t128") == -2       # the tile48 kernels 4:8 weights only
+    assert spmm_code(32, 4, 8, "tile48_w8_t128") == -2        # ... and 64 tokens or more
+    assert spmm_code(64, 4, 8, "stream_w8_r1_d7") == -2       # 4:8 through the stream kernels: rings of four slots only
+    assert spmm_code(256, 4, 8, "stream_w8_r1_d3") == -2      # ... and at most 128 tokens
+    assert spmm_code(32, 4, 8, "ksplit_w8_r1_q") == -2        # one metadata load per four steps: at most 16 tokens
+    assert spmm_code(256, 2, 4, "tile_w8_t256_h") == -2       # dense weights only
+    assert b"variant" in lib.esparse_last_error(ctx._h)
     assert lib.esparse_read_rate(ctx._h, 1 << 20, None) == -1                             # null result pointer
     assert lib.esparse_read_rate(ctx._h, 16, C.byref(rate)) == -1                         # fewer than 4 KiB
 
