@@ -851,17 +851,16 @@ __device__ __forceinline__ void tile_load_a(TileState<SPARSE, TR, TC, NWC>& st, 
     for (int i = 0; i < TR; i++) raw[i] = sa[(st.wr * TR + i) * 64 + st.lane];
 #pragma unroll
     for (int i = 0; i < TR; i++) expand_4_8<16>(raw[i], codes[i], st.lut, st.lane & 15u, r.a[2 * i], r.a[2 * i + 1]);
-    return;
-  }
+  } else {
 #pragma unroll
-  for (int i = 0; i < TR; i++) {
-    if constexpr (SPARSE == 2) {
-    } else if constexpr (SPARSE != 0) {
-      r.a[i] = sa[(st.wr * TR + i) * 64 + st.lane];
-      if constexpr (SPARSE == 1) r.m[i] = sm[(st.wr * TR + i) * 64 + st.lane];
-    } else {
-      r.a[2 * i] = sa[(st.wr * TR + i) * 128 + st.lane];
-      r.a[2 * i + 1] = sa[(st.wr * TR + i) * 128 + 64 + st.lane];
+    for (int i = 0; i < TR; i++) {
+      if constexpr (SPARSE != 0) {
+        r.a[i] = sa[(st.wr * TR + i) * 64 + st.lane];
+        if constexpr (SPARSE == 1) r.m[i] = sm[(st.wr * TR + i) * 64 + st.lane];
+      } else {
+        r.a[2 * i] = sa[(st.wr * TR + i) * 128 + st.lane];
+        r.a[2 * i + 1] = sa[(st.wr * TR + i) * 128 + 64 + st.lane];
+      }
     }
   }
 }
