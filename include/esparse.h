@@ -159,9 +159,11 @@ int esparse_spmm(esparse_ctx* ctx, const void* X, long long M, const void* nativ
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same product, same kernels and bitwise the same
  * result as esparse_spmm with the same variant; the scratch (staged activations, partial tiles of the variants
  * that split K) is a fixed array of ESPARSE_STATIC_SCRATCH_BYTES in the library's device image, one per GPU,
- * held until the process ends.  The call allocates and frees nothing on the device.  A shape whose variant needs
- * more scratch than that is rejected with ESPARSE_EWORKSPACE and nothing is launched (the message gives both
- * sizes); the first call on a GPU looks the array's device address up (that GPU current).  Every call on one GPU
+ * held until the process ends.  The call allocates and frees nothing on the device.  variant -1: where the tuned
+ * (or built-in) choice keeps fp32 partial tiles that do not fit the array, the built-in choice among the kernels
+ * without partial tiles runs instead (a decode kernel up to 64 tokens, tile32_w8_t128 up to 128, tile32_w8_t256
+ * beyond; 4:8: tile48_w8_r128_t256).  A shape whose variant still needs more scratch than the array holds is
+ * rejected with ESPARSE_EWORKSPACE and nothing is launched (the message gives both sizes); the first call on a GPU looks the array's device address up (that GPU current).  Every call on one GPU
  * uses the same array, on whatever stream its context has: calls that overlap on one GPU race - order them on
  * one stream or with events.  No part of the array needs clearing between calls (each kernel reads only what an
  * earlier kernel of the same call wrote).  Other errors as esparse_spmm.  Does not synchronise. */

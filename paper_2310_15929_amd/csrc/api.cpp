@@ -309,8 +309,14 @@ int esparse_spmm_static(esparse_ctx* ctx, const void* X, long long M, const void
   ESP_REQUIRE(ctx, K % m == 0, ESPARSE_EINVAL, "K = %lld is not a multiple of %d", K, m);
   ESP_REQUIRE(ctx, esp_aligned16(perm), ESPARSE_EINVAL, "perm is not 16-byte aligned");
   if (M == 0) return ESPARSE_OK;
-  const int v = pick_variant(ctx, mode, dtype, M, N, K, variant);
-  const size_t need = esp_variant_workspace_bytes(v, M, N, K);
+  int v = pick_variant(ctx, mode, dtype, M, N, K, variant);
+  size_t need = esp_variant_workspace_bytes(v, M, N, K);
+  if (variant < 0 && need > (size_t)ESPARSE_STATIC_SCRATCH_BYTES) {
+    // the tuned or built-in choice keeps partial tiles that do not fit the array: the built-in choice among the
+    // kernels without partial tiles instead
+    v = esp_default_variant_without_partials(M, N, K, mode);
+    need = esp_variant_workspace_bytes(v, M, N, K);
+  }
   ESP_REQUIRE(ctx, need <= (size_t)ESPARSE_STATIC_SCRATCH_BYTES, ESPARSE_EWORKSPACE,
               "M=%lld N=%lld K=%lld with variant %s needs %zu bytes of scratch, the static scratch holds %zu: use esparse_spmm "
               "with a workspace of the caller's", M, N, K, esp_variant_name(v), need, (size_t)ESPARSE_STATIC_SCRATCH_BYTES);

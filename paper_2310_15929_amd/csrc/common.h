@@ -110,6 +110,7 @@ int esp_num_variants();
 const char* esp_variant_name(int v);
 bool esp_variant_applicable(int v, long long M, long long N, long long K, int sparse);
 int esp_default_variant(long long M, long long N, long long K, int sparse);
+int esp_default_variant_without_partials(long long M, long long N, long long K, int sparse);
 size_t esp_workspace_bytes(long long M, long long N, long long K);
 size_t esp_variant_workspace_bytes(int variant, long long M, long long N, long long K);
 int esp_static_scratch(esparse_ctx* ctx, void** out);  // device address of this GPU's static scratch (ctx->device current)

@@ -1856,6 +1856,16 @@ int esp_default_variant(long long M, long long N, long long K, int sparse) {
   return 14;                                       // tile_w8_r128_t128
 }
 
+// the built-in choice among the variants that keep no fp32 partial tiles in the workspace (for callers whose scratch
+// is too small for them): a decode kernel up to 64 tokens, the tile kernels beyond
+int esp_default_variant_without_partials(long long M, long long N, long long K, int sparse) {
+  (void)K;
+  if (M <= 64) return esp_round_up(N, 16) / 16 <= 320 ? 4 : 5;  // ksplit_w16_r1 / ksplit_w16_r2
+  if (sparse == 2) return variant_index("tile48_w8_r128_t256");
+  if (sparse == 1) return variant_index(M <= 128 ? "tile32_w8_t128" : "tile32_w8_t256");
+  return variant_index(M <= 128 ? "tile_w8_t128_h" : "tile_w8_t256_h");
+}
+
 // tokens of the compact copy of the staged activations (0: none), written when there are at most 16 tokens
 static int compact_tokens(long long M) {
   if (M > 16) return 0;

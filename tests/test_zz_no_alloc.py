@@ -61,6 +61,17 @@ def test_static_scratch_product_equals_workspace_product(capfd):
             ctx.spmm_static(X, comp, th, variant=v, out=Y1)
             torch.cuda.synchronize()
             assert (_bits(Y0) == _bits(Y1)).all(), esp.variant_name(v)
+    # a shape whose built-in choice (a stream kernel) keeps more partial tiles than the array holds: the call takes the
+    # built-in choice among the kernels without partial tiles instead
+    M, N, K = 100, 9600, 256
+    vs = {esp.variant_name(v): v for v in range(esp.num_variants())}
+    assert esp.spmm_workspace(M, N, K) > (64 << 20) > esp.spmm_workspace(M, N, K, vs["tile32_w8_t128"])
+    X, comp, th, Yref = _case(esp, ctx, M, N, K, 6)
+    Y1 = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+    ctx.spmm_static(X, comp, th, out=Y1)
+    torch.cuda.synchronize()
+    assert orc.rowwise_rel_error(Y1.float().cpu().numpy(), Yref).max() <= 2e-3
+    assert (_bits(ctx.spmm(X, comp, th, variant=vs["tile32_w8_t128"])) == _bits(Y1)).all()
     # beyond the fixed size: a clear error, nothing launched, the output untouched
     M, N, K = 4096, 256, 16384          # 128 MiB of staged activations
     Y = torch.zeros((M, N), dtype=torch.float16, device="cuda")
