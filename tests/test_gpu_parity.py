@@ -621,6 +621,35 @@ def test_spmm_4_8(esp, ctx, M, N, K, dtype):
     assert ran >= 3
 
 
+def test_products_on_seeded_random_shapes(esp, ctx):
+    """Shapes drawn from a seeded generator (ragged tails in every dimension, token counts on both sides of every
+    kernel family's boundary), both weight formats and the dense product, each through the kernel the library
+    chooses by itself, against the oracle."""
+    rng = np.random.default_rng(20231015)
+    boundaries = [1, 2, 3, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 257, 300]
+    for case in range(18):
+        M = int(boundaries[case])
+        N = int(rng.integers(1, 700))
+        K = int(rng.integers(1, 200)) * 8
+        dtype = torch.float16 if case % 3 else torch.bfloat16
+        W = _rand((N, K), dtype, 300 + case, scale=K ** -0.5)
+        X = _rand((M, K), dtype, 400 + case, col_scale=wl.channel_scales("lognormal", K, wl.stream_id("rs", case)))
+        s = np.abs(rng.standard_normal(K)) + 0.1
+        theta = rng.permutation(K)
+        th = torch.tensor(theta, dtype=torch.int32).cuda()
+        print(f"random shape {case}: M={M} N={N} K={K} {dtype}", flush=True)
+        for n, m in ((2, 4), (4, 8)):
+            mask = orc.nm_mask_vectorised(_np(W), s, theta, n, m)
+            comp = ctx.compress(W.cuda(), torch.tensor(mask).cuda(), th, n, m, canonical=False)
+            Y = ctx.spmm(X.cuda(), comp, th)
+            torch.cuda.synchronize()
+            err = orc.rowwise_rel_error(_np(Y), orc.spmm_ref(_np(X), _np(W), theta, mask))
+            assert err.max() <= TOL[dtype], (case, n, m, err.max())
+        Yd = ctx.dense_gemm(X.cuda(), ctx.dense_pack(W.cuda()), N)
+        torch.cuda.synchronize()
+        assert orc.rowwise_rel_error(_np(Yd), orc.dense_ref(_np(X), _np(W))).max() <= TOL[dtype], case
+
+
 def test_spmm_4_8_one_hot_reads_back_weights(esp, ctx):
     N, K = 32, 256
     rng = np.random.default_rng(48)
